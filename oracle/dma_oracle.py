@@ -1,0 +1,342 @@
+"""Plain, slow, dense-masked fp64 reference of the Dynamic Mask Attention hot path.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).  Everything here is NumPy
+in float64, written from the paper's definitions, with no blocking or fusion
+beyond row-chunking of the dense score matrix to bound memory.
+
+What is computed (paper: Section 4 "Method", Eq. 3-10, Alg. 1-2, Listing 1):
+
+* content scores       z[h, j] = exp(A_h * softplus(w_h . v_{g(h), j}))      (Eq. 3)
+* kept set of row i    the min(k, #candidates) best candidate keys of row i
+                       under "larger z first, lower index first on ties";
+                       candidates = keys j <= i of the same document when
+                       causal, else all keys of the document           (Eq. 4, Listing 1)
+* attention            S_ij = scale * q_i . k_j + z_j on the kept set,
+                       P = softmax over the kept set, exactly 0 elsewhere,
+                       O = P V, LSE = log sum exp S                     (Eq. 5-6, Alg. 1)
+* gradients            dV, dS = P o (dP - D), dz = column sums of dS,
+                       dQ, dK                                          (Eq. 7-10, Alg. 2)
+
+Readings of the paper taken here (the paper is ambiguous on these points):
+the mask is *added* to the scaled scores (the case formula of Eq. 5, Alg. 1 and
+the listing agree; the words "element-wise multiplied" do not); the activation
+tau is softplus (Listing 1); the bias is delta itself, not its log; the
+sparsifier f acts element-wise; the top-w is taken per query row over that
+row's causal prefix (Listing 1); rows with fewer than k candidates keep all of
+them; Alg. 2's "rowsum(dS)" into dM is a sum over the query rows of a column
+(Eq. 9 summed over time steps); no gradient flows through the selection
+(Section 6, "Fully Differentiable Design").  Each q-head h uses its own vector
+w_h on the values of its kv-head g(h) = h // (H_q / H_kv).
+
+Layouts: Q, O, dO, dQ [T, H_q, d]; K, V, dK, dV [T, H_kv, d]; z, dz, LSE
+[H_q, T]; cu_seqlens [n_docs + 1] with cu[0] = 0, cu[-1] = T.
+
+Pins (tests/test_oracle_*.py): reduction to textbook causal softmax attention
+and to torch SDPA (k >= L, constant z), sliding-window / sink closed forms,
+k = 1, all-equal z (tie rule), row sums, exact zeros, finite differences for
+all four gradients, algebraic identities, scalar triple-loop brute force, and
+the gather-loop formulation of Listing 1.  No function here is unpinned.
+"""
+from __future__ import annotations
+
+import bisect
+import math
+
+import numpy as np
+
+__all__ = [
+    "softplus", "z_scores", "kept_mask_definition", "kept_mask_ranked",
+    "expiry_from_kept", "expiry_sequential", "topk_indices", "dma_forward",
+    "dma_backward", "dma_forward_gather_loop", "dma_scalar_bruteforce",
+    "n_active_pairs",
+]
+
+
+# --------------------------------------------------------------------------- scores
+def softplus(x):
+    """log(1 + exp(x)), evaluated without overflow (Listing 1 uses softplus for tau)."""
+    x = np.asarray(x, dtype=np.float64)
+    return np.maximum(x, 0.0) + np.log1p(np.exp(-np.abs(x)))
+
+
+def z_scores(V, W, A, H_q):
+    """Eq. 3: z[h, j] = exp(A_h * softplus(w_h . v_{g(h), j})).
+
+    V [T, H_kv, d], W [H_q, d], A [H_q]  ->  z [H_q, T] (float64).
+    """
+    V = np.asarray(V, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    T, H_kv, d = V.shape
+    G = H_q // H_kv
+    z = np.empty((H_q, T), dtype=np.float64)
+    for h in range(H_q):
+        x = V[:, h // G, :] @ W[h]
+        z[h] = np.exp(A[h] * softplus(x))
+    return z
+
+
+# --------------------------------------------------------------------------- kept sets
+def kept_mask_definition(z_doc, k, causal=True):
+    """Eq. 4 by its definition: for each row, stable-sort the candidates by
+    descending z and keep the first min(k, #candidates).
+
+    z_doc [n] (one document, one head) -> bool [n, n], entry (i, j) true iff
+    key j is kept by query row i.
+    """
+    z_doc = np.asarray(z_doc, dtype=np.float64)
+    n = z_doc.shape[0]
+    keep = np.zeros((n, n), dtype=bool)
+    for i in range(n):
+        ncand = i + 1 if causal else n
+        order = np.argsort(-z_doc[:ncand], kind="stable")  # ties: lower index first
+        keep[i, order[: min(k, ncand)]] = True
+    return keep
+
+
+def kept_mask_ranked(z_doc, k, causal=True):
+    """Same set as kept_mask_definition, computed densely: rank all keys once
+    (stable), then key j is kept by row i iff fewer than k candidates of row i
+    rank ahead of it."""
+    z_doc = np.asarray(z_doc, dtype=np.float64)
+    n = z_doc.shape[0]
+    order = np.argsort(-z_doc, kind="stable")
+    rank = np.empty(n, dtype=np.int64)
+    rank[order] = np.arange(n)
+    ahead = rank[None, :] < rank[:, None]          # ahead[j, j2]: j2 ranks ahead of j
+    if causal:
+        # cnt[i, j] = #{j2 <= i : j2 ahead of j}
+        cnt = np.cumsum(ahead.T, axis=0)           # cumsum over j2 (rows) -> [i, j]
+        cand = np.tril(np.ones((n, n), dtype=bool))
+        return cand & (cnt < k)
+    cnt = ahead.sum(axis=1)                        # [j]
+    return np.broadcast_to(cnt[None, :] < k, (n, n)).copy()
+
+
+def expiry_from_kept(keep):
+    """Encode a causal kept mask as one integer per key: e[j] = first row >= j
+    that does not keep key j (n if kept to the end, j if never kept).  Raises if
+    the rows keeping a key are not one contiguous interval starting at j."""
+    n = keep.shape[0]
+    e = np.empty(n, dtype=np.int64)
+    for j in range(n):
+        col = keep[j:, j]
+        dropped = np.flatnonzero(~col)
+        e[j] = j + (dropped[0] if dropped.size else n - j)
+        if col[e[j] - j:].any() or keep[:j, j].any():
+            raise AssertionError(f"key {j}: kept rows are not a contiguous interval [j, e)")
+    return e
+
+
+def expiry_sequential(z_doc, k):
+    """Causal expiry by walking the rows once with the kept set held as a
+    sorted list (an iteration, not the definition: pinned against
+    kept_mask_definition in the tests).  Row i: key i joins the candidates; if
+    more than k are then held, the worst one (lowest z, highest index among
+    equals) is dropped and its expiry is i."""
+    z_doc = np.asarray(z_doc, dtype=np.float64)
+    n = z_doc.shape[0]
+    e = np.full(n, n, dtype=np.int64)
+    held = []                                      # sorted ascending by (z, -index): held[0] is the worst
+    for i in range(n):
+        bisect.insort(held, (z_doc[i], -i))
+        if len(held) > k:
+            _, neg = held.pop(0)
+            e[-neg] = i
+    return e
+
+
+def topk_indices(z_doc, k, causal=True):
+    """Kept key indices of every row in ascending order, -1 padded: int32 [n, k]."""
+    keep = kept_mask_definition(z_doc, k, causal)
+    n = keep.shape[0]
+    out = np.full((n, k), -1, dtype=np.int32)
+    for i in range(n):
+        idx = np.flatnonzero(keep[i])
+        out[i, : idx.size] = idx
+    return out
+
+
+def n_active_pairs(n, k):
+    """Number of (row, key) pairs the causal mask keeps in a document of n rows."""
+    if k >= n:
+        return n * (n + 1) // 2
+    return k * n - k * (k - 1) // 2
+
+
+# --------------------------------------------------------------------------- attention
+def _doc_keep_provider(z_doc, k, causal, mask_method):
+    """Returns f(r0, r1) -> bool [r1 - r0, n] for one (document, head)."""
+    n = z_doc.shape[0]
+    if mask_method == "definition":
+        full = kept_mask_definition(z_doc, k, causal)
+        return lambda r0, r1: full[r0:r1]
+    if mask_method != "sequential":
+        raise ValueError(mask_method)
+    cols = np.arange(n)[None, :]
+    if causal:
+        e = expiry_sequential(z_doc, k)
+
+        def prov(r0, r1):
+            rows = np.arange(r0, r1)[:, None]
+            return (cols <= rows) & (rows < e[None, :])
+        return prov
+    order = np.argsort(-z_doc, kind="stable")
+    kept = np.zeros(n, dtype=bool)
+    kept[order[: min(k, n)]] = True
+    return lambda r0, r1: np.broadcast_to(kept[None, :], (r1 - r0, n))
+
+
+def _softmax_rows(S, keep):
+    """Masked softmax of a chunk of rows: returns (P, LSE); P is exactly 0 off the kept set."""
+    S = np.where(keep, S, -np.inf)
+    m = S.max(axis=1, keepdims=True)
+    Pu = np.exp(S - m)                             # exp(-inf) == 0.0 exactly
+    l = Pu.sum(axis=1, keepdims=True)
+    return Pu / l, (m + np.log(l))[:, 0]
+
+
+def _as64(x):
+    return np.asarray(x, dtype=np.float64)
+
+
+def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
+                mask_method="sequential", row_chunk=1024):
+    """Eq. 5-6 / Alg. 1 result: O [T, H_q, d], LSE [H_q, T].
+
+    heads: iterable of q-head indices to compute (others are left as NaN).
+    mask_method: "definition" (per-row stable sort, O(n^2 log n)) or
+    "sequential" (interval encoding from expiry_sequential; causal) -- the two
+    are asserted equal in the tests.
+    """
+    Q, K, V, z = _as64(Q), _as64(K), _as64(V), _as64(z)
+    T, H_q, d = Q.shape
+    H_kv = K.shape[1]
+    G = H_q // H_kv
+    scale = 1.0 / math.sqrt(d) if scale is None else float(scale)
+    heads = range(H_q) if heads is None else heads
+    O = np.full((T, H_q, d), np.nan)
+    LSE = np.full((H_q, T), np.nan)
+    cu = [int(c) for c in cu_seqlens]
+    for h in heads:
+        g = h // G
+        for a, b in zip(cu[:-1], cu[1:]):
+            n = b - a
+            if n == 0:
+                continue
+            q, kk, v, zb = Q[a:b, h], K[a:b, g], V[a:b, g], z[h, a:b]
+            prov = _doc_keep_provider(zb, k, causal, mask_method)
+            for r0 in range(0, n, row_chunk):
+                r1 = min(n, r0 + row_chunk)
+                S = scale * (q[r0:r1] @ kk.T) + zb[None, :]
+                P, lse = _softmax_rows(S, prov(r0, r1))
+                O[a + r0:a + r1, h] = P @ v
+                LSE[h, a + r0:a + r1] = lse
+    return O, LSE
+
+
+def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=None,
+                 mask_method="sequential", row_chunk=1024):
+    """Eq. 7-10 / Alg. 2 result: dQ [T, H_q, d], dK, dV [T, H_kv, d], dz [H_q, T].
+
+    dK and dV are summed over the q-heads listed in `heads` that share a
+    kv-head (all heads by default).  dV is the attention-path gradient only
+    (the path V -> z is not part of this function).
+    """
+    Q, K, V, z, dO = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO)
+    T, H_q, d = Q.shape
+    H_kv = K.shape[1]
+    G = H_q // H_kv
+    scale = 1.0 / math.sqrt(d) if scale is None else float(scale)
+    heads = range(H_q) if heads is None else heads
+    dQ = np.full((T, H_q, d), np.nan)
+    dz = np.full((H_q, T), np.nan)
+    dK = np.zeros((T, H_kv, d))
+    dV = np.zeros((T, H_kv, d))
+    cu = [int(c) for c in cu_seqlens]
+    for h in heads:
+        g = h // G
+        for a, b in zip(cu[:-1], cu[1:]):
+            n = b - a
+            if n == 0:
+                continue
+            q, kk, v, zb, do = Q[a:b, h], K[a:b, g], V[a:b, g], z[h, a:b], dO[a:b, h]
+            prov = _doc_keep_provider(zb, k, causal, mask_method)
+            dzd = np.zeros(n)
+            for r0 in range(0, n, row_chunk):
+                r1 = min(n, r0 + row_chunk)
+                S = scale * (q[r0:r1] @ kk.T) + zb[None, :]
+                P, _ = _softmax_rows(S, prov(r0, r1))
+                o = P @ v
+                D = (do[r0:r1] * o).sum(axis=1, keepdims=True)      # Alg. 2: D_i
+                dP = do[r0:r1] @ v.T                                # Eq. 8: dp_j = v_j . do
+                dS = P * (dP - D)                                   # Eq. 8
+                dV[a:b, g] += P.T @ do[r0:r1]                       # Eq. 7
+                dQ[a + r0:a + r1, h] = scale * (dS @ kk)            # Eq. 10
+                dK[a:b, g] += scale * (dS.T @ q[r0:r1])             # Eq. 10
+                dzd += dS.sum(axis=0)                               # Eq. 9, summed over rows
+            dz[h, a:b] = dzd
+    return dQ, dK, dV, dz
+
+
+def dma_forward_gather_loop(Q, K, V, z, cu_seqlens, k, causal=True, scale=None):
+    """The second formulation (Listing 1's per-query loop): for every query
+    gather its kept keys, softmax over just those, weighted sum of the gathered
+    values.  Small inputs only."""
+    Q, K, V, z = _as64(Q), _as64(K), _as64(V), _as64(z)
+    T, H_q, d = Q.shape
+    G = H_q // K.shape[1]
+    scale = 1.0 / math.sqrt(d) if scale is None else float(scale)
+    O = np.zeros((T, H_q, d))
+    cu = [int(c) for c in cu_seqlens]
+    for h in range(H_q):
+        g = h // G
+        for a, b in zip(cu[:-1], cu[1:]):
+            idx_all = topk_indices(z[h, a:b], k, causal)
+            for i in range(b - a):
+                idx = idx_all[i][idx_all[i] >= 0] + a
+                s = (K[idx, g] * Q[a + i, h][None, :]).sum(axis=1) * scale + z[h, idx]
+                w = np.exp(s - s.max())
+                w /= w.sum()
+                O[a + i, h] = (w[:, None] * V[idx, g]).sum(axis=0)
+    return O
+
+
+def dma_scalar_bruteforce(Q, K, V, z, dO, k, scale):
+    """Root of trust for tiny inputs: one document, one head (H_q = H_kv = 1),
+    causal, pure-Python scalar loops.  Q, K, V, dO: [n][d] nested sequences,
+    z: [n].  Returns (O, LSE, dQ, dK, dV, dz) as nested lists."""
+    n, d = len(Q), len(Q[0])
+    O = [[0.0] * d for _ in range(n)]
+    LSE = [0.0] * n
+    dQ = [[0.0] * d for _ in range(n)]
+    dK = [[0.0] * d for _ in range(n)]
+    dV = [[0.0] * d for _ in range(n)]
+    dz = [0.0] * n
+    for i in range(n):
+        cand = list(range(i + 1))
+        cand.sort(key=lambda j: (-z[j], j))
+        kept = sorted(cand[:k])
+        s = {}
+        for j in kept:
+            acc = 0.0
+            for c in range(d):
+                acc += Q[i][c] * K[j][c]
+            s[j] = acc * scale + z[j]
+        m = max(s.values())
+        tot = sum(math.exp(s[j] - m) for j in kept)
+        LSE[i] = m + math.log(tot)
+        p = {j: math.exp(s[j] - m) / tot for j in kept}
+        for j in kept:
+            for c in range(d):
+                O[i][c] += p[j] * V[j][c]
+        dp = {j: sum(dO[i][c] * V[j][c] for c in range(d)) for j in kept}
+        dot = sum(p[j] * dp[j] for j in kept)
+        for j in kept:
+            ds = p[j] * (dp[j] - dot)
+            dz[j] += ds
+            for c in range(d):
+                dV[j][c] += p[j] * dO[i][c]
+                dQ[i][c] += ds * K[j][c] * scale
+                dK[j][c] += ds * Q[i][c] * scale
+    return O, LSE, dQ, dK, dV, dz

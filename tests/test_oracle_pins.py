@@ -1,0 +1,306 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+The paper prints no worked numerical example, so the oracle is pinned by:
+reduction to textbook causal softmax attention / torch SDPA, closed forms for
+special score sequences, invariants of Eq. 5, finite differences for Eq. 7-10,
+algebraic identities, a scalar triple-loop brute force and the gather-loop
+formulation of Listing 1.  Each test names the mistake it is there to catch.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+
+RNG = np.random.default_rng(7)
+
+
+def rand_case(n=48, H_q=4, H_kv=2, d=8, seed=0, ties=False):
+    r = np.random.default_rng(seed)
+    Q = r.standard_normal((n, H_q, d))
+    K = r.standard_normal((n, H_kv, d))
+    V = r.standard_normal((n, H_kv, d))
+    dO = r.standard_normal((n, H_q, d))
+    z = r.uniform(0.05, 1.0, size=(H_q, n))
+    if ties:
+        z = np.round(z * 4) / 4            # heavy ties: 5 distinct values
+    return Q, K, V, dO, z
+
+
+def textbook_causal(Q, K, V, scale, bias=None, band=None):
+    """Independent five-line reference: dense causal softmax attention, one head."""
+    n = Q.shape[0]
+    S = scale * Q @ K.T
+    if bias is not None:
+        S = S + bias[None, :]
+    i, j = np.arange(n)[:, None], np.arange(n)[None, :]
+    ok = j <= i
+    if band is not None:
+        ok &= (i - j) < band
+    S = np.where(ok, S, -np.inf)
+    P = np.exp(S - S.max(1, keepdims=True))
+    P /= P.sum(1, keepdims=True)
+    return P @ V, P
+
+
+# ----------------------------------------------------------------------------- scores (Eq. 3)
+def test_softplus_matches_library_and_limits():
+    x = np.linspace(-40, 40, 161)
+    ref = torch.nn.functional.softplus(torch.tensor(x, dtype=torch.float64), threshold=1e9).numpy()
+    assert np.allclose(orc.softplus(x), ref, rtol=1e-14, atol=0)
+    assert orc.softplus(0.0) == pytest.approx(math.log(2.0), abs=1e-15)
+    assert orc.softplus(800.0) == 800.0          # no overflow
+    assert orc.softplus(-800.0) == 0.0 or orc.softplus(-800.0) < 1e-300
+
+
+def test_z_scores_closed_form_and_head_grouping():
+    # W = 0 => x = 0 => z = exp(A ln 2) = 2**A, for every key
+    V = RNG.standard_normal((10, 2, 4))
+    A = np.array([-1.0, -0.5, -2.0, -1.5])
+    z = orc.z_scores(V, np.zeros((4, 4)), A, 4)
+    assert np.allclose(z, (2.0 ** A)[:, None], rtol=1e-15)
+    # one-hot w_h picks one channel of the head's own kv-head (g = h // 2)
+    W = np.zeros((4, 4)); W[0, 1] = 1; W[1, 2] = 1; W[2, 0] = 1; W[3, 3] = 1
+    z = orc.z_scores(V, W, A, 4)
+    for h, (g, c) in enumerate([(0, 1), (0, 2), (1, 0), (1, 3)]):
+        x = V[:, g, c]
+        assert np.allclose(z[h], np.exp(A[h] * np.log1p(np.exp(x))), rtol=1e-13)
+
+
+# ----------------------------------------------------------------------------- kept sets (Eq. 4)
+@pytest.mark.parametrize("ties", [False, True])
+@pytest.mark.parametrize("n,k", [(1, 1), (7, 3), (64, 16), (200, 64), (50, 80)])
+def test_kept_mask_formulations_agree(n, k, ties):
+    r = np.random.default_rng(n * 100 + k)
+    z = r.uniform(0, 1, n)
+    if ties:
+        z = np.round(z * 3) / 3
+    ref = orc.kept_mask_definition(z, k)
+    assert (orc.kept_mask_ranked(z, k) == ref).all()
+    e = orc.expiry_from_kept(ref)                       # raises unless contiguous intervals [j, e)
+    assert (orc.expiry_sequential(z, k) == e).all()
+    i, j = np.arange(n)[:, None], np.arange(n)[None, :]
+    assert (((j <= i) & (i < e[None, :])) == ref).all()
+    # every row keeps exactly min(i + 1, k) keys, all of them causal
+    assert (ref.sum(1) == np.minimum(np.arange(n) + 1, k)).all()
+    assert not np.triu(ref, 1).any()
+    assert ref.sum() == orc.n_active_pairs(n, k)
+
+
+def test_kept_mask_noncausal():
+    z = np.array([0.3, 0.9, 0.3, 0.5, 0.9])
+    m = orc.kept_mask_definition(z, 3, causal=False)
+    assert (m == np.array([0, 1, 0, 1, 1], bool)[None, :]).all()     # 0.9, 0.9, 0.5
+    assert (orc.kept_mask_ranked(z, 3, causal=False) == m).all()
+    m2 = orc.kept_mask_definition(z, 4, causal=False)
+    assert (m2[0] == np.array([1, 1, 0, 1, 1], bool)).all()          # tie 0.3: lower index wins
+
+
+def test_tie_rule_lower_index_wins():
+    # all scores equal: the kept set of every row is keys 0..k-1
+    n, k = 20, 5
+    m = orc.kept_mask_definition(np.full(n, 0.25), k)
+    for i in range(n):
+        assert (np.flatnonzero(m[i]) == np.arange(min(i + 1, k))).all()
+    e = orc.expiry_sequential(np.full(n, 0.25), k)
+    assert (e[:k] == n).all() and (e[k:] == np.arange(k, n)).all()   # later keys never kept
+
+
+def test_increasing_and_decreasing_scores_closed_forms():
+    n, k = 30, 6
+    inc = np.linspace(0.1, 0.9, n)
+    m = orc.kept_mask_definition(inc, k)
+    i, j = np.arange(n)[:, None], np.arange(n)[None, :]
+    assert (m == ((j <= i) & (i - j < k))).all()                     # sliding window
+    dec = inc[::-1].copy()
+    m = orc.kept_mask_definition(dec, k)
+    assert (m == ((j <= i) & (j < k))).all()                         # attention sink
+
+
+def test_topk_indices_ascending_and_padded():
+    z = np.array([0.5, 0.1, 0.9, 0.7])
+    idx = orc.topk_indices(z, 2)
+    assert idx.tolist() == [[0, -1], [0, 1], [0, 2], [2, 3]]
+
+
+# ----------------------------------------------------------------------------- forward (Eq. 5-6)
+def test_reduces_to_causal_attention_textbook_and_sdpa():
+    """k >= L with constant z: softmax is shift-invariant, so the result is
+    plain causal attention.  Catches a wrong scale, a transposed operand, a
+    wrong head grouping or a bias applied multiplicatively."""
+    n, H_q, H_kv, d = 40, 4, 2, 8
+    Q, K, V, dO, _ = rand_case(n, H_q, H_kv, d, seed=3)
+    for const in (0.0, 0.37):
+        z = np.full((H_q, n), const)
+        O, LSE = orc.dma_forward(Q, K, V, z, [0, n], k=n + 5)
+        dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, [0, n], k=n + 5)
+        tq = torch.tensor(Q.transpose(1, 0, 2)[None], dtype=torch.float64, requires_grad=True)
+        tk = torch.tensor(K.transpose(1, 0, 2)[None], dtype=torch.float64, requires_grad=True)
+        tv = torch.tensor(V.transpose(1, 0, 2)[None], dtype=torch.float64, requires_grad=True)
+        tkr = tk.repeat_interleave(H_q // H_kv, dim=1)
+        tvr = tv.repeat_interleave(H_q // H_kv, dim=1)
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tkr, tvr, is_causal=True)
+        ref.backward(torch.tensor(dO.transpose(1, 0, 2)[None]))
+        assert np.allclose(O, ref.detach()[0].numpy().transpose(1, 0, 2), atol=1e-12)
+        assert np.allclose(dQ, tq.grad[0].numpy().transpose(1, 0, 2), atol=1e-12)
+        assert np.allclose(dK, tk.grad[0].numpy().transpose(1, 0, 2), atol=1e-12)
+        assert np.allclose(dV, tv.grad[0].numpy().transpose(1, 0, 2), atol=1e-12)
+        for h in range(H_q):
+            Oh, P = textbook_causal(Q[:, h], K[:, h // 2], V[:, h // 2], 1 / math.sqrt(d))
+            assert np.allclose(O[:, h], Oh, atol=1e-12)
+            S = np.where(np.tril(np.ones((n, n), bool)), Q[:, h] @ K[:, h // 2].T / math.sqrt(d), -np.inf)
+            lse = np.log(np.exp(S).sum(1)) + const
+            assert np.allclose(LSE[h], lse, atol=1e-12)
+
+
+def test_increasing_scores_equal_banded_attention_with_bias():
+    """z strictly increasing => sliding window of width k with z as additive
+    bias; compared with torch SDPA given an explicit additive mask."""
+    n, d, k = 36, 8, 7
+    Q, K, V, dO, _ = rand_case(n, 1, 1, d, seed=5)
+    z = np.linspace(0.05, 0.95, n)[None, :]
+    O, _ = orc.dma_forward(Q, K, V, z, [0, n], k=k)
+    i, j = np.arange(n)[:, None], np.arange(n)[None, :]
+    add = np.where((j <= i) & (i - j < k), z[0][None, :], -np.inf)
+    t = lambda a: torch.tensor(a.transpose(1, 0, 2)[None], dtype=torch.float64)
+    ref = torch.nn.functional.scaled_dot_product_attention(t(Q), t(K), t(V), attn_mask=torch.tensor(add)[None, None])
+    assert np.allclose(O, ref[0].numpy().transpose(1, 0, 2), atol=1e-12)
+    Oh, _ = textbook_causal(Q[:, 0], K[:, 0], V[:, 0], 1 / math.sqrt(d), bias=z[0], band=k)
+    assert np.allclose(O[:, 0], Oh, atol=1e-12)
+
+
+def test_k_equals_one_picks_first_prefix_maximum():
+    n, d = 25, 4
+    Q, K, V, dO, z = rand_case(n, 2, 1, d, seed=9, ties=True)
+    O, LSE = orc.dma_forward(Q, K, V, z, [0, n], k=1)
+    for h in range(2):
+        for i in range(n):
+            j = int(np.argmax(z[h, : i + 1]))               # first maximum
+            assert np.allclose(O[i, h], V[j, 0], atol=1e-14)
+            assert LSE[h, i] == pytest.approx(Q[i, h] @ K[j, 0] / math.sqrt(d) + z[h, j], abs=1e-12)
+
+
+def test_rows_sum_to_one_and_masked_weights_exactly_zero():
+    n, k = 64, 9
+    Q, K, V, dO, z = rand_case(n, 2, 2, 8, seed=11, ties=True)
+    for h in range(2):
+        keep = orc.kept_mask_definition(z[h], k)
+        S = Q[:, h] @ K[:, h].T / math.sqrt(8) + z[h][None, :]
+        from oracle.dma_oracle import _softmax_rows
+        P, lse = _softmax_rows(S, keep)
+        assert np.allclose(P.sum(1), 1.0, atol=1e-14)
+        assert (P[~keep] == 0.0).all()                        # exact zeros (Eq. 5, second case)
+        assert (P[keep] > 0.0).all()
+        assert ((P != 0).sum(1) == np.minimum(np.arange(n) + 1, k)).all()
+        O, LSE = orc.dma_forward(Q, K, V, z, [0, n], k=k, heads=[h])
+        assert np.allclose(O[:, h], P @ V[:, h], atol=1e-13)
+        assert np.allclose(LSE[h], lse, atol=1e-13)
+
+
+@pytest.mark.parametrize("ties", [False, True])
+def test_dense_masked_equals_gather_loop_and_both_mask_methods(ties):
+    n, k = 40, 6
+    Q, K, V, dO, z = rand_case(n, 4, 2, 8, seed=13, ties=ties)
+    cu = [0, 13, 13, 40]                                       # includes an empty document
+    O1, L1 = orc.dma_forward(Q, K, V, z, cu, k, mask_method="definition")
+    O2, L2 = orc.dma_forward(Q, K, V, z, cu, k, mask_method="sequential", row_chunk=7)
+    O3 = orc.dma_forward_gather_loop(Q, K, V, z, cu, k)
+    assert np.allclose(O1, O2, atol=1e-13) and np.allclose(L1, L2, atol=1e-13)
+    assert np.allclose(O1, O3, atol=1e-12)
+    g1 = orc.dma_backward(Q, K, V, z, dO, cu, k, mask_method="definition")
+    g2 = orc.dma_backward(Q, K, V, z, dO, cu, k, mask_method="sequential", row_chunk=5)
+    for a, b in zip(g1, g2):
+        assert np.allclose(a, b, atol=1e-12)
+
+
+def test_documents_are_independent():
+    n1, n2, k = 17, 23, 5
+    Q, K, V, dO, z = rand_case(n1 + n2, 2, 1, 8, seed=17)
+    O, LSE = orc.dma_forward(Q, K, V, z, [0, n1, n1 + n2], k)
+    Oa, La = orc.dma_forward(Q[:n1], K[:n1], V[:n1], z[:, :n1], [0, n1], k)
+    Ob, Lb = orc.dma_forward(Q[n1:], K[n1:], V[n1:], z[:, n1:], [0, n2], k)
+    assert np.allclose(O, np.concatenate([Oa, Ob]), atol=1e-14)
+    assert np.allclose(LSE, np.concatenate([La, Lb], axis=1), atol=1e-14)
+
+
+def test_vectorised_oracle_equals_scalar_bruteforce():
+    """Root of trust: pure-Python loops written from Eq. 6-10 (Eq. 8's sum form
+    for the softmax Jacobian rather than Alg. 2's D_i)."""
+    n, d, k = 24, 5, 4
+    Q, K, V, dO, z = rand_case(n, 1, 1, d, seed=19, ties=True)
+    scale = 0.31
+    ref = orc.dma_scalar_bruteforce(Q[:, 0].tolist(), K[:, 0].tolist(), V[:, 0].tolist(), z[0].tolist(),
+                                    dO[:, 0].tolist(), k, scale)
+    O, LSE = orc.dma_forward(Q, K, V, z, [0, n], k, scale=scale)
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, [0, n], k, scale=scale)
+    for got, want in zip((O[:, 0], LSE[0], dQ[:, 0], dK[:, 0], dV[:, 0], dz[0]), ref):
+        assert np.allclose(got, np.array(want), atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- backward (Eq. 7-10)
+def _loss(Q, K, V, z, dO, cu, k, scale):
+    O, _ = orc.dma_forward(Q, K, V, z, cu, k, scale=scale, mask_method="definition")
+    return float((O * dO).sum())
+
+
+def test_gradients_match_finite_differences():
+    """Central differences of sum(O o dO) w.r.t. Q, K, V and z.  Pins the
+    column-sum reading of the mask gradient, the scale factors, the GQA sum
+    over q-heads and the sign of the softmax Jacobian.  z is perturbed by much
+    less than its smallest gap, so the kept sets do not change (no gradient
+    flows through the selection)."""
+    n, H_q, H_kv, d, k = 12, 4, 2, 6, 4
+    r = np.random.default_rng(23)
+    Q, K, V, dO = (r.standard_normal(s) for s in [(n, H_q, d), (n, H_kv, d), (n, H_kv, d), (n, H_q, d)])
+    z = np.stack([r.permutation(n) for _ in range(H_q)]) * 0.05 + 0.1      # gaps of 0.05
+    cu, scale, eps = [0, 5, n], 0.4, 1e-5
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, cu, k, scale=scale, mask_method="definition")
+    args = dict(Q=Q, K=K, V=V, z=z)
+    for name, grad in (("Q", dQ), ("K", dK), ("V", dV), ("z", dz)):
+        base = args[name]
+        num = np.zeros_like(base)
+        it = np.nditer(base, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            hi = {**args, name: base.copy()}; hi[name][idx] += eps
+            lo = {**args, name: base.copy()}; lo[name][idx] -= eps
+            num[idx] = (_loss(dO=dO, cu=cu, k=k, scale=scale, **hi) -
+                        _loss(dO=dO, cu=cu, k=k, scale=scale, **lo)) / (2 * eps)
+        assert np.allclose(grad, num, atol=2e-8), name
+
+
+def test_gradient_identities():
+    n, H_q, H_kv, d, k = 50, 4, 2, 8, 7
+    Q, K, V, dO, z = rand_case(n, H_q, H_kv, d, seed=29)
+    cu = [0, 20, n]
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, cu, k)
+    # rows of the softmax Jacobian sum to zero => sum_j dz = 0 per (document, head)
+    for a, b in zip(cu[:-1], cu[1:]):
+        assert np.allclose(dz[:, a:b].sum(1), 0.0, atol=1e-12)
+    # scores are bilinear in (q, k): sum_i q_i.dQ_i over a kv-group == sum_j k_j.dK_j
+    for g in range(H_kv):
+        lhs = sum((Q[:, h] * dQ[:, h]).sum() for h in (2 * g, 2 * g + 1))
+        assert lhs == pytest.approx((K[:, g] * dK[:, g]).sum(), abs=1e-10)
+    # adding a constant to z leaves O unchanged and shifts LSE by that constant
+    O0, L0 = orc.dma_forward(Q, K, V, z, cu, k)
+    O1, L1 = orc.dma_forward(Q, K, V, z + 0.7, cu, k)
+    assert np.allclose(O0, O1, atol=1e-13) and np.allclose(L1 - L0, 0.7, atol=1e-12)
+    # keys that are never kept receive exactly zero gradient
+    for h in range(H_q):
+        for a, b in zip(cu[:-1], cu[1:]):
+            e = orc.expiry_sequential(z[h, a:b], k)
+            never = np.flatnonzero(e == np.arange(b - a)) + a
+            assert (dz[h, never] == 0.0).all()
+
+
+def test_heads_subset_matches_full():
+    n = 30
+    Q, K, V, dO, z = rand_case(n, 4, 2, 8, seed=31)
+    full = orc.dma_backward(Q, K, V, z, dO, [0, n], 5)
+    sub = orc.dma_backward(Q, K, V, z, dO, [0, n], 5, heads=[2, 3])     # one whole kv-group
+    assert np.allclose(sub[0][:, 2:], full[0][:, 2:], atol=1e-14)
+    assert np.allclose(sub[1][:, 1], full[1][:, 1], atol=1e-14)
+    assert np.allclose(sub[2][:, 1], full[2][:, 1], atol=1e-14)
+    assert (sub[1][:, 0] == 0).all()
