@@ -1,0 +1,117 @@
+/*
+ * dma.h -- C ABI of the MI355X (gfx950) Dynamic Mask Attention hot path.
+ *
+ * The operations are those of arxiv 2508.02124, Section 4 ("Method"):
+ *   dma_mask_gen : content scores  z = exp(A * softplus(v . w))            (Eq. 3)
+ *                  and the per-row top-k + causal kept sets                (Eq. 4, Listing 1)
+ *   dma_fwd      : O = softmax(Q K^T * scale + z, over the kept set) V     (Eq. 5-6, Alg. 1)
+ *   dma_bwd      : dQ, dK, dV and the gradient into z                      (Eq. 7-10, Alg. 2)
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers, 16-byte aligned, densely packed,
+ *     token-major, last dimension contiguous:
+ *         Q, O, dO, dQ : [T, H_q , d]      K, V, dK, dV : [T, H_kv, d]
+ *         z, dz, LSE   : [H_q, T] float    expiry       : [H_q, T] int32
+ *         W : [H_q, d] float               A            : [H_q] float
+ *         cu_seqlens   : [n_docs + 1] int32, cu[0] = 0, cu[n_docs] = T
+ *     Q/K/V/O/dO/dQ/dK/dV are bf16 (dtype DMA_BF16) or float (DMA_F32, a slow
+ *     debug path).  A fixed batch of B sequences of length L is T = B*L with
+ *     cu_seqlens = {0, L, 2L, ...}.
+ *   - q-head h reads kv-head h / (H_q / H_kv) (contiguous grouping).
+ *   - The `dma_shape` argument is a HOST pointer, read during the call.
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and keeps no pointer after the call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns without synchronising.
+ *   - Return value: DMA_OK (0) or a negative dma_status.  All argument checks
+ *     happen before the first launch, so a failing call enqueues nothing.
+ *   - Outputs are fully overwritten; the caller need not clear them.
+ */
+#ifndef DMA_H_
+#define DMA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DMA_OK = 0,
+  DMA_EINVAL = -1,       /* null pointer, misaligned pointer, T<=0, k<=0, n_docs<=0, H_q % H_kv != 0 */
+  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, causal == 0 */
+  DMA_EWORKSPACE = -3,   /* ws_bytes smaller than dma_workspace_bytes() */
+  DMA_EHIP = -4          /* a launch failed (hipGetLastError) */
+} dma_status;
+
+typedef enum { DMA_BF16 = 0, DMA_F32 = 1 } dma_dtype;
+
+typedef struct {
+  int32_t T;            /* total packed tokens                                        */
+  int32_t n_docs;       /* number of documents (sequences) packed into T              */
+  int32_t max_seqlen;   /* upper bound on the longest document (0 => T)               */
+  int32_t H_q;          /* query heads                                                */
+  int32_t H_kv;         /* key/value heads, divides H_q                               */
+  int32_t d;            /* head dimension: 64 or 128                                  */
+  int32_t k;            /* keep-window (the paper's w): kept keys per query row;
+                           k larger than a document keeps all of its causal keys      */
+  int32_t causal;       /* 1: candidates of row i are the keys j <= i of its document */
+  int32_t dtype;        /* dma_dtype of Q/K/V/O and their gradients                   */
+  float softmax_scale;  /* 0 => d^-1/2                                                */
+} dma_shape;
+
+/* Size in bytes of the opaque mask plan written by dma_mask_gen (slot table,
+ * per-block key lists and scratch of the selection), and of the scratch
+ * workspace dma_fwd / dma_bwd need.  0 if the shape is invalid. */
+size_t dma_mask_bytes(const dma_shape* shape);
+size_t dma_workspace_bytes(const dma_shape* shape);
+
+/*
+ * Mask generation (Eq. 3, Eq. 4, Listing 1's mask block).
+ *   V          in   [T, H_kv, d]
+ *   W, A       in   per-q-head projection vector and gate.  W == NULL means the
+ *                   caller supplies z (A is then ignored); z must be finite.
+ *   z          out if W != NULL, else in.  z[h, j] = exp(A_h * softplus(w_h . v_{g(h), j}))
+ *   expiry     out  e[h, j] (global row index) = first row >= j of j's document
+ *                   that does NOT keep key j; e == j: never kept; e == end of the
+ *                   document: kept to the end.  Row i keeps key j  <=>  j <= i < e[h, j].
+ *                   The kept set of a row is its min(k, i - doc_start + 1) best causal
+ *                   keys by (z descending, index ascending).
+ *   topk_idx   out, nullable: [H_q, T, k] int32, the kept keys of each row as global
+ *                   indices in ascending order, padded with -1 (debug; O(T k) memory).
+ *   mask       out  dma_mask_bytes(shape) bytes; consumed by dma_fwd / dma_bwd.
+ */
+int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
+                 const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,
+                 void* mask, void* stream);
+
+/*
+ * Forward (Eq. 5-6; online softmax as in Alg. 1, query-stationary).
+ *   O   out [T, H_q, d]     LSE out [H_q, T], natural-log sum-exp of the kept scores.
+ *   ws  scratch of at least dma_workspace_bytes(shape) (may be NULL if that is 0).
+ */
+int dma_fwd(const dma_shape* shape, const void* Q, const void* K, const void* V, const float* z,
+            const int32_t* expiry, const void* mask, const int32_t* cu_seqlens,
+            void* O, float* LSE, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward (Eq. 7-10; Alg. 2 with D_i = rowsum(dO o O)).
+ *   dQ out [T, H_q, d]; dK, dV out [T, H_kv, d], summed over the q-heads of a group;
+ *   dz out [H_q, T] = sum over query rows of dS (exactly 0 for keys never kept).
+ *   dV is the attention-path gradient only (not the path through z).
+ *   dK, dV and dz are accumulated with floating-point atomics: results can differ
+ *   in the last bits between runs.
+ */
+int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+            const void* dO, const float* LSE, const float* z, const int32_t* expiry,
+            const void* mask, const int32_t* cu_seqlens,
+            void* dQ, void* dK, void* dV, float* dz, void* ws, size_t ws_bytes, void* stream);
+
+const char* dma_strerror(int status);
+int dma_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMA_H_ */

@@ -1,0 +1,116 @@
+// Host side of the C ABI: argument validation, layout computation, dispatch.  No allocation, no
+// synchronisation, no retained state.
+#include "common.h"
+
+using namespace dma;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(const dma_shape* s) {
+  if (!s) return DMA_EINVAL;
+  if (s->T <= 0 || s->n_docs <= 0 || s->k <= 0 || s->H_q <= 0 || s->H_kv <= 0) return DMA_EINVAL;
+  if (s->H_q % s->H_kv != 0) return DMA_EINVAL;
+  if (s->n_docs > s->T) return DMA_EINVAL;
+  if (s->softmax_scale < 0.f || s->softmax_scale != s->softmax_scale) return DMA_EINVAL;
+  if (s->d != 64 && s->d != 128) return DMA_EUNSUPPORTED;
+  if (s->dtype != DMA_BF16 && s->dtype != DMA_F32) return DMA_EUNSUPPORTED;
+  if (!s->causal) return DMA_EUNSUPPORTED;
+  if (s->H_q > 65535 || s->H_kv > 65535) return DMA_EUNSUPPORTED;
+  return DMA_OK;
+}
+
+size_t ws_bytes_for(const dma_shape& s) {
+  if (s.dtype == DMA_F32) return align_up((size_t)s.H_q * s.T * 4, 256);
+  return ws_layout(s).total;
+}
+
+Ptrs make_ptrs(const dma_shape* s, const void* mask) {
+  Ptrs p;
+  p.s = *s;
+  p.pl = plan_layout(*s);
+  p.plan = const_cast<char*>(static_cast<const char*>(mask));
+  p.scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->d);
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dma_mask_bytes(const dma_shape* shape) {
+  if (check_shape(shape) != DMA_OK) return 0;
+  return plan_layout(*shape).total;
+}
+
+size_t dma_workspace_bytes(const dma_shape* shape) {
+  if (check_shape(shape) != DMA_OK) return 0;
+  return ws_bytes_for(*shape);
+}
+
+int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
+                 const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,
+                 void* mask, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!cu_seqlens || !z || !expiry || !mask) return DMA_EINVAL;
+  if (W && (!V || !A)) return DMA_EINVAL;
+  if (!aligned16(V) || !aligned16(W) || !aligned16(z) || !aligned16(expiry) || !aligned16(mask)) return DMA_EINVAL;
+  Ptrs p = make_ptrs(shape, mask);
+  return launch_mask_gen(p, V, W, A, cu_seqlens, z, expiry, topk_idx, (hipStream_t)stream);
+}
+
+int dma_fwd(const dma_shape* shape, const void* Q, const void* K, const void* V, const float* z,
+            const int32_t* expiry, const void* mask, const int32_t* cu_seqlens,
+            void* O, float* LSE, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!Q || !K || !V || !z || !expiry || !mask || !cu_seqlens || !O || !LSE) return DMA_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(z) || !aligned16(LSE) ||
+      !aligned16(mask))
+    return DMA_EINVAL;
+  Ptrs p = make_ptrs(shape, mask);
+  if (shape->dtype == DMA_F32)
+    return launch_fwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, z, expiry, cu_seqlens, (float*)O, LSE,
+                          (hipStream_t)stream);
+  return launch_fwd(p, Q, K, V, z, expiry, cu_seqlens, O, LSE, (hipStream_t)stream);
+}
+
+int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V, const void* O,
+            const void* dO, const float* LSE, const float* z, const int32_t* expiry,
+            const void* mask, const int32_t* cu_seqlens,
+            void* dQ, void* dK, void* dV, float* dz, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!Q || !K || !V || !O || !dO || !LSE || !z || !expiry || !mask || !cu_seqlens || !dQ || !dK || !dV || !dz)
+    return DMA_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(dQ) ||
+      !aligned16(dK) || !aligned16(dV) || !aligned16(dz) || !aligned16(LSE) || !aligned16(z) || !aligned16(mask) ||
+      !aligned16(ws))
+    return DMA_EINVAL;
+  if (!ws || ws_bytes < ws_bytes_for(*shape)) return DMA_EWORKSPACE;
+  Ptrs p = make_ptrs(shape, mask);
+  if (shape->dtype == DMA_F32)
+    return launch_bwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, (const float*)dO, LSE,
+                          z, expiry, cu_seqlens, (float*)dQ, (float*)dK, (float*)dV, dz, (char*)ws,
+                          (hipStream_t)stream);
+  return launch_bwd(p, Q, K, V, O, dO, LSE, z, expiry, cu_seqlens, dQ, dK, dV, dz, (char*)ws, (hipStream_t)stream);
+}
+
+const char* dma_strerror(int status) {
+  switch (status) {
+    case DMA_OK: return "ok";
+    case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32, causal = 1)";
+    case DMA_EWORKSPACE: return "workspace missing or smaller than dma_workspace_bytes()";
+    case DMA_EHIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int dma_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,152 @@
+// Shared device/host definitions of the gfx950 Dynamic Mask Attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/dma.h"
+
+namespace dma {
+
+// ------------------------------------------------------------------ tiling constants
+constexpr int BQ = 128;        // query rows per block (one workgroup of the attention kernels)
+constexpr int KT = 64;         // keys per tile of the query-stationary kernels
+constexpr int MAXPART = 2 * BQ;  // a block has at most BQ entering + BQ expiring keys
+constexpr int SG = 128;        // slot columns per workgroup of the key-stationary backward
+constexpr int SEG = 16;        // query blocks swept by one key-stationary work item
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// ------------------------------------------------------------------ mask plan layout (host + device)
+// The plan is one device buffer.  All offsets are in bytes from its start.
+struct PlanLayout {
+  int nblk_cap;    // upper bound on the number of query blocks: T / BQ + n_docs
+  int kpad;        // slot-table row length: min(k, T) rounded up to SG
+  int nbits_cap;   // wavelet levels needed for the longest possible document
+  int wcap;        // 64-bit words per wavelet level per head: T / 64 + 2 * n_docs
+  size_t off_hdr;      // int32[16]: [0] number of blocks
+  size_t off_blk;      // int4[nblk_cap]: {doc, row0, row1, doc_start}; doc = -1 past the end
+  size_t off_docblk;   // int32[n_docs + 1]: first block of each document
+  size_t off_slot;     // int32[H_q][nblk_cap][kpad]: clean resident key of each slot, or -1
+  size_t off_pcnt;     // int32[H_q][nblk_cap]
+  size_t off_plist;    // int32[H_q][nblk_cap][MAXPART]: keys partially active in the block
+  size_t off_parent;   // int32[H_q][T]: key evicted when this key entered (global index) or -1
+  size_t off_slotid;   // int32[H_q][T]: slot column of the key (local), valid if the key ever enters
+  size_t off_sk0, off_sk1;   // uint32[H_q][T] x2: sort keys (ping-pong), later wavelet values
+  size_t off_si0, off_si1;   // uint32[H_q][T] x2: sort payload (local key index)
+  size_t off_wbits;    // uint64[H_q][nbits_cap][wcap]: zero-bit masks of each wavelet level
+  size_t off_wcnt;     // uint32[H_q][nbits_cap][wcap]: zeros before each word
+  size_t off_wzero;    // uint32[H_q][n_docs][nbits_cap]: total zeros of each level
+  size_t total;
+};
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static inline int ceil_log2(int n) {
+  int b = 0;
+  while ((1ll << b) < n) b++;
+  return b;
+}
+
+static inline PlanLayout plan_layout(const dma_shape& s) {
+  PlanLayout p;
+  size_t T = s.T, H = s.H_q;
+  p.nblk_cap = s.T / BQ + s.n_docs;
+  int kk = s.k < s.T ? s.k : s.T;
+  p.kpad = (kk + SG - 1) / SG * SG;
+  p.nbits_cap = ceil_log2(s.T < 2 ? 2 : s.T);
+  p.wcap = s.T / 64 + 2 * s.n_docs;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  p.off_hdr = take(64);
+  p.off_blk = take((size_t)p.nblk_cap * 16);
+  p.off_docblk = take((size_t)(s.n_docs + 1) * 4);
+  p.off_slot = take(H * p.nblk_cap * (size_t)p.kpad * 4);
+  p.off_pcnt = take(H * p.nblk_cap * 4);
+  p.off_plist = take(H * p.nblk_cap * (size_t)MAXPART * 4);
+  p.off_parent = take(H * T * 4);
+  p.off_slotid = take(H * T * 4);
+  p.off_sk0 = take(H * T * 4);
+  p.off_sk1 = take(H * T * 4);
+  p.off_si0 = take(H * T * 4);
+  p.off_si1 = take(H * T * 4);
+  p.off_wbits = take(H * p.nbits_cap * (size_t)p.wcap * 8);
+  p.off_wcnt = take(H * p.nbits_cap * (size_t)p.wcap * 4);
+  p.off_wzero = take(H * (size_t)s.n_docs * p.nbits_cap * 4);
+  p.total = o;
+  return p;
+}
+
+// workspace of dma_bwd: D[H_q][T] float, dK32 / dV32 [T][H_kv][d] float
+struct WsLayout {
+  size_t off_D, off_dK, off_dV, total;
+};
+static inline WsLayout ws_layout(const dma_shape& s) {
+  WsLayout w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+  w.off_D = take((size_t)s.H_q * s.T * 4);
+  w.off_dK = take((size_t)s.T * s.H_kv * s.d * 4);
+  w.off_dV = take((size_t)s.T * s.H_kv * s.d * 4);
+  w.total = o;
+  return w;
+}
+
+// ------------------------------------------------------------------ launch entry points (defined in the .hip files)
+struct Ptrs {  // everything the kernels need, resolved by the host API
+  dma_shape s;
+  PlanLayout pl;
+  char* plan;
+  float scale;
+};
+
+int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A, const int32_t* cu,
+                    float* z, int32_t* expiry, int32_t* topk_idx, hipStream_t st);
+int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const float* z,
+               const int32_t* expiry, const int32_t* cu, void* O, float* LSE, hipStream_t st);
+int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+               const float* LSE, const float* z, const int32_t* expiry, const int32_t* cu,
+               void* dQ, void* dK, void* dV, float* dz, char* ws, hipStream_t st);
+int launch_fwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V, const float* z,
+                   const int32_t* expiry, const int32_t* cu, float* O, float* LSE, hipStream_t st);
+int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V, const float* O,
+                   const float* dO, const float* LSE, const float* z, const int32_t* expiry,
+                   const int32_t* cu, float* dQ, float* dK, float* dV, float* dz, char* ws, hipStream_t st);
+
+#ifdef __HIPCC__
+// ------------------------------------------------------------------ device helpers
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  // D[32x32] += A[32x16] B[16x32].  Lane l holds A[l%32][8*(l/32) .. +8), B[8*(l/32) .. +8)[l%32],
+  // and D[8*(v/4) + 4*(l/32) + v%4][l%32] in register v.
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Four bf16 of one column of a row-major LDS tile, taken from four consecutive rows:
+// within each group of 16 lanes, lane i supplies the address of row (i/4), columns 4*(i%4)..+3 of a
+// 4 x 16 patch, and receives column i of that patch (rows 0..3).
+__device__ __forceinline__ s16x4 lds_read_tr(const void* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// document of a global row: largest d with cu[d] <= t
+__device__ __forceinline__ int find_doc(const int32_t* __restrict__ cu, int n_docs, int t) {
+  int lo = 0, hi = n_docs;  // answer in [lo, hi)
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (cu[mid] <= t) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+#endif
+
+}  // namespace dma

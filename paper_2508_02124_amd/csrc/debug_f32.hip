@@ -1,0 +1,190 @@
+// fp32 debug path of the attention forward / backward (Eq. 5-10): plain FMA arithmetic, one wave
+// per query row or per key, no tiling.  It exists to check the mask plumbing and the gradient
+// formulas at fp32 accuracy on small inputs; it is not a performance path.
+#include "common.h"
+
+namespace dma {
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+  return x;
+}
+
+// One wave per (query row t, head h).  MODE 0: forward (O, LSE).  MODE 1: backward row pass
+// (D_t = dO_t . O_t, dQ_t), with P recomputed from LSE.
+template <int D, int MODE>
+__global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
+                                                     const float* __restrict__ V, const float* __restrict__ z,
+                                                     const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
+                                                     int n_docs, int T, int H_q, int H_kv, float scale,
+                                                     float* __restrict__ O, float* __restrict__ LSE,
+                                                     const float* __restrict__ dO, float* __restrict__ Dout,
+                                                     float* __restrict__ dQ) {
+  const int t = blockIdx.x, h = blockIdx.y, l = threadIdx.x;
+  const int g = h / (H_q / H_kv);
+  const int a = cu[find_doc(cu, n_docs, t)];
+  __shared__ float qs[D], dos[D];
+  const float* qrow = Q + ((size_t)t * H_q + h) * D;
+  for (int c = l; c < D; c += 64) qs[c] = qrow[c];
+  float Dt = 0.f, lse = 0.f;
+  if (MODE == 1) {
+    const float* dorow = dO + ((size_t)t * H_q + h) * D;
+    const float* orow = O + ((size_t)t * H_q + h) * D;
+    float part = 0.f;
+    for (int c = l; c < D; c += 64) {
+      dos[c] = dorow[c];
+      part = fmaf(dorow[c], orow[c], part);
+    }
+    Dt = wave_sum(part);
+    lse = LSE[(size_t)h * T + t];
+    if (l == 0) Dout[(size_t)h * T + t] = Dt;
+  }
+  __syncthreads();
+  float m = -INFINITY;
+  if (MODE == 0) {
+    for (int j0 = a; j0 <= t; j0 += 64) {
+      const int j = j0 + l;
+      if (j <= t && expiry[(size_t)h * T + j] > t) {
+        const float* kr = K + ((size_t)j * H_kv + g) * D;
+        float s = 0.f;
+        for (int c = 0; c < D; c++) s = fmaf(qs[c], kr[c], s);
+        m = fmaxf(m, s * scale + z[(size_t)h * T + j]);
+      }
+    }
+    m = wave_max(m);
+  }
+  float acc[D];
+#pragma unroll
+  for (int c = 0; c < D; c++) acc[c] = 0.f;
+  float lsum = 0.f;
+  for (int j0 = a; j0 <= t; j0 += 64) {
+    const int j = j0 + l;
+    if (j <= t && expiry[(size_t)h * T + j] > t) {
+      const float* kr = K + ((size_t)j * H_kv + g) * D;
+      const float* vr = V + ((size_t)j * H_kv + g) * D;
+      float s = 0.f;
+      for (int c = 0; c < D; c++) s = fmaf(qs[c], kr[c], s);
+      s = s * scale + z[(size_t)h * T + j];
+      if (MODE == 0) {
+        const float pr = expf(s - m);
+        lsum += pr;
+#pragma unroll
+        for (int c = 0; c < D; c++) acc[c] = fmaf(pr, vr[c], acc[c]);
+      } else {
+        const float pr = expf(s - lse);
+        float dp = 0.f;
+        for (int c = 0; c < D; c++) dp = fmaf(dos[c], vr[c], dp);
+        const float ds = pr * (dp - Dt);
+#pragma unroll
+        for (int c = 0; c < D; c++) acc[c] = fmaf(ds, kr[c], acc[c]);
+      }
+    }
+  }
+  if (MODE == 0) {
+    lsum = wave_sum(lsum);
+    if (l == 0) LSE[(size_t)h * T + t] = m + logf(lsum);
+  }
+  const float mul = (MODE == 0) ? 1.f / lsum : scale;
+  float* outrow = (MODE == 0 ? O : dQ) + ((size_t)t * H_q + h) * D;
+#pragma unroll
+  for (int c = 0; c < D; c++) {
+    const float tot = wave_sum(acc[c]);
+    if (l == (c & 63)) outrow[c] = tot * mul;
+  }
+}
+
+// One wave per (key t, kv-head g): dK_t, dV_t summed over the q-heads of the group, dz per q-head.
+// Lane l owns channels l, l + 64, ...; rows are walked in order, so the result is deterministic.
+template <int D>
+__global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
+                                                     const float* __restrict__ V, const float* __restrict__ z,
+                                                     const int32_t* __restrict__ expiry, int T, int H_q, int H_kv,
+                                                     float scale, const float* __restrict__ LSE,
+                                                     const float* __restrict__ dO, const float* __restrict__ Dws,
+                                                     float* __restrict__ dK, float* __restrict__ dV,
+                                                     float* __restrict__ dz) {
+  constexpr int CPL = D / 64;
+  const int t = blockIdx.x, g = blockIdx.y, l = threadIdx.x;
+  const int G = H_q / H_kv;
+  float kc[CPL], vc[CPL], dk[CPL], dv[CPL];
+#pragma unroll
+  for (int u = 0; u < CPL; u++) {
+    kc[u] = K[((size_t)t * H_kv + g) * D + l + 64 * u];
+    vc[u] = V[((size_t)t * H_kv + g) * D + l + 64 * u];
+    dk[u] = 0.f;
+    dv[u] = 0.f;
+  }
+  for (int hh = 0; hh < G; hh++) {
+    const int h = g * G + hh;
+    const int e = expiry[(size_t)h * T + t];
+    const float zt = z[(size_t)h * T + t];
+    float dzacc = 0.f;
+    for (int i = t; i < e; i++) {
+      const float* qr = Q + ((size_t)i * H_q + h) * D;
+      const float* dor = dO + ((size_t)i * H_q + h) * D;
+      float qv[CPL], dov[CPL], s = 0.f, dp = 0.f;
+#pragma unroll
+      for (int u = 0; u < CPL; u++) {
+        qv[u] = qr[l + 64 * u];
+        dov[u] = dor[l + 64 * u];
+        s = fmaf(qv[u], kc[u], s);
+        dp = fmaf(dov[u], vc[u], dp);
+      }
+      s = wave_sum(s);
+      dp = wave_sum(dp);
+      const float pr = expf(s * scale + zt - LSE[(size_t)h * T + i]);
+      const float ds = pr * (dp - Dws[(size_t)h * T + i]);
+      dzacc += ds;
+#pragma unroll
+      for (int u = 0; u < CPL; u++) {
+        dk[u] = fmaf(ds, qv[u], dk[u]);
+        dv[u] = fmaf(pr, dov[u], dv[u]);
+      }
+    }
+    if (l == 0) dz[(size_t)h * T + t] = dzacc;
+  }
+#pragma unroll
+  for (int u = 0; u < CPL; u++) {
+    dK[((size_t)t * H_kv + g) * D + l + 64 * u] = dk[u] * scale;
+    dV[((size_t)t * H_kv + g) * D + l + 64 * u] = dv[u];
+  }
+}
+
+int launch_fwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V, const float* z,
+                   const int32_t* expiry, const int32_t* cu, float* O, float* LSE, hipStream_t st) {
+  const dma_shape& s = p.s;
+  dim3 grid(s.T, s.H_q);
+  if (s.d == 128)
+    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+                                                nullptr, nullptr, nullptr);
+  else
+    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+                                               nullptr, nullptr, nullptr);
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
+int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V, const float* O, const float* dO,
+                   const float* LSE, const float* z, const int32_t* expiry, const int32_t* cu, float* dQ, float* dK,
+                   float* dV, float* dz, char* ws, hipStream_t st) {
+  const dma_shape& s = p.s;
+  float* Dws = (float*)ws;
+  dim3 grid(s.T, s.H_q), gridk(s.T, s.H_kv);
+  if (s.d == 128) {
+    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale,
+                                                const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
+    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+  } else {
+    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale,
+                                               const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
+    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+  }
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
+}  // namespace dma

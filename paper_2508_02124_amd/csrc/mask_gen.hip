@@ -1,0 +1,472 @@
+// Mask generation: content scores (Eq. 3), per-row causal top-k as one expiry per key (Eq. 4),
+// and the slot table / per-block partial key lists the attention kernels walk.
+//
+// Selection.  Row i keeps the min(k, i+1) best keys j <= i under (z descending, index ascending).
+// Sort the keys of a document once under that order (stable radix sort); the keys that rank ahead
+// of key j are exactly its "dominators".  Key j stops being kept at the row where the k-th
+// dominator (in index order) appears, so
+//     e_j = max(j, k-th smallest index among the keys ranked ahead of j)
+// (never kept if that index is below j; kept to the end if fewer than k keys rank ahead).  The
+// k-th smallest index in a rank prefix is a range-quantile query, answered with a wavelet matrix
+// built over the rank-ordered index array.  Everything is integer work on the fp32 score bits, so
+// the result is the exact kept set of the scores as stored.
+//
+// Slots.  While a document has more than k rows, each row admits at most one key and evicts the
+// weakest resident; the newcomer inherits the evicted key's "slot".  Slot chains partition the
+// kept region into k columns that are always occupied, which gives the attention kernels dense
+// tiles: per query block, the resident of every slot that stays the whole block ("clean"), plus a
+// short list of keys that enter or expire inside the block ("partial").
+#include "common.h"
+
+namespace dma {
+
+// ------------------------------------------------------------------ block table
+__global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int nblk_cap, int4* blk,
+                               int32_t* docblk, int32_t* hdr) {
+  __shared__ int s_total;
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int d = 0; d < n_docs; d++) {
+      docblk[d] = acc;
+      int n = cu[d + 1] - cu[d];
+      acc += (n + BQ - 1) / BQ;
+    }
+    docblk[n_docs] = acc;
+    hdr[0] = acc;
+    s_total = acc;
+  }
+  __syncthreads();
+  for (int d = threadIdx.x; d < n_docs; d += blockDim.x) {
+    int a = cu[d], b = cu[d + 1];
+    int b0 = docblk[d];
+    for (int r = a, i = 0; r < b; r += BQ, i++) blk[b0 + i] = make_int4(d, r, min(r + BQ, b), a);
+  }
+  for (int i = s_total + threadIdx.x; i < nblk_cap; i += blockDim.x) blk[i] = make_int4(-1, 0, 0, 0);
+}
+
+__global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  size_t st = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += st) p[i] = v;
+}
+
+// ------------------------------------------------------------------ content scores (Eq. 3)
+// One workgroup per (64 tokens, kv-head): each value row is read once and scored for all q-heads
+// of its group.  z = exp(A * softplus(w . v)) in fp32.
+template <typename TV, int D>
+__global__ __launch_bounds__(256) void z_kernel(const TV* __restrict__ V, const float* __restrict__ W,
+                                                const float* __restrict__ A, float* __restrict__ z,
+                                                int T, int H_q, int H_kv) {
+  extern __shared__ float zs[];  // [G][64]
+  constexpr int LPR = D / 8;     // lanes per value row (8 elements per lane)
+  constexpr int RPP = 256 / LPR; // rows per pass
+  const int g = blockIdx.y, G = H_q / H_kv, t0 = blockIdx.x * 64;
+  const int tid = threadIdx.x, sub = tid % LPR, rl = tid / LPR;
+  for (int pass = 0; pass < 64 / RPP; pass++) {
+    const int r = pass * RPP + rl, t = t0 + r;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) v[e] = 0.f;
+    if (t < T) {
+      const TV* src = V + ((size_t)t * H_kv + g) * D + 8 * sub;
+      if constexpr (sizeof(TV) == 2) {
+        uint4 raw = *reinterpret_cast<const uint4*>(src);
+        uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          v[2 * e] = __uint_as_float(u[e] << 16);
+          v[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+        }
+      } else {
+        float4 x0 = *reinterpret_cast<const float4*>(src);
+        float4 x1 = *reinterpret_cast<const float4*>(src + 4);
+        v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
+        v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+      }
+    }
+    for (int hh = 0; hh < G; hh++) {
+      const float* w = W + (size_t)(g * G + hh) * D + 8 * sub;
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc = fmaf(v[e], w[e], acc);
+#pragma unroll
+      for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+      if (sub == 0) zs[hh * 64 + r] = acc;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * 64; idx += 256) {
+    const int hh = idx / 64, r = idx % 64, t = t0 + r;
+    if (t < T) {
+      const float x = zs[idx];
+      const float sp = fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
+      z[(size_t)(g * G + hh) * T + t] = expf(A[g * G + hh] * sp);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ sort + wavelet matrix
+// Ascending unsigned order of the result == descending float order of z (-0 and +0 compare equal).
+__device__ __forceinline__ uint32_t desc_key(float z) {
+  z = z + 0.0f;
+  uint32_t u = __float_as_uint(z);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ~u;
+}
+
+__device__ __forceinline__ int dev_ceil_log2(int n) { return n <= 1 ? 0 : 32 - __clz(n - 1); }
+
+struct SortArgs {
+  const float* z;
+  const int32_t* cu;
+  int32_t* expiry;
+  uint32_t *sk0, *sk1, *si0, *si1;
+  unsigned long long* wbits;
+  uint32_t* wcnt;
+  uint32_t* wzero;
+  int T, n_docs, k, nbits_cap, wcap;
+};
+
+// One workgroup (16 waves) per (document, head).  Stable LSD radix sort, 8-bit digits: every wave
+// owns a contiguous run of 64-key chunks, counts its digits, and after a (digit, wave)-ordered scan
+// scatters its chunks in order, ranking equal digits inside a chunk with ballots.
+__global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
+  const int d = blockIdx.x, h = blockIdx.y;
+  const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
+  if (n <= 0) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const size_t hb = (size_t)h * p.T + a;
+  if (n <= p.k) {  // every causal key is kept by every later row
+    for (int j = tid; j < n; j += 1024) p.expiry[hb + j] = b;
+    return;
+  }
+  uint32_t *k0 = p.sk0 + hb, *k1 = p.sk1 + hb, *i0 = p.si0 + hb, *i1 = p.si1 + hb;
+  for (int j = tid; j < n; j += 1024) {
+    k0[j] = desc_key(p.z[hb + j]);
+    i0[j] = j;
+  }
+  __shared__ uint32_t hist[4096];  // [digit][wave]
+  __shared__ uint32_t wsum[16];
+  const int nchunks = (n + 63) / 64, cpw = (nchunks + 15) / 16;
+  const int c_begin = w * cpw, c_end = min(nchunks, c_begin + cpw);
+  const unsigned long long lt = (1ull << l) - 1ull;
+  __syncthreads();
+
+  uint32_t *sk = k0, *dk = k1, *si = i0, *di = i1;
+  for (int pass = 0; pass < 4; pass++) {
+    const int shift = 8 * pass;
+    for (int i = tid; i < 4096; i += 1024) hist[i] = 0;
+    __syncthreads();
+    for (int c = c_begin; c < c_end; c++) {
+      const int j = c * 64 + l;
+      if (j < n) atomicAdd(&hist[((sk[j] >> shift) & 255u) * 16 + w], 1u);
+    }
+    __syncthreads();
+    {  // exclusive scan of hist[4096] in (digit, wave) order
+      const uint32_t v0 = hist[4 * tid], v1 = hist[4 * tid + 1], v2 = hist[4 * tid + 2], v3 = hist[4 * tid + 3];
+      const uint32_t s = v0 + v1 + v2 + v3;
+      uint32_t inc = s;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(inc, off);
+        if (l >= off) inc += t;
+      }
+      if (l == 63) wsum[w] = inc;
+      __syncthreads();
+      uint32_t wbase = 0;
+      for (int i = 0; i < w; i++) wbase += wsum[i];
+      const uint32_t ex = wbase + inc - s;
+      hist[4 * tid] = ex;
+      hist[4 * tid + 1] = ex + v0;
+      hist[4 * tid + 2] = ex + v0 + v1;
+      hist[4 * tid + 3] = ex + v0 + v1 + v2;
+    }
+    __syncthreads();
+    for (int c = c_begin; c < c_end; c++) {
+      const int j = c * 64 + l;
+      const bool valid = j < n;
+      const uint32_t key = valid ? sk[j] : 0u, idx = valid ? si[j] : 0u;
+      const uint32_t dig = (key >> shift) & 255u;
+      unsigned long long m = __ballot(valid);
+#pragma unroll
+      for (int bit = 0; bit < 8; bit++) {
+        const bool one = (dig >> bit) & 1u;
+        const unsigned long long bm = __ballot(one);
+        m &= one ? bm : ~bm;
+      }
+      const uint32_t rank = __popcll(m & lt);
+      const uint32_t base = hist[dig * 16 + w];
+      if (valid) {
+        dk[base + rank] = key;
+        di[base + rank] = idx;
+        if (rank == 0) hist[dig * 16 + w] = base + (uint32_t)__popcll(m);
+      }
+    }
+    __syncthreads();
+    uint32_t* t;
+    t = sk; sk = dk; dk = t;
+    t = si; si = di; di = t;
+  }
+  // sorted: si == i0 holds the key indices in rank order.
+
+  // Wavelet matrix over that array (values = key indices), most significant bit first.  Each level
+  // stores, per 64 positions, the mask of zero bits and the number of zeros before the word; the
+  // array is then stably partitioned (zeros first) for the next level.
+  const int nbits = dev_ceil_log2(n);
+  const int woff = a / 64 + 2 * d;
+  uint32_t* src = i0;
+  uint32_t* dst = k0;
+  for (int lev = 0; lev < nbits; lev++) {
+    const int sh = nbits - 1 - lev;
+    unsigned long long* wb = p.wbits + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
+    uint32_t* wc = p.wcnt + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
+    uint32_t zc = 0;
+    for (int c = c_begin; c < c_end; c++) {
+      const int j = c * 64 + l;
+      const bool zero = (j < n) && !((src[j] >> sh) & 1u);
+      zc += (uint32_t)__popcll(__ballot(zero));
+    }
+    if (l == 0) wsum[w] = zc;
+    __syncthreads();
+    uint32_t run = 0, Z = 0;
+    for (int i = 0; i < 16; i++) {
+      const uint32_t x = wsum[i];
+      if (i < w) run += x;
+      Z += x;
+    }
+    for (int c = c_begin; c < c_end; c++) {
+      const int j = c * 64 + l;
+      const bool valid = j < n;
+      const uint32_t v = valid ? src[j] : 0u;
+      const bool zero = valid && !((v >> sh) & 1u);
+      const unsigned long long zm = __ballot(zero);
+      const uint32_t zb = run + (uint32_t)__popcll(zm & lt);  // zeros before position j
+      if (l == 0) {
+        wb[c] = zm;
+        wc[c] = run;
+      }
+      if (valid) dst[zero ? zb : Z + ((uint32_t)j - zb)] = v;
+      run += (uint32_t)__popcll(zm);
+    }
+    if (tid == 0) {
+      wb[nchunks] = 0ull;
+      wc[nchunks] = Z;
+      p.wzero[((size_t)h * p.n_docs + d) * p.nbits_cap + lev] = Z;
+    }
+    __syncthreads();
+    src = dst;
+    dst = (dst == k0) ? k1 : k0;
+  }
+}
+
+// One thread per (head, rank position): expiry of the key at that rank.
+__global__ __launch_bounds__(256) void expiry_kernel(SortArgs p) {
+  const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+  if (t >= p.T) return;
+  const int d = find_doc(p.cu, p.n_docs, t);
+  const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
+  if (n <= p.k) return;
+  const int r = t - a;
+  const int j = (int)p.si0[(size_t)h * p.T + t];
+  int e;
+  if (r < p.k) {
+    e = b;
+  } else {
+    const int nbits = dev_ceil_log2(n);
+    const int woff = a / 64 + 2 * d;
+    uint32_t lo = 0, hi = (uint32_t)r, kk = (uint32_t)p.k - 1u, val = 0;
+    for (int lev = 0; lev < nbits; lev++) {
+      const unsigned long long* wb = p.wbits + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
+      const uint32_t* wc = p.wcnt + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
+      const uint32_t zlo = wc[lo >> 6] + (uint32_t)__popcll(wb[lo >> 6] & ((1ull << (lo & 63)) - 1ull));
+      const uint32_t zhi = wc[hi >> 6] + (uint32_t)__popcll(wb[hi >> 6] & ((1ull << (hi & 63)) - 1ull));
+      const uint32_t c0 = zhi - zlo;
+      if (kk < c0) {
+        lo = zlo;
+        hi = zhi;
+      } else {
+        kk -= c0;
+        const uint32_t Z = p.wzero[((size_t)h * p.n_docs + d) * p.nbits_cap + lev];
+        lo = Z + (lo - zlo);
+        hi = Z + (hi - zhi);
+        val |= 1u << (nbits - 1 - lev);
+      }
+    }
+    e = a + max(j, (int)val);
+  }
+  p.expiry[(size_t)h * p.T + a + j] = e;
+}
+
+// ------------------------------------------------------------------ slots
+// parent[i] = the key evicted when key i entered (global index, -1 if none); slotid[i] = root of
+// i's eviction chain = its slot column (document-local, < k).
+__global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ cu, const int32_t* __restrict__ expiry,
+                                                    int32_t* parent, int32_t* slotid, int T, int k) {
+  const int d = blockIdx.x, h = blockIdx.y;
+  const int a = cu[d], b = cu[d + 1], n = b - a;
+  if (n <= 0) return;
+  const size_t hb = (size_t)h * T + a;
+  int32_t* par = parent + hb;
+  int32_t* sid = slotid + hb;
+  const int32_t* ex = expiry + hb;
+  const int tid = threadIdx.x;
+  for (int j = tid; j < n; j += 1024) {
+    par[j] = -1;
+    sid[j] = j;
+  }
+  __syncthreads();
+  if (n <= k) return;
+  for (int j = tid; j < n; j += 1024) {
+    const int e = ex[j] - a;
+    if (e > j && e < n) {  // key j is evicted at row e by key e
+      par[e] = a + j;
+      sid[e] = j;
+    }
+  }
+  __syncthreads();
+  const int rounds = dev_ceil_log2(n);
+  for (int r = 0; r < rounds; r++) {  // pointer jumping towards the chain root (< k)
+    for (int j = tid; j < n; j += 1024) {
+      const int q = sid[j];
+      if (q >= k) sid[j] = sid[q];
+    }
+    __syncthreads();
+  }
+}
+
+// One thread per (head, key): write the key into the slot table of every block it is clean in.
+__global__ __launch_bounds__(256) void slot_table_kernel(const int32_t* __restrict__ cu, int n_docs,
+                                                         const int32_t* __restrict__ expiry,
+                                                         const int32_t* __restrict__ slotid,
+                                                         const int32_t* __restrict__ docblk, int32_t* slot_tab,
+                                                         int T, int nblk_cap, int kpad) {
+  const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+  if (t >= T) return;
+  const int d = find_doc(cu, n_docs, t);
+  const int a = cu[d], n = cu[d + 1] - a;
+  const int j = t - a;
+  const int e = expiry[(size_t)h * T + t] - a;
+  if (e <= j) return;
+  const int slot = slotid[(size_t)h * T + t];
+  const int blk0 = docblk[d];
+  for (int bl = j / BQ + 1;; bl++) {
+    const int i_lo = bl * BQ;
+    if (i_lo >= n) break;
+    const int i_hi = min(i_lo + BQ, n) - 1;
+    if (e <= i_hi) break;
+    slot_tab[((size_t)h * nblk_cap + blk0 + bl) * kpad + slot] = t;
+  }
+}
+
+// One workgroup (BQ threads) per (block, head): keys that enter inside the block (ascending), then
+// keys that were resident at the block's first row and are evicted inside it (by ascending evictor).
+__global__ __launch_bounds__(BQ) void partial_list_kernel(const int4* __restrict__ blk,
+                                                          const int32_t* __restrict__ expiry,
+                                                          const int32_t* __restrict__ parent, int32_t* pcnt,
+                                                          int32_t* plist, int T, int nblk_cap) {
+  const int bi = blockIdx.x, h = blockIdx.y;
+  const int4 info = blk[bi];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  if (info.x < 0) {
+    if (tid == 0) pcnt[(size_t)h * nblk_cap + bi] = 0;
+    return;
+  }
+  const int i = info.y + tid;
+  const bool ent = (i < info.z) && expiry[(size_t)h * T + i] > i;
+  int m = -1;
+  if (ent) m = parent[(size_t)h * T + i];
+  const bool exq = ent && m >= 0 && m < info.y;
+  __shared__ int cnt[2][BQ / 64];
+  const unsigned long long em = __ballot(ent), xm = __ballot(exq);
+  const unsigned long long lt = (1ull << l) - 1ull;
+  if (l == 0) {
+    cnt[0][w] = __popcll(em);
+    cnt[1][w] = __popcll(xm);
+  }
+  __syncthreads();
+  int ebase = 0, xbase = 0, etot = 0, xtot = 0;
+  for (int i2 = 0; i2 < BQ / 64; i2++) {
+    if (i2 < w) { ebase += cnt[0][i2]; xbase += cnt[1][i2]; }
+    etot += cnt[0][i2];
+    xtot += cnt[1][i2];
+  }
+  int32_t* out = plist + ((size_t)h * nblk_cap + bi) * MAXPART;
+  if (ent) out[ebase + __popcll(em & lt)] = i;
+  if (exq) out[etot + xbase + __popcll(xm & lt)] = m;
+  if (tid == 0) pcnt[(size_t)h * nblk_cap + bi] = etot + xtot;
+}
+
+// Debug output: kept keys of every row, ascending, -1 padded.  One wave per (row, head).
+__global__ __launch_bounds__(64) void topk_idx_kernel(const int32_t* __restrict__ cu, int n_docs,
+                                                      const int32_t* __restrict__ expiry, int32_t* out, int T, int k) {
+  const int t = blockIdx.x, h = blockIdx.y, l = threadIdx.x;
+  const int d = find_doc(cu, n_docs, t);
+  const int a = cu[d];
+  int32_t* o = out + ((size_t)h * T + t) * k;
+  const unsigned long long lt = (1ull << l) - 1ull;
+  int count = 0;
+  for (int j0 = a; j0 <= t; j0 += 64) {
+    const int j = j0 + l;
+    const bool keep = (j <= t) && expiry[(size_t)h * T + j] > t;
+    const unsigned long long m = __ballot(keep);
+    const int pos = count + __popcll(m & lt);
+    if (keep && pos < k) o[pos] = j;
+    count += __popcll(m);
+  }
+  for (int q = count + l; q < k; q += 64) o[q] = -1;
+}
+
+// ------------------------------------------------------------------ host side
+int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A, const int32_t* cu,
+                    float* z, int32_t* expiry, int32_t* topk_idx, hipStream_t st) {
+  const dma_shape& s = p.s;
+  const PlanLayout& L = p.pl;
+  char* base = p.plan;
+  int32_t* hdr = (int32_t*)(base + L.off_hdr);
+  int4* blk = (int4*)(base + L.off_blk);
+  int32_t* docblk = (int32_t*)(base + L.off_docblk);
+  int32_t* slot_tab = (int32_t*)(base + L.off_slot);
+  int32_t* pcnt = (int32_t*)(base + L.off_pcnt);
+  int32_t* plist = (int32_t*)(base + L.off_plist);
+  int32_t* parent = (int32_t*)(base + L.off_parent);
+  int32_t* slotid = (int32_t*)(base + L.off_slotid);
+
+  blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, blk, docblk, hdr);
+  if (W) {
+    const int G = s.H_q / s.H_kv;
+    dim3 grid((s.T + 63) / 64, s.H_kv);
+    const size_t sh = (size_t)G * 64 * sizeof(float);
+    if (s.dtype == DMA_BF16) {
+      if (s.d == 128) z_kernel<uint16_t, 128><<<grid, 256, sh, st>>>((const uint16_t*)V, W, A, z, s.T, s.H_q, s.H_kv);
+      else z_kernel<uint16_t, 64><<<grid, 256, sh, st>>>((const uint16_t*)V, W, A, z, s.T, s.H_q, s.H_kv);
+    } else {
+      if (s.d == 128) z_kernel<float, 128><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
+      else z_kernel<float, 64><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
+    }
+  }
+  SortArgs sa;
+  sa.z = z; sa.cu = cu; sa.expiry = expiry;
+  sa.sk0 = (uint32_t*)(base + L.off_sk0); sa.sk1 = (uint32_t*)(base + L.off_sk1);
+  sa.si0 = (uint32_t*)(base + L.off_si0); sa.si1 = (uint32_t*)(base + L.off_si1);
+  sa.wbits = (unsigned long long*)(base + L.off_wbits);
+  sa.wcnt = (uint32_t*)(base + L.off_wcnt);
+  sa.wzero = (uint32_t*)(base + L.off_wzero);
+  sa.T = s.T; sa.n_docs = s.n_docs; sa.k = s.k; sa.nbits_cap = L.nbits_cap; sa.wcap = L.wcap;
+  sort_wavelet_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(sa);
+  expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+  slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
+  {
+    const size_t n = (size_t)s.H_q * L.nblk_cap * L.kpad;
+    size_t grid = (n + 2047) / 2048;
+    if (grid > (1u << 20)) grid = 1u << 20;
+    if (grid < 1) grid = 1;
+    fill_i32_kernel<<<(unsigned)grid, 256, 0, st>>>(slot_tab, n, -1);
+  }
+  slot_table_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, expiry, slotid, docblk, slot_tab,
+                                                                  s.T, L.nblk_cap, L.kpad);
+  partial_list_kernel<<<dim3(L.nblk_cap, s.H_q), BQ, 0, st>>>(blk, expiry, parent, pcnt, plist, s.T, L.nblk_cap);
+  if (topk_idx) topk_idx_kernel<<<dim3(s.T, s.H_q), 64, 0, st>>>(cu, s.n_docs, expiry, topk_idx, s.T, s.k);
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
+}  // namespace dma

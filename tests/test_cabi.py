@@ -1,0 +1,74 @@
+"""The C-ABI library: loads, exports every symbol include/dma.h declares, sizes its buffers, and
+rejects bad arguments before launching anything (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2508_02124_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return B.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dma.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dma_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = declared_symbols()
+    assert {"dma_mask_gen", "dma_fwd", "dma_bwd", "dma_mask_bytes", "dma_workspace_bytes",
+            "dma_strerror", "dma_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert B.dma_version() >= 100
+
+
+def test_sizes_and_shape_validation(lib):
+    s = B.make_shape(T=16384, n_docs=1, H_q=32, H_kv=8, d=128, k=2048)
+    mb, wb = B.dma_mask_bytes(s), B.dma_workspace_bytes(s)
+    assert mb > 32 * 129 * 2048 * 4            # at least the slot table
+    assert wb >= 32 * 16384 * 4 + 2 * 16384 * 8 * 128 * 4
+    for bad in (dict(T=0), dict(k=0), dict(H_kv=3), dict(n_docs=0)):
+        kw = dict(T=256, n_docs=1, H_q=4, H_kv=2, d=64, k=16)
+        kw.update(bad)
+        assert B.dma_mask_bytes(B.make_shape(**kw)) == 0
+    assert B.dma_mask_bytes(B.make_shape(T=256, n_docs=1, H_q=4, H_kv=2, d=96, k=16)) == 0
+    f32 = B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=64, k=64, dtype=B.DMA_F32)
+    assert B.dma_workspace_bytes(f32) >= 2 * 256 * 4
+
+
+def test_error_codes_before_any_launch(lib):
+    ok = B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=64, k=64)
+    p = 0x1000                                   # aligned dummy address: never dereferenced on a failing call
+    with pytest.raises(B.DmaError) as e:
+        B.dma_mask_gen(ok, p, p, p, None, p, p, None, p, stream=0)       # cu_seqlens missing
+    assert e.value.status == B.DMA_EINVAL
+    with pytest.raises(B.DmaError) as e:
+        B.dma_mask_gen(ok, p, p, p, p, p + 4, p, None, p, stream=0)      # z misaligned
+    assert e.value.status == B.DMA_EINVAL
+    with pytest.raises(B.DmaError) as e:
+        B.dma_fwd(B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=80, k=64), p, p, p, p, p, p, p, p, p, None, 0, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
+    with pytest.raises(B.DmaError) as e:
+        B.dma_fwd(B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=64, k=64, causal=False),
+                  p, p, p, p, p, p, p, p, p, None, 0, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
+    with pytest.raises(B.DmaError) as e:
+        B.dma_bwd(ok, p, p, p, p, p, p, p, p, p, p, p, p, p, p, p, 16, stream=0)   # workspace too small
+    assert e.value.status == B.DMA_EWORKSPACE
+    with pytest.raises(B.DmaError) as e:
+        B.dma_bwd(ok, p, p, p, p, p, p, p, p, p, p, None, p, p, p, p, 1 << 30, stream=0)   # dQ missing
+    assert e.value.status == B.DMA_EINVAL
+    assert "workspace" in B.strerror(B.DMA_EWORKSPACE)
+    assert B.strerror(0) == "ok"

@@ -1,0 +1,138 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle.
+
+Index work (expiry, kept-key lists) must match bit for bit when both sides see
+the same fp32 scores; floating-point outputs must meet the tolerances in
+gpu_harness.tol().  The attention comparisons feed the oracle the scores the GPU
+produced (widened exactly to fp64), so both sides select on identical keys; the
+scores themselves are compared with the oracle's own Eq. 3 separately.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2508_02124_amd import workloads as wlmod
+from gpu_harness import BQ, DeviceCase, check_close, tol
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    "cfg1": lambda: wlmod.CONFIGS["cfg1"],
+    "ragged_varlen_d64": lambda: wlmod.small_workload("ragged_varlen_d64", 11, 4, 2, 64, 48, (200, 77, 300, 1, 129)),
+    "ragged_d128": lambda: wlmod.small_workload("ragged_d128", 12, 2, 1, 128, 100, (333,)),
+    "k_ge_len": lambda: wlmod.small_workload("k_ge_len", 13, 4, 4, 64, 512, (150, 150)),
+    "empty_doc": lambda: wlmod.small_workload("empty_doc", 14, 2, 2, 64, 32, (100, 0, 60)),
+    "multi_tile_d128": lambda: wlmod.small_workload("multi_tile_d128", 15, 4, 2, 128, 160, (700, 260)),
+}
+
+
+def tie_scores(H, T, seed, levels=6):
+    r = np.random.default_rng(seed)
+    return (r.integers(1, levels + 1, size=(H, T)) / levels).astype(np.float32)
+
+
+def check_mask(case: DeviceCase, label):
+    inp, wl = case.inp, case.wl
+    cu = inp.cu_seqlens
+    zg = case.host("z").astype(np.float64)
+    eg = case.host("expiry")
+    if not case.z_given:
+        zo = orc.z_scores(inp.V, inp.W, inp.A, wl.H_q)
+        rel = np.abs(zg - zo) / np.abs(zo)
+        assert rel.max() <= 1e-5, f"{label}: z rel err {rel.max():.3e}"
+    n_sel_diff = 0
+    for h in range(wl.H_q):
+        for a, b in zip(cu[:-1], cu[1:]):
+            if b == a:
+                continue
+            e = orc.expiry_sequential(zg[h, a:b], wl.k) + a
+            assert (eg[h, a:b] == e).all(), f"{label}: expiry mismatch head {h} doc [{a},{b})"
+            if not case.z_given:
+                n_sel_diff += int((orc.expiry_sequential(zo[h, a:b], wl.k) + a != e).sum())
+    if case.topk is not None:
+        tk = case.host("topk")
+        for h in range(wl.H_q):
+            for a, b in zip(cu[:-1], cu[1:]):
+                if b == a:
+                    continue
+                ref = orc.topk_indices(zg[h, a:b], wl.k)
+                ref = np.where(ref >= 0, ref + a, -1)
+                assert (tk[h, a:b] == ref).all(), f"{label}: topk_idx mismatch head {h}"
+    # plan structure: clean residents + partial list == keys active in the block
+    pv = case.plan_views()
+    nblk = sum((int(b - a) + BQ - 1) // BQ for a, b in zip(cu[:-1], cu[1:]))
+    assert pv["nblk"] == nblk
+    bi = 0
+    for d, (a, b) in enumerate(zip(cu[:-1], cu[1:])):
+        for r0 in range(a, b, BQ):
+            r1 = min(r0 + BQ, b)
+            assert pv["blk"][bi].tolist() == [d, r0, r1, a]
+            for h in range(wl.H_q):
+                j = np.arange(a, r1)
+                e = eg[h, a:r1]
+                active = j[e > np.maximum(j, r0)]
+                clean = j[(j < r0) & (e > r1 - 1)]
+                row = pv["slot"][h, bi]
+                got_clean = row[row >= 0]
+                assert len(set(got_clean.tolist())) == got_clean.size
+                assert sorted(got_clean.tolist()) == clean.tolist(), f"{label}: slot table block {bi} head {h}"
+                assert (row[min(wl.k, r0 - a):] == -1).all()
+                pc = pv["pcnt"][h, bi]
+                part = pv["plist"][h, bi, :pc]
+                assert len(set(part.tolist())) == pc
+                assert sorted(part.tolist()) == sorted(set(active.tolist()) - set(clean.tolist())), \
+                    f"{label}: partial list block {bi} head {h}"
+            bi += 1
+    return n_sel_diff
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_mask_gen_and_forward_small(gpu, name, dtype):
+    print(f"[case] mask+fwd {name} {dtype}", flush=True)
+    inp = wlmod.make_inputs(SMALL[name](), dtype=dtype)
+    case = DeviceCase(inp, gpu, topk=True)
+    case.mask_gen()
+    nd = check_mask(case, f"{name}/{dtype}")
+    print(f"  selection differences oracle-z vs gpu-z: {nd}", flush=True)
+    case.fwd()
+    zg = case.host("z").astype(np.float64)
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, inp.wl.k)
+    t = tol(dtype == "bf16")
+    print("  O", check_close("O", case.host("O"), O, **t), flush=True)
+    print("  LSE", check_close("LSE", case.host("LSE"), LSE, **tol(False) if dtype == "f32" else
+                               dict(atol=2e-2, rtol=1e-2, frob=1e-2)), flush=True)
+
+
+@pytest.mark.parametrize("levels", [1, 6])
+def test_mask_gen_heavy_ties_supplied_scores(gpu, levels):
+    print(f"[case] ties levels={levels}", flush=True)
+    wl = wlmod.small_workload("ties", 21, 4, 2, 64, 70, (500, 140))
+    inp = wlmod.make_inputs(wl)
+    z = tie_scores(wl.H_q, inp.T, 5, levels)
+    case = DeviceCase(inp, gpu, z_override=z, topk=True)
+    case.mask_gen()
+    check_mask(case, f"ties{levels}")
+    assert (case.host("z") == z).all()                   # supplied scores are left untouched
+    case.fwd()
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, z.astype(np.float64), inp.cu_seqlens, wl.k)
+    check_close("O", case.host("O"), O, **tol(True))
+    check_close("LSE", case.host("LSE"), LSE, **tol(True))
+
+
+def test_dense_equivalence_zero_scores(gpu):
+    """k >= L and z = 0: the path must reduce to plain causal attention (torch SDPA in fp32 as a
+    second, independent reference next to the oracle)."""
+    print("[case] dense equivalence", flush=True)
+    wl = wlmod.small_workload("dense", 22, 4, 2, 128, 400, (384,))
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu, z_override=np.zeros((wl.H_q, inp.T), np.float32))
+    case.mask_gen()
+    case.fwd()
+    q = torch.tensor(inp.Q).permute(1, 0, 2)[None]
+    k = torch.tensor(inp.K).permute(1, 0, 2)[None].repeat_interleave(2, dim=1)
+    v = torch.tensor(inp.V).permute(1, 0, 2)[None].repeat_interleave(2, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0].permute(1, 0, 2).numpy()
+    check_close("O vs SDPA", case.host("O"), ref, **tol(True))
+    O, _ = orc.dma_forward(inp.Q, inp.K, inp.V, np.zeros((wl.H_q, inp.T)), inp.cu_seqlens, wl.k)
+    check_close("O vs oracle", case.host("O"), O, **tol(True))
