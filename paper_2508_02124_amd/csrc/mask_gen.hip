@@ -375,7 +375,7 @@ __global__ __launch_bounds__(BQ) void partial_list_kernel(const int4* __restrict
   const bool ent = (i < info.z) && expiry[(size_t)h * T + i] > i;
   int m = -1;
   if (ent) m = parent[(size_t)h * T + i];
-  const bool exq = ent && m >= 0 && m < info.y;
+  const bool exq = ent && m >= 0 && m < info.y && i > info.y;  // evicted at the block's first row: not active here
   __shared__ int cnt[2][BQ / 64];
   const unsigned long long em = __ballot(ent), xm = __ballot(exq);
   const unsigned long long lt = (1ull << l) - 1ull;
