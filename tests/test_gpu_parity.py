@@ -136,3 +136,37 @@ def test_dense_equivalence_zero_scores(gpu):
     check_close("O vs SDPA", case.host("O"), ref, **tol(True))
     O, _ = orc.dma_forward(inp.Q, inp.K, inp.V, np.zeros((wl.H_q, inp.T)), inp.cu_seqlens, wl.k)
     check_close("O vs oracle", case.host("O"), O, **tol(True))
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_backward_small(gpu, name, dtype):
+    print(f"[case] bwd {name} {dtype}", flush=True)
+    inp = wlmod.make_inputs(SMALL[name](), dtype=dtype)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen()
+    case.fwd()
+    case.bwd()
+    zg = case.host("z").astype(np.float64)
+    dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, inp.wl.k)
+    t = tol(dtype == "bf16")
+    for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
+        print(f"  {nm}", check_close(nm, case.host(nm), ref, **t), flush=True)
+    # keys that are never kept get exactly zero gradient into z
+    eg = case.host("expiry")
+    never = eg == np.arange(inp.T)[None, :]
+    assert (case.host("dz")[never] == 0.0).all()
+
+
+def test_backward_heavy_ties(gpu):
+    print("[case] bwd ties", flush=True)
+    wl = wlmod.small_workload("ties", 21, 4, 2, 128, 70, (500, 140))
+    inp = wlmod.make_inputs(wl)
+    z = tie_scores(wl.H_q, inp.T, 6, 4)
+    case = DeviceCase(inp, gpu, z_override=z)
+    case.mask_gen()
+    case.fwd()
+    case.bwd()
+    dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, z.astype(np.float64), inp.dO, inp.cu_seqlens, wl.k)
+    for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
+        print(f"  {nm}", check_close(nm, case.host(nm), ref, **tol(True)), flush=True)
