@@ -33,6 +33,7 @@ struct BwdArgs {
   const int32_t* pcnt;
   const int32_t* plist;
   int T, H_q, H_kv, k, nblk_cap, kpad;
+  int seg;  // query blocks swept by one clean-mode work item of dkv_kernel
   float scale, c2;
 };
 
@@ -44,7 +45,7 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* ap, int ld) {
 
 // ------------------------------------------------------------------ dQ (and D)
 template <int D>
-__global__ __launch_bounds__(256) void dq_kernel(BwdArgs p) {
+__global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
   constexpr int LDK = D + 8, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = KT * CPR / 256;
   __shared__ __align__(16) uint16_t smem[2 * KT * LDK];
   __shared__ __align__(16) float zs[KT];
@@ -102,16 +103,23 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdArgs p) {
   uint4 kst[NCH], vst[NCH];
   float z_st = 0.f;
   int j_st = 0, e_st = 0;
+  int idn[NCH], idz = -1;  // key ids of the tile about to be loaded (rows of this thread's chunks; row tid)
   auto tile_id = [&](int t, int r) -> int {
+    if (t >= nt) return -1;
     if (t < nc) return slot_row[t * KT + r];
     const int q = (t - nc) * KT + r;
     return q < np_keys ? plist_row[q] : -1;
   };
-  auto load_tile = [&](int t) {
+  auto load_ids = [&](int t) {
+#pragma unroll
+    for (int it = 0; it < NCH; it++) idn[it] = tile_id(t, (tid + 256 * it) / CPR);
+    if (tid < KT) idz = tile_id(t, tid);
+  };
+  auto load_tile = [&]() {  // gathers the tile whose ids are in idn / idz
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
-      const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
-      const int id = tile_id(t, r);
+      const int col = (tid + 256 * it) % CPR;
+      const int id = idn[it];
       kst[it] = make_uint4(0, 0, 0, 0);
       vst[it] = make_uint4(0, 0, 0, 0);
       if (id >= 0) {
@@ -121,14 +129,16 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdArgs p) {
       }
     }
     if (tid < KT) {
-      const int id = tile_id(t, tid);
+      const int id = idz;
       z_st = id >= 0 ? zh[id] * LOG2E : -INFINITY;
       j_st = id >= 0 ? id : 0x7fffffff;
       e_st = id >= 0 ? eh[id] : 0;
     }
   };
 
-  load_tile(0);
+  load_ids(0);
+  load_tile();
+  load_ids(1);
   const int l16 = l & 15, b16 = (l >> 4) & 1;
   for (int t = 0; t < nt; t++) {
     __syncthreads();
@@ -144,7 +154,10 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdArgs p) {
       es[tid] = e_st;
     }
     __syncthreads();
-    if (t + 1 < nt) load_tile(t + 1);
+    if (t + 1 < nt) {
+      load_tile();
+      load_ids(t + 2);
+    }
     const bool masked = t >= nc;
 
     bf16x8 dsb[2][2];
@@ -226,6 +239,8 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
   __shared__ __align__(16) uint16_t dOs[BQ * LDQ];
   __shared__ __align__(16) float lses[BQ];
   __shared__ __align__(16) float Dss[BQ];
+  constexpr int LDS_ST = D + 4;
+  __shared__ __align__(16) float stage_all[4 * 32 * LDS_ST];  // per wave: [32 columns][D] fp32, flush staging
 
   const int grp = blockIdx.y, h = blockIdx.z;
   const int g = h / (p.H_q / p.H_kv);
@@ -239,8 +254,8 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
     bi_begin = blockIdx.x;
     bi_end = bi_begin + 1;
   } else {
-    bi_begin = blockIdx.x * SEG;
-    bi_end = min(bi_begin + SEG, p.nblk_cap);
+    bi_begin = blockIdx.x * p.seg;
+    bi_end = min(bi_begin + p.seg, p.nblk_cap);
   }
 
   int curid = -1, kj = 0x7fffffff, ke = 0;
@@ -258,22 +273,40 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
     for (int v = 0; v < 16; v++) { dkacc[cb][v] = 0.f; dvacc[cb][v] = 0.f; }
   float dzacc = 0.f;
 
-  auto flush = [&]() {
-    // called wave-uniformly; lanes with curid < 0 contribute nothing
+  float* stage = stage_all + w * 32 * LDS_ST;
+  // Flush the columns whose lanes pass doit = true (wave-uniform call).  The accumulators are
+  // transposed through the wave's LDS staging area so that each atomic instruction adds 64
+  // consecutive channels of one key.
+  auto flush = [&](bool doit) {
     const float dzt = dzacc + __shfl_xor(dzacc, 32);
-    if (curid >= 0) {
-      float* dkp = p.dK32 + ((size_t)curid * p.H_kv + g) * D + 4 * hh;
-      float* dvp = p.dV32 + ((size_t)curid * p.H_kv + g) * D + 4 * hh;
+    doit = doit && curid >= 0;
+    const unsigned fm = (unsigned)(__ballot(doit) & 0xffffffffull);
+    if (fm == 0) return;
+    if (doit && hh == 0) atomicAdd(p.dz + (size_t)h * p.T + curid, dzt);
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++)
+    for (int which = 0; which < 2; which++) {
+      if (doit) {
 #pragma unroll
-        for (int gq = 0; gq < 4; gq++)
+        for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-          for (int u = 0; u < 4; u++) {
-            atomicAdd(dkp + 32 * cb + 8 * gq + u, dkacc[cb][4 * gq + u] * p.scale);
-            atomicAdd(dvp + 32 * cb + 8 * gq + u, dvacc[cb][4 * gq + u]);
+          for (int gq = 0; gq < 4; gq++) {
+            f32x4 v4;
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+              v4[u] = which == 0 ? dkacc[cb][4 * gq + u] * p.scale : dvacc[cb][4 * gq + u];
+            *reinterpret_cast<f32x4*>(&stage[n * LDS_ST + 32 * cb + 8 * gq + 4 * hh]) = v4;
           }
-      if (hh == 0) atomicAdd(p.dz + (size_t)h * p.T + curid, dzt);
+      }
+      float* dst = which == 0 ? p.dK32 : p.dV32;
+      unsigned m = fm;
+      while (m) {
+        const int c = __ffs(m) - 1;
+        m &= m - 1;
+        const int id = __shfl(curid, c);
+        float* row = dst + ((size_t)id * p.H_kv + g) * D;
+#pragma unroll
+        for (int u = 0; u < D / 64; u++) atomicAdd(row + l + 64 * u, stage[c * LDS_ST + l + 64 * u]);
+      }
     }
   };
 
@@ -292,13 +325,7 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
     }
     const bool changed = newid != curid;
     if (__any(changed)) {
-      // flush finished keys, then re-arm the changed columns
-      {
-        const int keep_id = curid;
-        if (!changed) curid = -1;   // unchanged lanes must not flush
-        flush();
-        curid = keep_id;
-      }
+      flush(changed);  // finished keys out, then re-arm the changed columns
       if (changed) {
 #pragma unroll
         for (int cb = 0; cb < CB; cb++)
@@ -400,7 +427,7 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
       }
     }
   }
-  flush();
+  flush(true);
 }
 
 __global__ void fill_f32_kernel(float* p, size_t n, float v) {
@@ -449,12 +476,19 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   a.plist = (const int32_t*)(p.plan + L.off_plist);
   a.T = s.T; a.H_q = s.H_q; a.H_kv = s.H_kv; a.k = s.k; a.nblk_cap = L.nblk_cap; a.kpad = L.kpad;
   a.scale = p.scale; a.c2 = p.scale * LOG2E;
+  {  // sweep length of a clean-mode work item: as long as possible while keeping >= 512 work items
+    const long groups = (long)(L.kpad / SG) * s.H_q;
+    long seg = (long)L.nblk_cap * groups / 512;
+    if (seg < 4) seg = 4;
+    if (seg > L.nblk_cap) seg = L.nblk_cap;
+    a.seg = (int)seg;
+  }
 
   const size_t nkv = (size_t)s.T * s.H_kv * s.d;
   fill_f32_kernel<<<grid_for(2 * nkv, 2048), 256, 0, st>>>(a.dK32, (wl.off_dV - wl.off_dK) / 4 + nkv, 0.f);
   fill_f32_kernel<<<grid_for((size_t)s.H_q * s.T, 2048), 256, 0, st>>>(dz, (size_t)s.H_q * s.T, 0.f);
   dim3 gq(L.nblk_cap, s.H_q);
-  dim3 gclean((L.nblk_cap + SEG - 1) / SEG, L.kpad / SG, s.H_q);
+  dim3 gclean((L.nblk_cap + a.seg - 1) / a.seg, L.kpad / SG, s.H_q);
   dim3 gpart(L.nblk_cap, MAXPART / SG, s.H_q);
   if (s.d == 128) {
     dq_kernel<128><<<gq, 256, 0, st>>>(a);

@@ -12,7 +12,6 @@ constexpr int BQ = 128;        // query rows per block (one workgroup of the att
 constexpr int KT = 64;         // keys per tile of the query-stationary kernels
 constexpr int MAXPART = 2 * BQ;  // a block has at most BQ entering + BQ expiring keys
 constexpr int SG = 128;        // slot columns per workgroup of the key-stationary backward
-constexpr int SEG = 16;        // query blocks swept by one key-stationary work item
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 

@@ -29,7 +29,7 @@ struct FwdArgs {
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void fwd_kernel(FwdArgs p) {
+__global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
   constexpr int LDK = D + 8;      // LDS row stride in elements (16 bytes of padding)
   constexpr int KS = D / 16;      // contraction steps of K Q^T
   constexpr int CB = D / 32;      // 32-channel blocks of O^T
@@ -80,16 +80,23 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs p) {
   uint4 kst[NCH], vst[NCH];
   float z_st = 0.f;
   int j_st = 0, e_st = 0;
+  int idn[NCH], idz = -1;  // key ids of the tile about to be loaded (rows of this thread's chunks; row tid)
   auto tile_id = [&](int t, int r) -> int {
+    if (t >= nt) return -1;
     if (t < nc) return slot_row[t * KT + r];
     const int q = (t - nc) * KT + r;
     return q < np_keys ? plist_row[q] : -1;
   };
-  auto load_tile = [&](int t) {
+  auto load_ids = [&](int t) {
+#pragma unroll
+    for (int it = 0; it < NCH; it++) idn[it] = tile_id(t, (tid + 256 * it) / CPR);
+    if (tid < KT) idz = tile_id(t, tid);
+  };
+  auto load_tile = [&]() {  // gathers the tile whose ids are in idn / idz
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
-      const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
-      const int id = tile_id(t, r);
+      const int col = (tid + 256 * it) % CPR;
+      const int id = idn[it];
       kst[it] = make_uint4(0, 0, 0, 0);
       vst[it] = make_uint4(0, 0, 0, 0);
       if (id >= 0) {
@@ -99,14 +106,16 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs p) {
       }
     }
     if (tid < KT) {
-      const int id = tile_id(t, tid);
+      const int id = idz;
       z_st = id >= 0 ? zh[id] * LOG2E : -INFINITY;
       j_st = id >= 0 ? id : 0x7fffffff;
       e_st = id >= 0 ? eh[id] : 0;
     }
   };
 
-  load_tile(0);
+  load_ids(0);
+  load_tile();
+  load_ids(1);
   for (int t = 0; t < nt; t++) {
     __syncthreads();
 #pragma unroll
@@ -121,7 +130,10 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs p) {
       es[tid] = e_st;
     }
     __syncthreads();
-    if (t + 1 < nt) load_tile(t + 1);
+    if (t + 1 < nt) {
+      load_tile();
+      load_ids(t + 2);
+    }
     const bool masked = t >= nc;
 
     // S^T = K Q^T for the two 32-key halves of the tile
@@ -174,10 +186,12 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs p) {
         pb[kb][v >> 3][v & 7] = (__bf16)pv;
       }
     lsum = lsum * alpha + psum;
+    if (!__all(alpha == 1.0f)) {  // the running maximum rarely moves after the first tiles
 #pragma unroll
-    for (int cb = 0; cb < CB; cb++)
+      for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) oacc[cb][v] *= alpha;
+        for (int v = 0; v < 16; v++) oacc[cb][v] *= alpha;
+    }
 
     // O^T += V^T P^T
     const int l16 = l & 15, b16 = (l >> 4) & 1;
