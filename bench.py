@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dynamic Mask Attention hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch already resident in HBM:
+dma_mask_gen (scores, top-k expiry, slot plan) + dma_fwd + dma_bwd, all through the C ABI.
+Prints ONE JSON line.  `value` is the effective TFLOP/s of the step: the algorithmic
+forward+backward FLOPs (14 * d per kept (query, key) pair) divided by the step time, mask
+generation included.  `roofline` is measured live with HIP events recorded inside the library
+around each kernel stage; `cpu_baseline` times the CPU oracle on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, published
+HEADLINE = "cfg3"
+
+
+def n_active(seqlens, k):
+    tot = 0
+    for n in seqlens:
+        n = int(n)
+        tot += n * (n + 1) // 2 if k >= n else k * n - k * (k - 1) // 2
+    return tot
+
+
+class HipEvents:
+    """Raw hipEvent_t handles (the library records them; torch's events wrap the same API)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.arr = (ctypes.c_void_p * n)()
+        for i in range(n):
+            ev = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(ev))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.arr[i] = ev
+
+    def elapsed(self, i, j):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.arr[i], self.arr[j])
+        return ms.value if rc == 0 else float("nan")
+
+    def destroy(self):
+        for ev in self.arr:
+            self.hip.hipEventDestroy(ev)
+
+
+def cpu_baseline(inp, wl, flops_per_head):
+    """The oracle as it stands, on the q-heads of one kv-group of the same workload."""
+    import oracle as orc
+    G = wl.H_q // wl.H_kv
+    nh = min(G, 4)
+    Q, K, V, dO = inp.Q[:, :nh], inp.K[:, :1], inp.V[:, :1], inp.dO[:, :nh]
+    t0 = time.perf_counter()
+    z = orc.z_scores(V, inp.W[:nh], inp.A[:nh], nh)
+    orc.dma_forward(Q, K, V, z, inp.cu_seqlens, wl.k)
+    if wl.backward:
+        orc.dma_backward(Q, K, V, z, dO, inp.cu_seqlens, wl.k)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": nh * flops_per_head / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{nh} of {wl.H_q} q-heads (one kv-head) of {wl.name}, all rows, scores + forward"
+                      f"{' + backward' if wl.backward else ''}, {dt:.1f} s; same algorithmic FLOPs per head",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default=HEADLINE, help="cfg1..cfg5 (default: the headline shape)")
+    ap.add_argument("--k", type=int, default=0, help="override the keep-window (cfg4 sweep)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2508_02124_amd import binding as B
+    from paper_2508_02124_amd import workloads as wlmod
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_harness import DeviceCase
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    wl = wlmod.CONFIGS[args.config]
+    if args.k:
+        wl = wl.with_k(args.k)
+    inp = wlmod.make_inputs(wl)
+    dev = torch.device("cuda:0")
+    case = DeviceCase(inp, dev)
+    seqlens = np.diff(inp.cu_seqlens)
+    nact = n_active(seqlens, wl.k)
+    per_pair = 14 if wl.backward else 4
+    flops = float(per_pair) * wl.d * nact * wl.H_q
+
+    def step():
+        case.mask_gen()
+        case.fwd()
+        if wl.backward:
+            case.bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    nst = len(B.STAGES)
+    evsets = [HipEvents(2 * nst) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        B.dma_profile_events(evsets[i].arr)
+        step()
+    B.dma_profile_events(None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    used = [s for s in range(nst) if wl.backward or s <= 4]
+    stage_ms = {B.STAGES[s]: float(np.mean([e.elapsed(2 * s, 2 * s + 1) for e in evsets])) for s in used}
+    for e in evsets:
+        e.destroy()
+    mask_ms = sum(stage_ms[n] for n in ("z", "sort", "expiry", "plan"))
+    fwd_ms = stage_ms["fwd"]
+    bwd_ms = sum(v for n, v in stage_ms.items() if n.startswith("bwd")) if wl.backward else 0.0
+
+    # dominant kernel and its algorithmic FLOPs per launch (per kept pair: forward 4d = S and PV;
+    # dQ kernel 6d = S, dP, dQ; key-stationary kernel 8d = S, dP, dV, dK on the pairs of its launch)
+    eg = case.host("expiry").astype(np.int64)
+    BQ = 128
+    clean_pairs = 0
+    for a, b in zip(inp.cu_seqlens[:-1], inp.cu_seqlens[1:]):
+        a, b = int(a), int(b)
+        n = b - a
+        if n == 0:
+            continue
+        j = np.arange(n)[None, :]
+        e = eg[:, a:b] - a
+        first = j // BQ + 1                                   # first block a key can be clean in
+        # block bl is clean for the key iff bl >= first and e > min((bl + 1) BQ, n) - 1
+        last_full = np.where(e >= n, (n - 1) // BQ, e // BQ - 1)    # last block with e > its last row
+        nb = np.clip(last_full - first + 1, 0, None) * (e > j)
+        rows_last = n - ((n - 1) // BQ) * BQ                  # rows of the (possibly ragged) last block
+        pairs = nb * BQ - np.where((nb > 0) & (last_full == (n - 1) // BQ), BQ - rows_last, 0)
+        clean_pairs += int(pairs.sum())
+    stage_flops = {"fwd": 4.0 * wl.d * nact * wl.H_q}
+    if wl.backward:
+        stage_flops["bwd_dq"] = 6.0 * wl.d * nact * wl.H_q
+        stage_flops["bwd_dkv"] = 8.0 * wl.d * clean_pairs
+    dom = max(stage_flops, key=lambda n: stage_ms[n])
+    achieved = stage_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
+    kernel_names = {"fwd": "fwd_kernel", "bwd_dq": "dq_kernel", "bwd_dkv": "dkv_kernel<clean>"}
+    roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "launch_ms": stage_ms[dom], "flops_per_launch": stage_flops[dom]}
+
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "dma_mask_fwd_bwd_effective_tflops" if wl.backward else "dma_mask_fwd_effective_tflops",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={inp.T} docs={len(seqlens)} H_q={wl.H_q} H_kv={wl.H_kv} d={wl.d} "
+                               f"k={wl.k} causal bf16 {'fwd+bwd' if wl.backward else 'fwd'}",
+                   "max_seqlen": int(inp.max_seqlen), "active_pairs_per_head": int(nact)},
+        "pct_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
+        "mask_gen_ms": mask_ms, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "fwd_bwd_ms": fwd_ms + bwd_ms,
+        "fwd_bwd_tflops": flops / ((fwd_ms + bwd_ms) * 1e-3) / 1e12,
+        "stage_ms": stage_ms, "algorithmic_gflop": flops / 1e9,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, wl, flops / wl.H_q)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -108,6 +108,29 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
             const void* mask, const int32_t* cu_seqlens,
             void* dQ, void* dK, void* dV, float* dz, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Per-stage timing aid.  dma_mask_gen, dma_fwd and dma_bwd each launch several kernels, so a
+ * caller cannot bracket one of them with events from outside.  `events` is a HOST array of
+ * 2 * DMA_N_STAGES hipEvent_t handles (as void*) owned by the caller, or NULL to switch the aid
+ * off (the default).  While set -- per host thread -- every entry point records events[2*s] on its
+ * stream immediately before stage s and events[2*s + 1] immediately after it.  Nothing is
+ * synchronised; the caller reads the events after synchronising the stream itself.
+ */
+typedef enum {
+  DMA_STAGE_Z = 0,          /* mask_gen: block table + content scores (Eq. 3)            */
+  DMA_STAGE_SORT = 1,       /* mask_gen: stable sort + wavelet matrix per (document, head) */
+  DMA_STAGE_EXPIRY = 2,     /* mask_gen: expiry of every key (Eq. 4)                      */
+  DMA_STAGE_PLAN = 3,       /* mask_gen: slots, slot table, partial lists, topk_idx       */
+  DMA_STAGE_FWD = 4,        /* fwd: the attention kernel                                  */
+  DMA_STAGE_BWD_ZERO = 5,   /* bwd: clearing the fp32 accumulators                        */
+  DMA_STAGE_BWD_DQ = 6,     /* bwd: D and dQ (query-stationary)                           */
+  DMA_STAGE_BWD_DKV = 7,    /* bwd: dK, dV, dz on the slot columns (key-stationary)       */
+  DMA_STAGE_BWD_PART = 8,   /* bwd: dK, dV, dz of keys entering / expiring inside a block */
+  DMA_STAGE_BWD_CVT = 9,    /* bwd: fp32 accumulators -> output dtype                     */
+  DMA_N_STAGES = 10
+} dma_stage;
+void dma_profile_events(void** events);
+
 const char* dma_strerror(int status);
 int dma_version(void);
 

@@ -55,6 +55,8 @@ def lib():
         L.dma_fwd.restype = i32
         L.dma_bwd.argtypes = [shp] + [vp] * 15 + [sz, vp]
         L.dma_bwd.restype = i32
+        L.dma_profile_events.argtypes = [vp]
+        L.dma_profile_events.restype = None
         L.dma_strerror.argtypes = [i32]
         L.dma_strerror.restype = ctypes.c_char_p
         L.dma_version.argtypes = []
@@ -91,6 +93,14 @@ def strerror(status):
 
 def dma_version():
     return int(lib().dma_version())
+
+
+STAGES = ("z", "sort", "expiry", "plan", "fwd", "bwd_zero", "bwd_dq", "bwd_dkv", "bwd_part", "bwd_cvt")
+
+
+def dma_profile_events(events):
+    """events: a ctypes array of 2 * len(STAGES) hipEvent_t handles (c_void_p), or None."""
+    lib().dma_profile_events(events)
 
 
 def dma_mask_bytes(shape):

@@ -4,6 +4,16 @@
 
 using namespace dma;
 
+namespace dma {
+static thread_local void** g_stage_events = nullptr;
+void prof_begin(int stage, hipStream_t st) {
+  if (g_stage_events) (void)hipEventRecord((hipEvent_t)g_stage_events[2 * stage], st);
+}
+void prof_end(int stage, hipStream_t st) {
+  if (g_stage_events) (void)hipEventRecord((hipEvent_t)g_stage_events[2 * stage + 1], st);
+}
+}  // namespace dma
+
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -99,6 +109,8 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
                           (hipStream_t)stream);
   return launch_bwd(p, Q, K, V, O, dO, LSE, z, expiry, cu_seqlens, dQ, dK, dV, dz, (char*)ws, (hipStream_t)stream);
 }
+
+void dma_profile_events(void** events) { dma::g_stage_events = events; }
 
 const char* dma_strerror(int status) {
   switch (status) {

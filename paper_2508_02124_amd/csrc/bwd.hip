@@ -54,7 +54,9 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
   uint16_t* Ks = smem;
   uint16_t* Vs = smem + KT * LDK;
 
-  const int bi = p.nblk_cap - 1 - (int)blockIdx.x, h = blockIdx.y;
+  int h, item;
+  if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
+  const int bi = p.nblk_cap - 1 - item;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;
   const int row0 = info.y, row1 = info.z, doc0 = info.w;
@@ -160,52 +162,52 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
     }
     const bool masked = t >= nc;
 
-    bf16x8 dsb[2][2];
-#pragma unroll
+#pragma unroll 1
     for (int kb = 0; kb < 2; kb++) {
-      f32x16 sacc, dpacc;
+      bf16x8 dsb[2];
+      {
+        f32x16 sacc, dpacc;
 #pragma unroll
-      for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
+        for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
-        const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
-        sacc = mfma32(ak, qreg[ks], sacc);
-        dpacc = mfma32(av, doreg[ks], dpacc);
-      }
-#pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        const int r = 32 * kb + 8 * gq + 4 * hh;
-        const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
-        int jv[4] = {0, 0, 0, 0}, ev[4] = {0, 0, 0, 0};
-        if (masked) {
-          const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
-          const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
-          jv[0] = jj.x; jv[1] = jj.y; jv[2] = jj.z; jv[3] = jj.w;
-          ev[0] = ee.x; ev[1] = ee.y; ev[2] = ee.z; ev[3] = ee.w;
+        for (int ks = 0; ks < KS; ks++) {
+          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
+          const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
+          sacc = mfma32(ak, qreg[ks], sacc);
+          dpacc = mfma32(av, doreg[ks], dpacc);
         }
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-          const int v = 4 * gq + u;
-          float pv = fast_exp2(fmaf(sacc[v], p.c2, zz[u]) - lse2);
-          if (masked && !(qi >= jv[u] && qi < ev[u])) pv = 0.f;
-          const float ds = pv * (dpacc[v] - Dsum);
-          dsb[kb][v >> 3][v & 7] = (__bf16)ds;
+        for (int gq = 0; gq < 4; gq++) {
+          const int r = 32 * kb + 8 * gq + 4 * hh;
+          const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
+          int jv[4] = {0, 0, 0, 0}, ev[4] = {0, 0, 0, 0};
+          if (masked) {
+            const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
+            const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
+            jv[0] = jj.x; jv[1] = jj.y; jv[2] = jj.z; jv[3] = jj.w;
+            ev[0] = ee.x; ev[1] = ee.y; ev[2] = ee.z; ev[3] = ee.w;
+          }
+#pragma unroll
+          for (int u = 0; u < 4; u++) {
+            const int v = 4 * gq + u;
+            float pv = fast_exp2(fmaf(sacc[v], p.c2, zz[u]) - lse2);
+            if (masked && !(qi >= jv[u] && qi < ev[u])) pv = 0.f;
+            const float ds = pv * (dpacc[v] - Dsum);
+            dsb[v >> 3][v & 7] = (__bf16)ds;
+          }
         }
       }
-    }
-    // dQ^T += K^T dS^T
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++)
+      // dQ^T += K^T dS^T for this half of the tile
 #pragma unroll
       for (int c = 0; c < 2; c++) {
         const int r0 = 32 * kb + 16 * c + 4 * hh + (l16 >> 2);
 #pragma unroll
         for (int cb = 0; cb < CB; cb++) {
           const bf16x8 a = tr_frag(&Ks[r0 * LDK + 32 * cb + 16 * b16 + 4 * (l16 & 3)], LDK);
-          dqacc[cb] = mfma32(a, dsb[kb][c], dqacc[cb]);
+          dqacc[cb] = mfma32(a, dsb[c], dqacc[cb]);
         }
       }
+    }
   }
 
   __syncthreads();
@@ -242,7 +244,12 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
   constexpr int LDS_ST = D + 4;
   __shared__ __align__(16) float stage_all[4 * 32 * LDS_ST];  // per wave: [32 columns][D] fp32, flush staging
 
-  const int grp = blockIdx.y, h = blockIdx.z;
+  // item = chunk * ngrp + group: the groups of one (head, chunk) run side by side and share Q / dO
+  const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
+  const int nchunk = PARTIAL ? p.nblk_cap : (p.nblk_cap + p.seg - 1) / p.seg;
+  int h, item;
+  if (!xcd_map(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
+  const int chunk = item / ngrp, grp = item - chunk * ngrp;
   const int g = h / (p.H_q / p.H_kv);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
   const int l16 = l & 15, b16 = (l >> 4) & 1;
@@ -251,10 +258,10 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
 
   int bi_begin, bi_end;
   if (PARTIAL) {
-    bi_begin = blockIdx.x;
+    bi_begin = chunk;
     bi_end = bi_begin + 1;
   } else {
-    bi_begin = blockIdx.x * p.seg;
+    bi_begin = chunk * p.seg;
     bi_end = min(bi_begin + p.seg, p.nblk_cap);
   }
 
@@ -485,21 +492,28 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   }
 
   const size_t nkv = (size_t)s.T * s.H_kv * s.d;
+  prof_begin(DMA_STAGE_BWD_ZERO, st);
   fill_f32_kernel<<<grid_for(2 * nkv, 2048), 256, 0, st>>>(a.dK32, (wl.off_dV - wl.off_dK) / 4 + nkv, 0.f);
   fill_f32_kernel<<<grid_for((size_t)s.H_q * s.T, 2048), 256, 0, st>>>(dz, (size_t)s.H_q * s.T, 0.f);
-  dim3 gq(L.nblk_cap, s.H_q);
-  dim3 gclean((L.nblk_cap + a.seg - 1) / a.seg, L.kpad / SG, s.H_q);
-  dim3 gpart(L.nblk_cap, MAXPART / SG, s.H_q);
-  if (s.d == 128) {
-    dq_kernel<128><<<gq, 256, 0, st>>>(a);
-    dkv_kernel<128, false><<<gclean, 256, 0, st>>>(a);
-    dkv_kernel<128, true><<<gpart, 256, 0, st>>>(a);
-  } else {
-    dq_kernel<64><<<gq, 256, 0, st>>>(a);
-    dkv_kernel<64, false><<<gclean, 256, 0, st>>>(a);
-    dkv_kernel<64, true><<<gpart, 256, 0, st>>>(a);
-  }
+  prof_end(DMA_STAGE_BWD_ZERO, st);
+  const unsigned gq = xcd_grid(s.H_q, L.nblk_cap);
+  const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
+  const unsigned gpart = xcd_grid(s.H_q, (long)L.nblk_cap * (MAXPART / SG));
+  prof_begin(DMA_STAGE_BWD_DQ, st);
+  if (s.d == 128) dq_kernel<128><<<gq, 256, 0, st>>>(a);
+  else dq_kernel<64><<<gq, 256, 0, st>>>(a);
+  prof_end(DMA_STAGE_BWD_DQ, st);
+  prof_begin(DMA_STAGE_BWD_DKV, st);
+  if (s.d == 128) dkv_kernel<128, false><<<gclean, 256, 0, st>>>(a);
+  else dkv_kernel<64, false><<<gclean, 256, 0, st>>>(a);
+  prof_end(DMA_STAGE_BWD_DKV, st);
+  prof_begin(DMA_STAGE_BWD_PART, st);
+  if (s.d == 128) dkv_kernel<128, true><<<gpart, 256, 0, st>>>(a);
+  else dkv_kernel<64, true><<<gpart, 256, 0, st>>>(a);
+  prof_end(DMA_STAGE_BWD_PART, st);
+  prof_begin(DMA_STAGE_BWD_CVT, st);
   cvt_bf16_kernel<<<grid_for(nkv / 4, 1024), 256, 0, st>>>(a.dK32, a.dV32, (uint16_t*)dK, (uint16_t*)dV, nkv / 4);
+  prof_end(DMA_STAGE_BWD_CVT, st);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
 

@@ -118,6 +118,10 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
                    const float* dO, const float* LSE, const float* z, const int32_t* expiry,
                    const int32_t* cu, float* dQ, float* dK, float* dV, float* dz, char* ws, hipStream_t st);
 
+// stage events (see dma_profile_events): no-ops unless the caller armed them on this thread
+void prof_begin(int stage, hipStream_t st);
+void prof_end(int stage, hipStream_t st);
+
 #ifdef __HIPCC__
 // ------------------------------------------------------------------ device helpers
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -136,6 +140,20 @@ __device__ __forceinline__ s16x4 lds_read_tr(const void* p) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Workgroups are dealt round-robin to the chip's 8 XCDs in launch order, and each XCD has its own
+// L2.  A 1-D grid of 8 * ceil(H / 8) * items_per_head workgroups is mapped so that XCD x works
+// through heads x, x + 8, ... one after the other, with consecutive items of a head running
+// side by side on that XCD: neighbouring query blocks of a head gather almost the same keys, and
+// the slot groups of a head sweep the same Q / dO tiles, so those re-reads hit in that L2.
+__device__ __forceinline__ bool xcd_map(int wg, int H, int items_per_head, int& h, int& item) {
+  const int x = wg & 7, idx = wg >> 3;
+  const int hq = idx / items_per_head;
+  h = x + 8 * hq;
+  item = idx - hq * items_per_head;
+  return h < H;
+}
+static inline unsigned xcd_grid(int H, long items_per_head) { return (unsigned)(8l * ((H + 7) / 8) * items_per_head); }
 
 // document of a global row: largest d with cu[d] <= t
 __device__ __forceinline__ int find_doc(const int32_t* __restrict__ cu, int n_docs, int t) {

@@ -42,7 +42,9 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
   uint16_t* Ks = smem;
   uint16_t* Vs = smem + KT * LDK;
 
-  const int bi = p.nblk_cap - 1 - (int)blockIdx.x, h = blockIdx.y;
+  int h, item;
+  if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
+  const int bi = p.nblk_cap - 1 - item;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;
   const int row0 = info.y, row1 = info.z, doc0 = info.w;
@@ -250,9 +252,11 @@ int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   a.plist = (const int32_t*)(p.plan + L.off_plist);
   a.T = s.T; a.H_q = s.H_q; a.H_kv = s.H_kv; a.k = s.k; a.nblk_cap = L.nblk_cap; a.kpad = L.kpad;
   a.c2 = p.scale * LOG2E;
-  dim3 grid(L.nblk_cap, s.H_q);
+  const unsigned grid = xcd_grid(s.H_q, L.nblk_cap);
+  prof_begin(DMA_STAGE_FWD, st);
   if (s.d == 128) fwd_kernel<128><<<grid, 256, 0, st>>>(a);
   else fwd_kernel<64><<<grid, 256, 0, st>>>(a);
+  prof_end(DMA_STAGE_FWD, st);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
 

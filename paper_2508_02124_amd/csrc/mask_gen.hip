@@ -431,6 +431,7 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   int32_t* parent = (int32_t*)(base + L.off_parent);
   int32_t* slotid = (int32_t*)(base + L.off_slotid);
 
+  prof_begin(DMA_STAGE_Z, st);
   blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, blk, docblk, hdr);
   if (W) {
     const int G = s.H_q / s.H_kv;
@@ -444,6 +445,7 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
       else z_kernel<float, 64><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
     }
   }
+  prof_end(DMA_STAGE_Z, st);
   SortArgs sa;
   sa.z = z; sa.cu = cu; sa.expiry = expiry;
   sa.sk0 = (uint32_t*)(base + L.off_sk0); sa.sk1 = (uint32_t*)(base + L.off_sk1);
@@ -452,8 +454,13 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   sa.wcnt = (uint32_t*)(base + L.off_wcnt);
   sa.wzero = (uint32_t*)(base + L.off_wzero);
   sa.T = s.T; sa.n_docs = s.n_docs; sa.k = s.k; sa.nbits_cap = L.nbits_cap; sa.wcap = L.wcap;
+  prof_begin(DMA_STAGE_SORT, st);
   sort_wavelet_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(sa);
+  prof_end(DMA_STAGE_SORT, st);
+  prof_begin(DMA_STAGE_EXPIRY, st);
   expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+  prof_end(DMA_STAGE_EXPIRY, st);
+  prof_begin(DMA_STAGE_PLAN, st);
   slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
   {
     const size_t n = (size_t)s.H_q * L.nblk_cap * L.kpad;
@@ -466,6 +473,7 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
                                                                   s.T, L.nblk_cap, L.kpad);
   partial_list_kernel<<<dim3(L.nblk_cap, s.H_q), BQ, 0, st>>>(blk, expiry, parent, pcnt, plist, s.T, L.nblk_cap);
   if (topk_idx) topk_idx_kernel<<<dim3(s.T, s.H_q), 64, 0, st>>>(cu, s.n_docs, expiry, topk_idx, s.T, s.k);
+  prof_end(DMA_STAGE_PLAN, st);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
 
