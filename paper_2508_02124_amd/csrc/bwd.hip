@@ -37,16 +37,11 @@ struct BwdArgs {
   float scale, c2;
 };
 
-__device__ __forceinline__ bf16x8 tr_frag(const uint16_t* ap, int ld) {
-  const s16x4 lo = lds_read_tr(ap);
-  const s16x4 hi = lds_read_tr(ap + 8 * ld);
-  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-}
-
 // ------------------------------------------------------------------ dQ (and D)
 template <int D>
 __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
-  constexpr int LDK = D + 8, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = KT * CPR / 256;
+  using TL = TileLayout<D>;
+  constexpr int LDK = TL::LD, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = KT * CPR / 256;
   __shared__ __align__(16) uint16_t smem[2 * KT * LDK];
   __shared__ __align__(16) float zs[KT];
   __shared__ __align__(16) int js[KT];
@@ -141,14 +136,13 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
   load_ids(0);
   load_tile();
   load_ids(1);
-  const int l16 = l & 15, b16 = (l >> 4) & 1;
   for (int t = 0; t < nt; t++) {
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
       const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
-      *reinterpret_cast<uint4*>(&Ks[r * LDK + 8 * col]) = kst[it];
-      *reinterpret_cast<uint4*>(&Vs[r * LDK + 8 * col]) = vst[it];
+      *reinterpret_cast<uint4*>(&Ks[TL::off(r, col)]) = kst[it];
+      *reinterpret_cast<uint4*>(&Vs[TL::off(r, col)]) = vst[it];
     }
     if (tid < KT) {
       zs[tid] = z_st;
@@ -171,8 +165,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
         for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
-          const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
+          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
+          const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[TL::off(32 * kb + n, 2 * ks + hh)]);
           sacc = mfma32(ak, qreg[ks], sacc);
           dpacc = mfma32(av, doreg[ks], dpacc);
         }
@@ -200,12 +194,9 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
       // dQ^T += K^T dS^T for this half of the tile
 #pragma unroll
       for (int c = 0; c < 2; c++) {
-        const int r0 = 32 * kb + 16 * c + 4 * hh + (l16 >> 2);
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++) {
-          const bf16x8 a = tr_frag(&Ks[r0 * LDK + 32 * cb + 16 * b16 + 4 * (l16 & 3)], LDK);
-          dqacc[cb] = mfma32(a, dsb[c], dqacc[cb]);
-        }
+        for (int cb = 0; cb < CB; cb++)
+          dqacc[cb] = mfma32(tr_frag<D>(Ks, 32 * kb + 16 * c, cb, l), dsb[c], dqacc[cb]);
       }
     }
   }
@@ -219,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
       bf16x4 o4;
 #pragma unroll
       for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[cb][4 * gq + u] * p.scale);
-      *reinterpret_cast<bf16x4*>(&Os[(32 * w + n) * LDK + 32 * cb + 8 * gq + 4 * hh]) = o4;
+      *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
     }
   __syncthreads();
 #pragma unroll
@@ -227,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
     const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
     if (row0 + r < row1)
       *reinterpret_cast<uint4*>(p.dQ + ((size_t)(row0 + r) * p.H_q + h) * D + 8 * col) =
-          *reinterpret_cast<const uint4*>(&Os[r * LDK + 8 * col]);
+          *reinterpret_cast<const uint4*>(&Os[TL::off(r, col)]);
   }
 }
 
@@ -236,7 +227,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
 // channels 32cb + 8gq + 4hh + u of dK^T / dV^T for that column's key.
 template <int D, bool PARTIAL>
 __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
-  constexpr int LDQ = D + 8, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = BQ * CPR / 256;
+  using TL = TileLayout<D>;
+  constexpr int LDQ = TL::LD, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = BQ * CPR / 256;
   __shared__ __align__(16) uint16_t Qs[BQ * LDQ];
   __shared__ __align__(16) uint16_t dOs[BQ * LDQ];
   __shared__ __align__(16) float lses[BQ];
@@ -252,7 +244,6 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
   const int chunk = item / ngrp, grp = item - chunk * ngrp;
   const int g = h / (p.H_q / p.H_kv);
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
-  const int l16 = l & 15, b16 = (l >> 4) & 1;
   const int col = grp * SG + 32 * w + n;
   const float* zh = p.z + (size_t)h * p.T;
 
@@ -379,8 +370,8 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
         rq = *reinterpret_cast<const uint4*>(p.Q + off);
         rd = *reinterpret_cast<const uint4*>(p.dO + off);
       }
-      *reinterpret_cast<uint4*>(&Qs[r * LDQ + 8 * cc]) = rq;
-      *reinterpret_cast<uint4*>(&dOs[r * LDQ + 8 * cc]) = rd;
+      *reinterpret_cast<uint4*>(&Qs[TL::off(r, cc)]) = rq;
+      *reinterpret_cast<uint4*>(&dOs[TL::off(r, cc)]) = rd;
     }
     if (tid < BQ) {
       const bool rv = row0 + tid < row1;
@@ -396,8 +387,8 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
       for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(&Qs[(32 * qs + n) * LDQ + 16 * ks + 8 * hh]);
-        const bf16x8 ad = *reinterpret_cast<const bf16x8*>(&dOs[(32 * qs + n) * LDQ + 16 * ks + 8 * hh]);
+        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(&Qs[TL::off(32 * qs + n, 2 * ks + hh)]);
+        const bf16x8 ad = *reinterpret_cast<const bf16x8*>(&dOs[TL::off(32 * qs + n, 2 * ks + hh)]);
         sacc = mfma32(aq, kreg[ks], sacc);
         dpacc = mfma32(ad, vreg[ks], dpacc);
       }
@@ -424,12 +415,10 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
       // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this sub-block)
 #pragma unroll
       for (int c = 0; c < 2; c++) {
-        const int r0 = 32 * qs + 16 * c + 4 * hh + (l16 >> 2);
 #pragma unroll
         for (int cb = 0; cb < CB; cb++) {
-          const int off = r0 * LDQ + 32 * cb + 16 * b16 + 4 * (l16 & 3);
-          dvacc[cb] = mfma32(tr_frag(&dOs[off], LDQ), pb[c], dvacc[cb]);
-          dkacc[cb] = mfma32(tr_frag(&Qs[off], LDQ), dsb[c], dkacc[cb]);
+          dvacc[cb] = mfma32(tr_frag<D>(dOs, 32 * qs + 16 * c, cb, l), pb[c], dvacc[cb]);
+          dkacc[cb] = mfma32(tr_frag<D>(Qs, 32 * qs + 16 * c, cb, l), dsb[c], dkacc[cb]);
         }
       }
     }

@@ -137,6 +137,37 @@ __device__ __forceinline__ s16x4 lds_read_tr(const void* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
+// LDS layout of a row-major bf16 tile with D channels per row, addressed in 16-byte chunks.
+// D = 128: rows are 256 bytes (one pass over all LDS banks) and chunk c of row r is stored at chunk
+// position c ^ f(r), f(r) = 4 * (r % 4) + (r / 4) % 4.  Sixteen consecutive rows then put the same
+// chunk in sixteen different positions (conflict-free 16-byte row reads), and four consecutive rows
+// put a 64-byte channel group in four different 64-byte bank groups (conflict-free transposing
+// reads).  D = 64: plain rows padded by 16 bytes.
+template <int D> struct TileLayout;
+template <> struct TileLayout<128> {
+  static constexpr int LD = 128;
+  static __device__ __forceinline__ int off(int r, int c) {
+    return r * 128 + ((c ^ (((r & 3) << 2) | ((r >> 2) & 3))) << 3);
+  }
+};
+template <> struct TileLayout<64> {
+  static constexpr int LD = 72;
+  static __device__ __forceinline__ int off(int r, int c) { return r * 72 + (c << 3); }
+};
+
+// A-operand fragment of the TRANSPOSE of a row-major LDS tile: for lane (n = l % 32, hh = l / 32),
+// element e of the result is tile[rowbase + 4*hh + (e % 4) + 8*(e / 4)][32*cb + n].
+template <int D>
+__device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int rowbase, int cb, int l) {
+  const int l16 = l & 15, b16 = (l >> 4) & 1, hh = l >> 5;
+  const int r = rowbase + 4 * hh + (l16 >> 2);
+  const int c = 4 * cb + 2 * b16 + ((l16 & 3) >> 1);
+  const int sub = 4 * (l16 & 1);
+  const s16x4 lo = lds_read_tr(tile + TileLayout<D>::off(r, c) + sub);
+  const s16x4 hi = lds_read_tr(tile + TileLayout<D>::off(r + 8, c) + sub);
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }

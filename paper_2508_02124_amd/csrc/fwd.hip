@@ -30,7 +30,8 @@ struct FwdArgs {
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
-  constexpr int LDK = D + 8;      // LDS row stride in elements (16 bytes of padding)
+  using TL = TileLayout<D>;
+  constexpr int LDK = TL::LD;     // LDS row stride in elements
   constexpr int KS = D / 16;      // contraction steps of K Q^T
   constexpr int CB = D / 32;      // 32-channel blocks of O^T
   constexpr int CPR = D / 8;      // 16-byte chunks per row
@@ -123,8 +124,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
 #pragma unroll
     for (int it = 0; it < NCH; it++) {
       const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
-      *reinterpret_cast<uint4*>(&Ks[r * LDK + 8 * col]) = kst[it];
-      *reinterpret_cast<uint4*>(&Vs[r * LDK + 8 * col]) = vst[it];
+      *reinterpret_cast<uint4*>(&Ks[TL::off(r, col)]) = kst[it];
+      *reinterpret_cast<uint4*>(&Vs[TL::off(r, col)]) = vst[it];
     }
     if (tid < KT) {
       zs[tid] = z_st;
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
       for (int v = 0; v < 16; v++) sacc[kb][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + n) * LDK + 16 * ks + 8 * hh]);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
         sacc[kb] = mfma32(a, qreg[ks], sacc[kb]);
       }
     }
@@ -196,21 +197,13 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
     }
 
     // O^T += V^T P^T
-    const int l16 = l & 15, b16 = (l >> 4) & 1;
 #pragma unroll
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-      for (int c = 0; c < 2; c++) {
-        const int r0 = 32 * kb + 16 * c + 4 * hh + (l16 >> 2);
+      for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++) {
-          const uint16_t* ap = &Vs[r0 * LDK + 32 * cb + 16 * b16 + 4 * (l16 & 3)];
-          const s16x4 lo = lds_read_tr(ap);
-          const s16x4 hi = lds_read_tr(ap + 8 * LDK);
-          const s16x8 a8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[cb] = mfma32(__builtin_bit_cast(bf16x8, a8), pb[kb][c], oacc[cb]);
-        }
-      }
+        for (int cb = 0; cb < CB; cb++)
+          oacc[cb] = mfma32(tr_frag<D>(Vs, 32 * kb + 16 * c, cb, l), pb[kb][c], oacc[cb]);
   }
 
   // epilogue: normalise, stage O through LDS for coalesced rows, write LSE
@@ -226,7 +219,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
       bf16x4 o4;
 #pragma unroll
       for (int u = 0; u < 4; u++) o4[u] = (__bf16)(oacc[cb][4 * gq + u] * inv);
-      *reinterpret_cast<bf16x4*>(&Os[(32 * w + n) * LDK + 32 * cb + 8 * gq + 4 * hh]) = o4;
+      *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
     }
   __syncthreads();
 #pragma unroll
@@ -234,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
     const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
     if (row0 + r < row1)
       *reinterpret_cast<uint4*>(p.O + ((size_t)(row0 + r) * p.H_q + h) * D + 8 * col) =
-          *reinterpret_cast<const uint4*>(&Os[r * LDK + 8 * col]);
+          *reinterpret_cast<const uint4*>(&Os[TL::off(r, col)]);
   }
 }
 
