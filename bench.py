@@ -148,7 +148,7 @@ def main():
     # dominant kernel and its algorithmic FLOPs per launch (per kept pair: forward 4d = S and PV;
     # dQ kernel 6d = S, dP, dQ; key-stationary kernel 8d = S, dP, dV, dK on the pairs of its launch)
     eg = case.host("expiry").astype(np.int64)
-    BQ = 128
+    BQ = 256
     clean_pairs = 0
     for a, b in zip(inp.cu_seqlens[:-1], inp.cu_seqlens[1:]):
         a, b = int(a), int(b)

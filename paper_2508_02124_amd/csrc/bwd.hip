@@ -2,20 +2,21 @@
 //
 // Two kernels share the work so that no accumulator is spread over workgroups at tile granularity:
 //
-//  * dq_kernel, query-stationary (the forward's structure): per block of BQ rows it recomputes
-//    S^T and dP^T on the gathered key tiles, forms dS^T = P^T o (dP^T - D) and accumulates
-//    dQ^T += K^T dS^T in registers.  It also produces D for the other kernel.
+//  * dq_kernel, query-stationary (the forward's structure and copy ring): per block of BQ rows it
+//    recomputes S^T and dP^T on the gathered key tiles, forms dS^T = P^T o (dP^T - D) and
+//    accumulates dQ^T += K^T dS^T in registers.  It also produces D and LSE * log2(e) for the
+//    other kernel.
 //
 //  * dkv_kernel, key-stationary: a workgroup owns SG slot columns of one head and sweeps query
-//    blocks.  A slot column always holds one resident key, so its tiles are dense and need no
-//    mask; K and V fragments of the resident stay in registers together with the dK^T, dV^T and dz
-//    accumulators.  When the resident of a column changes, the finished key is flushed with a
-//    handful of fp32 atomics (dK and dV are shared by the q-heads of a group) and the column is
-//    re-armed.  The same kernel, in "partial" mode, handles the keys that enter or expire inside a
-//    block: columns come from the block's partial list, elements are masked with j <= i < e_j, and
-//    the sweep is that single block.
+//    blocks in steps of 32 rows, fed by a ring of asynchronous Q / dO copies.  A slot column always
+//    holds one resident key, so its tiles are dense and need no mask; K and V fragments of the
+//    resident stay in registers together with the dK^T, dV^T and dz accumulators.  When the
+//    resident of a column changes, the finished key is flushed with a handful of fp32 atomics (dK
+//    and dV are shared by the q-heads of a group) and the column is re-armed.  The same kernel, in
+//    "partial" mode, handles the keys that enter or expire inside a block: columns come from the
+//    block's partial list, elements are masked with j <= i < e_j, and the sweep is that one block.
 //
-// The dS/P blocks are produced in the accumulator layout of S = Q K^T (dkv) or S^T = K Q^T (dq),
+// The dS / P blocks are produced in the accumulator layout of S = Q K^T (dkv) or S^T = K Q^T (dq),
 // which is exactly the B-operand layout of the products that consume them; the other operand of
 // those products is read from row-major LDS tiles with transposing LDS reads.
 #include "common.h"
@@ -25,29 +26,30 @@ namespace dma {
 struct BwdArgs {
   const uint16_t *Q, *K, *V, *O, *dO;
   uint16_t* dQ;
-  const float *z, *LSE;
-  float *Dws, *dK32, *dV32, *dz;
+  const float *z2, *LSE;
+  float *Dws, *L2ws, *dK32, *dV32, *dz;
   const int32_t* expiry;
   const int4* blk;
   const int32_t* slot_tab;
   const int32_t* pcnt;
   const int32_t* plist;
+  const char* consts;  // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1; +268: float +inf
   int T, H_q, H_kv, k, nblk_cap, kpad;
   int seg;  // query blocks swept by one clean-mode work item of dkv_kernel
   float scale, c2;
 };
 
-// ------------------------------------------------------------------ dQ (and D)
+// ------------------------------------------------------------------ dQ (and D, LSE * log2 e)
 template <int D>
-__global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
+__global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
-  constexpr int LDK = TL::LD, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = KT * CPR / 256;
-  __shared__ __align__(16) uint16_t smem[2 * KT * LDK];
-  __shared__ __align__(16) float zs[KT];
-  __shared__ __align__(16) int js[KT];
-  __shared__ __align__(16) int es[KT];
-  uint16_t* Ks = smem;
-  uint16_t* Vs = smem + KT * LDK;
+  constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, WL = KT / RPL / 4;
+  constexpr int NS = 4, TILE = KT * D;
+  __shared__ __align__(16) uint16_t ringK[NS * TILE];
+  __shared__ __align__(16) uint16_t ringV[NS * TILE];
+  __shared__ __align__(16) int ids_ring[2 * NS][KT];
+  __shared__ __align__(16) float z_ring[NS][KT];
+  __shared__ __align__(16) int e_ring[NS][KT];
 
   int h, item;
   if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
@@ -56,22 +58,81 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
   if (info.x < 0) return;
   const int row0 = info.y, row1 = info.z, doc0 = info.w;
   const int g = h / (p.H_q / p.H_kv);
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int ncol = min(p.k, row0 - doc0);
   const int nc = (ncol + KT - 1) / KT;
   const int np_keys = p.pcnt[(size_t)h * p.nblk_cap + bi];
   const int nt = nc + (np_keys + KT - 1) / KT;
   const int32_t* slot_row = p.slot_tab + ((size_t)h * p.nblk_cap + bi) * p.kpad;
   const int32_t* plist_row = p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART;
-  const float* zh = p.z + (size_t)h * p.T;
+  const float* z2h = p.z2 + (size_t)h * p.T;
   const int32_t* eh = p.expiry + (size_t)h * p.T;
+  const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
+  const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
+  const int32_t* c_zero = reinterpret_cast<const int32_t*>(p.consts + 260);
+  const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
 
-  const int qi = row0 + 32 * w + n;
-  const bool qvalid = qi < row1;
-  bf16x8 qreg[KS], doreg[KS];
-  float Dsum = 0.f;
-  {
-    const size_t off = ((size_t)qi * p.H_q + h) * D + 8 * hh;
+  auto issue_ids = [&](int tt) {
+    if (w == 0) {
+      const int32_t* src = c_m1;
+      if (tt < nc) {
+        src = slot_row + tt * KT + l;
+      } else if (tt < nt) {
+        const int q = (tt - nc) * KT + l;
+        if (q < np_keys) src = plist_row + q;
+      }
+      dma4(src, &ids_ring[tt % (2 * NS)][0]);
+    }
+  };
+  auto issue_kv = [&](int tt) {
+    const int* idr = ids_ring[tt % (2 * NS)];
+    uint16_t* kd = ringK + (tt % NS) * TILE;
+    uint16_t* vd = ringV + (tt % NS) * TILE;
+#pragma unroll
+    for (int j = 0; j < WL; j++) {
+      const int rbase = (w * WL + j) * RPL;
+      const int r = rbase + l / CPR;
+      const int c = (l % CPR) ^ TL::swz(r);
+      const int id = idr[r];
+      const uint16_t* ks = zero_row + 8 * c;
+      const uint16_t* vs = ks;
+      if (id >= 0) {
+        const size_t off = ((size_t)id * p.H_kv + g) * D + 8 * c;
+        ks = p.K + off;
+        vs = p.V + off;
+      }
+      dma16(ks, kd + rbase * D);
+      dma16(vs, vd + rbase * D);
+    }
+    if (w == 1) {
+      const int id = idr[l];
+      dma4(id >= 0 ? z2h + id : c_ninf, &z_ring[tt % NS][0]);
+      dma4(id >= 0 ? (const void*)(eh + id) : (const void*)c_zero, &e_ring[tt % NS][0]);
+    }
+  };
+  auto wait_tile = [&]() {
+    if (w == 0) wait_vmcnt<(NS - 2) * (2 * WL + 1)>();
+    else if (w == 1) wait_vmcnt<(NS - 2) * (2 * WL + 2)>();
+    else wait_vmcnt<(NS - 2) * (2 * WL)>();
+  };
+
+  for (int tt = 0; tt < NS - 1; tt++) issue_ids(tt);
+  wait_vmcnt<0>();
+  lds_barrier();
+  for (int i = 0; i < NS - 1; i++) {
+    issue_ids(NS - 1 + i);
+    issue_kv(i);
+  }
+
+  int qi[2];
+  bf16x8 qreg[2][KS], doreg[2][KS];
+  float Dsum[2], lse2[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+    qi[qb] = row0 + 64 * w + 32 * qb + n;
+    const bool qvalid = qi[qb] < row1;
+    const size_t off = ((size_t)qi[qb] * p.H_q + h) * D + 8 * hh;
+    float ds = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       uint4 rq = make_uint4(0, 0, 0, 0), rd = rq, ro = rq;
@@ -80,95 +141,58 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
         rd = *reinterpret_cast<const uint4*>(p.dO + off + 16 * ks);
         ro = *reinterpret_cast<const uint4*>(p.O + off + 16 * ks);
       }
-      qreg[ks] = __builtin_bit_cast(bf16x8, rq);
-      doreg[ks] = __builtin_bit_cast(bf16x8, rd);
+      qreg[qb][ks] = __builtin_bit_cast(bf16x8, rq);
+      doreg[qb][ks] = __builtin_bit_cast(bf16x8, rd);
       const bf16x8 ov = __builtin_bit_cast(bf16x8, ro);
 #pragma unroll
-      for (int e = 0; e < 8; e++) Dsum = fmaf((float)doreg[ks][e], (float)ov[e], Dsum);
+      for (int e = 0; e < 8; e++) ds = fmaf((float)doreg[qb][ks][e], (float)ov[e], ds);
+    }
+    ds += __shfl_xor(ds, 32);
+    Dsum[qb] = ds;
+    lse2[qb] = qvalid ? p.LSE[(size_t)h * p.T + qi[qb]] * LOG2E : INFINITY;
+    if (qvalid && hh == 0) {
+      p.Dws[(size_t)h * p.T + qi[qb]] = ds;
+      p.L2ws[(size_t)h * p.T + qi[qb]] = lse2[qb];
     }
   }
-  Dsum += __shfl_xor(Dsum, 32);
-  const float lse2 = qvalid ? p.LSE[(size_t)h * p.T + qi] * LOG2E : INFINITY;
-  if (qvalid && hh == 0) p.Dws[(size_t)h * p.T + qi] = Dsum;
+  f32x16 dqacc[2][CB];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) dqacc[qb][cb][v] = 0.f;
+  wait_vmcnt<0>();  // the ordinary loads and stores above; from here on only copies are in flight
 
-  f32x16 dqacc[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-    for (int v = 0; v < 16; v++) dqacc[cb][v] = 0.f;
-
-  uint4 kst[NCH], vst[NCH];
-  float z_st = 0.f;
-  int j_st = 0, e_st = 0;
-  int idn[NCH], idz = -1;  // key ids of the tile about to be loaded (rows of this thread's chunks; row tid)
-  auto tile_id = [&](int t, int r) -> int {
-    if (t >= nt) return -1;
-    if (t < nc) return slot_row[t * KT + r];
-    const int q = (t - nc) * KT + r;
-    return q < np_keys ? plist_row[q] : -1;
-  };
-  auto load_ids = [&](int t) {
-#pragma unroll
-    for (int it = 0; it < NCH; it++) idn[it] = tile_id(t, (tid + 256 * it) / CPR);
-    if (tid < KT) idz = tile_id(t, tid);
-  };
-  auto load_tile = [&]() {  // gathers the tile whose ids are in idn / idz
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int col = (tid + 256 * it) % CPR;
-      const int id = idn[it];
-      kst[it] = make_uint4(0, 0, 0, 0);
-      vst[it] = make_uint4(0, 0, 0, 0);
-      if (id >= 0) {
-        const size_t off = ((size_t)id * p.H_kv + g) * D + 8 * col;
-        kst[it] = *reinterpret_cast<const uint4*>(p.K + off);
-        vst[it] = *reinterpret_cast<const uint4*>(p.V + off);
-      }
-    }
-    if (tid < KT) {
-      const int id = idz;
-      z_st = id >= 0 ? zh[id] * LOG2E : -INFINITY;
-      j_st = id >= 0 ? id : 0x7fffffff;
-      e_st = id >= 0 ? eh[id] : 0;
-    }
-  };
-
-  load_ids(0);
-  load_tile();
-  load_ids(1);
   for (int t = 0; t < nt; t++) {
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
-      *reinterpret_cast<uint4*>(&Ks[TL::off(r, col)]) = kst[it];
-      *reinterpret_cast<uint4*>(&Vs[TL::off(r, col)]) = vst[it];
-    }
-    if (tid < KT) {
-      zs[tid] = z_st;
-      js[tid] = j_st;
-      es[tid] = e_st;
-    }
-    __syncthreads();
-    if (t + 1 < nt) {
-      load_tile();
-      load_ids(t + 2);
-    }
+    if (t > 0) wait_tile();
+    lds_barrier();
+    issue_ids(t + 2 * NS - 2);
+    issue_kv(t + NS - 1);
+    const uint16_t* Ks = ringK + (t % NS) * TILE;
+    const uint16_t* Vs = ringV + (t % NS) * TILE;
+    const float* zs = z_ring[t % NS];
+    const int* js = ids_ring[t % (2 * NS)];
+    const int* es = e_ring[t % NS];
     const bool masked = t >= nc;
 
 #pragma unroll 1
     for (int kb = 0; kb < 2; kb++) {
-      bf16x8 dsb[2];
+      bf16x8 dsb[2][2];  // [qb][16-key half]
       {
-        f32x16 sacc, dpacc;
+        f32x16 sacc[2], dpacc[2];
 #pragma unroll
-        for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
+        for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) { sacc[qb][v] = 0.f; dpacc[qb][v] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
           const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
           const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[TL::off(32 * kb + n, 2 * ks + hh)]);
-          sacc = mfma32(ak, qreg[ks], sacc);
-          dpacc = mfma32(av, doreg[ks], dpacc);
+          sacc[0] = mfma32(ak, qreg[0][ks], sacc[0]);
+          sacc[1] = mfma32(ak, qreg[1][ks], sacc[1]);
+          dpacc[0] = mfma32(av, doreg[0][ks], dpacc[0]);
+          dpacc[1] = mfma32(av, doreg[1][ks], dpacc[1]);
         }
 #pragma unroll
         for (int gq = 0; gq < 4; gq++) {
@@ -182,37 +206,46 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
             ev[0] = ee.x; ev[1] = ee.y; ev[2] = ee.z; ev[3] = ee.w;
           }
 #pragma unroll
-          for (int u = 0; u < 4; u++) {
-            const int v = 4 * gq + u;
-            float pv = fast_exp2(fmaf(sacc[v], p.c2, zz[u]) - lse2);
-            if (masked && !(qi >= jv[u] && qi < ev[u])) pv = 0.f;
-            const float ds = pv * (dpacc[v] - Dsum);
-            dsb[v >> 3][v & 7] = (__bf16)ds;
-          }
+          for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+              const int v = 4 * gq + u;
+              float pv = fast_exp2(fmaf(sacc[qb][v], p.c2, zz[u]) - lse2[qb]);
+              const bool ok = !masked | ((jv[u] >= 0) & (qi[qb] >= jv[u]) & (qi[qb] < ev[u]));
+              pv = ok ? pv : 0.f;
+              const float ds = pv * (dpacc[qb][v] - Dsum[qb]);
+              dsb[qb][v >> 3][v & 7] = (__bf16)ds;
+            }
         }
       }
       // dQ^T += K^T dS^T for this half of the tile
 #pragma unroll
-      for (int c = 0; c < 2; c++) {
+      for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++)
-          dqacc[cb] = mfma32(tr_frag<D>(Ks, 32 * kb + 16 * c, cb, l), dsb[c], dqacc[cb]);
-      }
+        for (int cb = 0; cb < CB; cb++) {
+          const bf16x8 a = tr_frag<D>(Ks, 32 * kb + 16 * c, cb, l);
+          dqacc[0][cb] = mfma32(a, dsb[0][c], dqacc[0][cb]);
+          dqacc[1][cb] = mfma32(a, dsb[1][c], dqacc[1][cb]);
+        }
     }
   }
 
-  __syncthreads();
-  uint16_t* Os = smem;  // [BQ][LDK]
+  wait_vmcnt<0>();
+  lds_barrier();
+  uint16_t* Os = ringK;  // [BQ][D] staging with the tile swizzle
+  static_assert(NS * KT == BQ, "dQ staging aliases the K ring");
 #pragma unroll
-  for (int cb = 0; cb < CB; cb++)
+  for (int qb = 0; qb < 2; qb++)
 #pragma unroll
-    for (int gq = 0; gq < 4; gq++) {
-      bf16x4 o4;
+    for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-      for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[cb][4 * gq + u] * p.scale);
-      *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
-    }
-  __syncthreads();
+      for (int gq = 0; gq < 4; gq++) {
+        bf16x4 o4;
+#pragma unroll
+        for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[qb][cb][4 * gq + u] * p.scale);
+        *reinterpret_cast<bf16x4*>(&Os[TL::off(64 * w + 32 * qb + n, 4 * cb + gq) + 4 * hh]) = o4;
+      }
+  lds_barrier();
 #pragma unroll
   for (int it = 0; it < BQ * CPR / 256; it++) {
     const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
@@ -226,14 +259,20 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(BwdArgs p) {
 // Lane (n, hh) of wave w owns column 32w + n of the workgroup's SG columns; its accumulators hold
 // channels 32cb + 8gq + 4hh + u of dK^T / dV^T for that column's key.
 template <int D, bool PARTIAL>
-__global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
+__global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
-  constexpr int LDQ = TL::LD, KS = D / 16, CB = D / 32, CPR = D / 8, NCH = BQ * CPR / 256;
-  __shared__ __align__(16) uint16_t Qs[BQ * LDQ];
-  __shared__ __align__(16) uint16_t dOs[BQ * LDQ];
-  __shared__ __align__(16) float lses[BQ];
-  __shared__ __align__(16) float Dss[BQ];
+  constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR;
+  constexpr int SUB = 32;                 // query rows per pipeline step
+  constexpr int NSUB = BQ / SUB;          // steps per query block
+  constexpr int WLQ = SUB / RPL / 4;      // 16-byte wave copies per wave per Q (or dO) step tile
+  constexpr int NS = 5;                   // ring stages
+  constexpr int STILE = SUB * D;
   constexpr int LDS_ST = D + 4;
+  static_assert(WLQ >= 1, "tile too small for four waves");
+  __shared__ __align__(16) uint16_t ringQ[NS * STILE];
+  __shared__ __align__(16) uint16_t ringdO[NS * STILE];
+  __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) D
+  __shared__ __align__(16) int idbuf[2][SG];     // column ids of the current / next block
   __shared__ __align__(16) float stage_all[4 * 32 * LDS_ST];  // per wave: [32 columns][D] fp32, flush staging
 
   // item = chunk * ngrp + group: the groups of one (head, chunk) run side by side and share Q / dO
@@ -243,9 +282,14 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
   if (!xcd_map(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
   const int chunk = item / ngrp, grp = item - chunk * ngrp;
   const int g = h / (p.H_q / p.H_kv);
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
-  const int col = grp * SG + 32 * w + n;
-  const float* zh = p.z + (size_t)h * p.T;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
+  const float* z2h = p.z2 + (size_t)h * p.T;
+  const float* Dh = p.Dws + (size_t)h * p.T;
+  const float* L2h = p.L2ws + (size_t)h * p.T;
+  const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
+  const float* c_zero_f = reinterpret_cast<const float*>(p.consts + 260);
+  const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
+  const float* c_pinf = reinterpret_cast<const float*>(p.consts + 268);
 
   int bi_begin, bi_end;
   if (PARTIAL) {
@@ -255,6 +299,67 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
     bi_begin = chunk * p.seg;
     bi_end = min(bi_begin + p.seg, p.nblk_cap);
   }
+  // (workgroup-uniform) does block bi have any column for this group?
+  auto block_cols = [&](int bi, const int4& info) -> int {
+    if (info.x < 0) return 0;
+    const int total = PARTIAL ? p.pcnt[(size_t)h * p.nblk_cap + bi] : min(p.k, info.y - info.w);
+    return max(0, min(SG, total - grp * SG));
+  };
+  if (PARTIAL) {
+    const int4 info = p.blk[bi_begin];
+    if (block_cols(bi_begin, info) == 0) return;
+  } else {
+    // skip leading blocks that have nothing resident in this group's columns
+    while (bi_begin < bi_end) {
+      const int4 info = p.blk[bi_begin];
+      if (info.x < 0) return;
+      if (block_cols(bi_begin, info) > 0) break;
+      bi_begin++;
+    }
+    if (bi_begin >= bi_end) return;
+  }
+  const int nsteps = (bi_end - bi_begin) * NSUB;
+
+  // ---- producer: copies of step v (32 query rows of Q and dO, their LSE/D, and at a block's first
+  // step the block's column ids).  Steps past the end or of blocks without columns copy dummies.
+  auto issue = [&](int v) {
+    const int bi = bi_begin + v / NSUB, qs = v % NSUB;
+    int4 info = make_int4(-1, 0, 0, 0);
+    if (bi < bi_end) info = p.blk[bi];
+    const int ncols = block_cols(bi, info);
+    const int st = v % NS;
+#pragma unroll
+    for (int j = 0; j < WLQ; j++) {
+      const int rbase = (w * WLQ + j) * RPL;
+      const int r = rbase + l / CPR;
+      const int c = (l % CPR) ^ TL::swz(r);
+      const int row = info.y + SUB * qs + r;
+      const uint16_t* sq = zero_row + 8 * c;
+      const uint16_t* sd = sq;
+      if (ncols > 0 && row < info.z) {
+        const size_t off = ((size_t)row * p.H_q + h) * D + 8 * c;
+        sq = p.Q + off;
+        sd = p.dO + off;
+      }
+      dma16(sq, ringQ + st * STILE + rbase * D);
+      dma16(sd, ringdO + st * STILE + rbase * D);
+    }
+    if (w == 0) {
+      const int row = info.y + SUB * qs + n;
+      const bool ok = ncols > 0 && row < info.z;
+      const float* src = hh == 0 ? (ok ? L2h + row : c_pinf) : (ok ? Dh + row : c_zero_f);
+      dma4(src, &meta[st][0]);
+    }
+    if (qs == 0 && (w == 1 || w == 2)) {
+      const int cl = (w - 1) * 64 + l;
+      const int32_t* src = c_m1;
+      if (cl < ncols) {
+        src = PARTIAL ? p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART + grp * SG + cl
+                      : p.slot_tab + ((size_t)h * p.nblk_cap + bi) * p.kpad + grp * SG + cl;
+      }
+      dma4(src, &idbuf[(v / NSUB) & 1][(w - 1) * 64]);
+    }
+  };
 
   int curid = -1, kj = 0x7fffffff, ke = 0;
   float z2 = -INFINITY;
@@ -308,121 +413,106 @@ __global__ __launch_bounds__(256) void dkv_kernel(BwdArgs p) {
     }
   };
 
-  for (int bi = bi_begin; bi < bi_end; bi++) {
+  for (int v = 0; v < NS - 1; v++) issue(v);
+
+  for (int v = 0; v < nsteps; v++) {
+    // copies of step v must have landed: at most NS-2 later steps' worth may still be in flight
+    // (the occasional id copies and the flush traffic only make this wait more conservative)
+    if (w == 0) wait_vmcnt<(NS - 2) * (2 * WLQ + 1)>();
+    else wait_vmcnt<(NS - 2) * (2 * WLQ)>();
+    lds_barrier();
+    issue(v + NS - 1);
+
+    const int bi = bi_begin + v / NSUB, qs = v % NSUB;
     const int4 info = p.blk[bi];
-    if (info.x < 0) break;
+    const int ncols = block_cols(bi, info);
     const int row0 = info.y, row1 = info.z;
-    int newid = -1;
-    if (PARTIAL) {
-      const int np_keys = p.pcnt[(size_t)h * p.nblk_cap + bi];
-      if (grp * SG >= np_keys) return;
-      if (col < np_keys) newid = p.plist[((size_t)h * p.nblk_cap + bi) * MAXPART + col];
-    } else {
-      const int ncol = min(p.k, row0 - info.w);
-      if (col < ncol) newid = p.slot_tab[((size_t)h * p.nblk_cap + bi) * p.kpad + col];
-    }
-    const bool changed = newid != curid;
-    if (__any(changed)) {
-      flush(changed);  // finished keys out, then re-arm the changed columns
-      if (changed) {
+    if (qs == 0) {
+      const int cl = 32 * w + n;
+      const int newid = (cl < ncols) ? idbuf[(v / NSUB) & 1][cl] : -1;
+      const bool changed = newid != curid;
+      if (__any(changed)) {
+        flush(changed);  // finished keys out, then re-arm the changed columns
+        if (changed) {
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++)
+          for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-          for (int v = 0; v < 16; v++) { dkacc[cb][v] = 0.f; dvacc[cb][v] = 0.f; }
-        dzacc = 0.f;
-        curid = newid;
-        if (newid >= 0) {
-          const size_t off = ((size_t)newid * p.H_kv + g) * D + 8 * hh;
+            for (int vv = 0; vv < 16; vv++) { dkacc[cb][vv] = 0.f; dvacc[cb][vv] = 0.f; }
+          dzacc = 0.f;
+          curid = newid;
+          if (newid >= 0) {
+            const size_t off = ((size_t)newid * p.H_kv + g) * D + 8 * hh;
 #pragma unroll
-          for (int ks = 0; ks < KS; ks++) {
-            kreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.K + off + 16 * ks));
-            vreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.V + off + 16 * ks));
+            for (int ks = 0; ks < KS; ks++) {
+              kreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.K + off + 16 * ks));
+              vreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.V + off + 16 * ks));
+            }
+            z2 = z2h[newid];
+            if (PARTIAL) {
+              kj = newid;
+              ke = p.expiry[(size_t)h * p.T + newid];
+            }
+          } else {
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+              kreg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+              vreg[ks] = kreg[ks];
+            }
+            z2 = -INFINITY;
+            kj = 0x7fffffff;
+            ke = 0;
           }
-          z2 = zh[newid] * LOG2E;
-          if (PARTIAL) {
-            kj = newid;
-            ke = p.expiry[(size_t)h * p.T + newid];
-          }
-        } else {
-#pragma unroll
-          for (int ks = 0; ks < KS; ks++) {
-            kreg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-            vreg[ks] = kreg[ks];
-          }
-          z2 = -INFINITY;
-          kj = 0x7fffffff;
-          ke = 0;
         }
       }
     }
-    if (!PARTIAL) {
-      // nothing resident in this group's columns for this block: skip the tile (workgroup-uniform)
-      if (min(p.k, row0 - info.w) <= grp * SG) continue;
-    }
+    if (ncols == 0 || row0 + SUB * qs >= row1) continue;  // workgroup-uniform: nothing to do this step
 
-    __syncthreads();  // previous block's LDS reads are done
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int c = tid + 256 * it, r = c / CPR, cc = c % CPR;
-      uint4 rq = make_uint4(0, 0, 0, 0), rd = rq;
-      if (row0 + r < row1) {
-        const size_t off = ((size_t)(row0 + r) * p.H_q + h) * D + 8 * cc;
-        rq = *reinterpret_cast<const uint4*>(p.Q + off);
-        rd = *reinterpret_cast<const uint4*>(p.dO + off);
-      }
-      *reinterpret_cast<uint4*>(&Qs[TL::off(r, cc)]) = rq;
-      *reinterpret_cast<uint4*>(&dOs[TL::off(r, cc)]) = rd;
-    }
-    if (tid < BQ) {
-      const bool rv = row0 + tid < row1;
-      lses[tid] = rv ? p.LSE[(size_t)h * p.T + row0 + tid] * LOG2E : INFINITY;
-      Dss[tid] = rv ? p.Dws[(size_t)h * p.T + row0 + tid] : 0.f;
-    }
-    __syncthreads();
+    const int st = v % NS;
+    const uint16_t* Qs = ringQ + st * STILE;
+    const uint16_t* dOs = ringdO + st * STILE;
+    const float* lses = meta[st];
+    const float* Dss = meta[st] + 32;
 
-#pragma unroll 1
-    for (int qs = 0; qs < BQ / 32; qs++) {
-      f32x16 sacc, dpacc;
+    f32x16 sacc, dpacc;
 #pragma unroll
-      for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
+    for (int vv = 0; vv < 16; vv++) { sacc[vv] = 0.f; dpacc[vv] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(&Qs[TL::off(32 * qs + n, 2 * ks + hh)]);
-        const bf16x8 ad = *reinterpret_cast<const bf16x8*>(&dOs[TL::off(32 * qs + n, 2 * ks + hh)]);
-        sacc = mfma32(aq, kreg[ks], sacc);
-        dpacc = mfma32(ad, vreg[ks], dpacc);
-      }
-      bf16x8 pb[2], dsb[2];
+    for (int ks = 0; ks < KS; ks++) {
+      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(&Qs[TL::off(n, 2 * ks + hh)]);
+      const bf16x8 ad = *reinterpret_cast<const bf16x8*>(&dOs[TL::off(n, 2 * ks + hh)]);
+      sacc = mfma32(aq, kreg[ks], sacc);
+      dpacc = mfma32(ad, vreg[ks], dpacc);
+    }
+    bf16x8 pb[2], dsb[2];
 #pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        const int r = 32 * qs + 8 * gq + 4 * hh;
-        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lses[r]);
-        const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
+    for (int gq = 0; gq < 4; gq++) {
+      const int r = 8 * gq + 4 * hh;
+      const f32x4 ls = *reinterpret_cast<const f32x4*>(&lses[r]);
+      const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-          const int v = 4 * gq + u;
-          float pv = fast_exp2(fmaf(sacc[v], p.c2, z2) - ls[u]);
-          if (PARTIAL) {
-            const int row = row0 + r + u;
-            if (!(row >= kj && row < ke)) pv = 0.f;
-          }
-          const float ds = pv * (dpacc[v] - dd[u]);
-          dzacc += ds;
-          pb[v >> 3][v & 7] = (__bf16)pv;
-          dsb[v >> 3][v & 7] = (__bf16)ds;
+      for (int u = 0; u < 4; u++) {
+        const int vv = 4 * gq + u;
+        float pv = fast_exp2(fmaf(sacc[vv], p.c2, z2) - ls[u]);
+        if (PARTIAL) {
+          const int row = row0 + SUB * qs + r + u;
+          pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
         }
-      }
-      // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this sub-block)
-#pragma unroll
-      for (int c = 0; c < 2; c++) {
-#pragma unroll
-        for (int cb = 0; cb < CB; cb++) {
-          dvacc[cb] = mfma32(tr_frag<D>(dOs, 32 * qs + 16 * c, cb, l), pb[c], dvacc[cb]);
-          dkacc[cb] = mfma32(tr_frag<D>(Qs, 32 * qs + 16 * c, cb, l), dsb[c], dkacc[cb]);
-        }
+        const float ds = pv * (dpacc[vv] - dd[u]);
+        dzacc += ds;
+        pb[vv >> 3][vv & 7] = (__bf16)pv;
+        dsb[vv >> 3][vv & 7] = (__bf16)ds;
       }
     }
+    // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this step)
+#pragma unroll
+    for (int c = 0; c < 2; c++)
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        dvacc[cb] = mfma32(tr_frag<D>(dOs, 16 * c, cb, l), pb[c], dvacc[cb]);
+        dkacc[cb] = mfma32(tr_frag<D>(Qs, 16 * c, cb, l), dsb[c], dkacc[cb]);
+      }
   }
+  wait_vmcnt<0>();
   flush(true);
 }
 
@@ -458,24 +548,27 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
                const float* LSE, const float* z, const int32_t* expiry, const int32_t* cu, void* dQ, void* dK,
                void* dV, float* dz, char* ws, hipStream_t st) {
   (void)cu;
+  (void)z;
   const dma_shape& s = p.s;
   const PlanLayout& L = p.pl;
   const WsLayout wl = ws_layout(s);
   BwdArgs a;
   a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
   a.O = (const uint16_t*)O; a.dO = (const uint16_t*)dO; a.dQ = (uint16_t*)dQ;
-  a.z = z; a.LSE = LSE; a.expiry = expiry;
-  a.Dws = (float*)(ws + wl.off_D); a.dK32 = (float*)(ws + wl.off_dK); a.dV32 = (float*)(ws + wl.off_dV); a.dz = dz;
+  a.z2 = (const float*)(p.plan + L.off_z2); a.LSE = LSE; a.expiry = expiry;
+  a.Dws = (float*)(ws + wl.off_D); a.L2ws = (float*)(ws + wl.off_L2);
+  a.dK32 = (float*)(ws + wl.off_dK); a.dV32 = (float*)(ws + wl.off_dV); a.dz = dz;
   a.blk = (const int4*)(p.plan + L.off_blk);
   a.slot_tab = (const int32_t*)(p.plan + L.off_slot);
   a.pcnt = (const int32_t*)(p.plan + L.off_pcnt);
   a.plist = (const int32_t*)(p.plan + L.off_plist);
+  a.consts = p.plan + L.off_consts;
   a.T = s.T; a.H_q = s.H_q; a.H_kv = s.H_kv; a.k = s.k; a.nblk_cap = L.nblk_cap; a.kpad = L.kpad;
   a.scale = p.scale; a.c2 = p.scale * LOG2E;
   {  // sweep length of a clean-mode work item: as long as possible while keeping >= 512 work items
     const long groups = (long)(L.kpad / SG) * s.H_q;
     long seg = (long)L.nblk_cap * groups / 512;
-    if (seg < 4) seg = 4;
+    if (seg < 2) seg = 2;
     if (seg > L.nblk_cap) seg = L.nblk_cap;
     a.seg = (int)seg;
   }

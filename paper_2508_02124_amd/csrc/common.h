@@ -8,7 +8,7 @@
 namespace dma {
 
 // ------------------------------------------------------------------ tiling constants
-constexpr int BQ = 128;        // query rows per block (one workgroup of the attention kernels)
+constexpr int BQ = 256;        // query rows per block (one workgroup of the attention kernels: 4 waves x 64 rows)
 constexpr int KT = 64;         // keys per tile of the query-stationary kernels
 constexpr int MAXPART = 2 * BQ;  // a block has at most BQ entering + BQ expiring keys
 constexpr int SG = 128;        // slot columns per workgroup of the key-stationary backward
@@ -30,6 +30,8 @@ struct PlanLayout {
   int nbits_cap;   // wavelet levels needed for the longest possible document
   int wcap;        // 64-bit words per wavelet level per head: T / 64 + 2 * n_docs
   size_t off_hdr;      // int32[16]: [0] number of blocks
+  size_t off_consts;   // 512 B: [0,256) zeros (a dummy K/V row); then float -inf, int32 0, int32 -1, float +inf
+  size_t off_z2;       // float[H_q][T]: z * log2(e), the bias in the exp2 domain of the kernels
   size_t off_blk;      // int4[nblk_cap]: {doc, row0, row1, doc_start}; doc = -1 past the end
   size_t off_docblk;   // int32[n_docs + 1]: first block of each document
   size_t off_slot;     // int32[H_q][nblk_cap][kpad]: clean resident key of each slot, or -1
@@ -64,6 +66,8 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   p.off_hdr = take(64);
+  p.off_consts = take(512);
+  p.off_z2 = take(H * T * 4);
   p.off_blk = take((size_t)p.nblk_cap * 16);
   p.off_docblk = take((size_t)(s.n_docs + 1) * 4);
   p.off_slot = take(H * p.nblk_cap * (size_t)p.kpad * 4);
@@ -82,15 +86,16 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   return p;
 }
 
-// workspace of dma_bwd: D[H_q][T] float, dK32 / dV32 [T][H_kv][d] float
+// workspace of dma_bwd: D and LSE * log2(e) [H_q][T] float, dK32 / dV32 [T][H_kv][d] float
 struct WsLayout {
-  size_t off_D, off_dK, off_dV, total;
+  size_t off_D, off_L2, off_dK, off_dV, total;
 };
 static inline WsLayout ws_layout(const dma_shape& s) {
   WsLayout w;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   w.off_D = take((size_t)s.H_q * s.T * 4);
+  w.off_L2 = take((size_t)s.H_q * s.T * 4);
   w.off_dK = take((size_t)s.T * s.H_kv * s.d * 4);
   w.off_dV = take((size_t)s.T * s.H_kv * s.d * 4);
   w.total = o;
@@ -137,23 +142,44 @@ __device__ __forceinline__ s16x4 lds_read_tr(const void* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
-// LDS layout of a row-major bf16 tile with D channels per row, addressed in 16-byte chunks.
-// D = 128: rows are 256 bytes (one pass over all LDS banks) and chunk c of row r is stored at chunk
-// position c ^ f(r), f(r) = 4 * (r % 4) + (r / 4) % 4.  Sixteen consecutive rows then put the same
-// chunk in sixteen different positions (conflict-free 16-byte row reads), and four consecutive rows
-// put a 64-byte channel group in four different 64-byte bank groups (conflict-free transposing
-// reads).  D = 64: plain rows padded by 16 bytes.
+// LDS layout of a row-major bf16 tile with D channels per row, addressed in 16-byte chunks: chunk c
+// of row r is stored at chunk position c ^ swz(r) of that row (rows are D * 2 bytes, unpadded).
+// D = 128 (256-byte rows, one pass over all LDS banks): swz(r) = 4 * (r % 4) + (r / 4) % 4.  Sixteen
+// consecutive rows put the same chunk in sixteen different positions (conflict-free 16-byte row
+// reads); four consecutive rows put a 64-byte channel group in four different 64-byte bank groups
+// (conflict-free transposing reads).  D = 64 (128-byte rows, two per bank pass):
+// swz(r) = 4 * ((r / 2) % 2) + (r / 4) % 4 gives the same two properties.
 template <int D> struct TileLayout;
 template <> struct TileLayout<128> {
-  static constexpr int LD = 128;
-  static __device__ __forceinline__ int off(int r, int c) {
-    return r * 128 + ((c ^ (((r & 3) << 2) | ((r >> 2) & 3))) << 3);
-  }
+  static __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+  static __device__ __forceinline__ int off(int r, int c) { return r * 128 + ((c ^ swz(r)) << 3); }
 };
 template <> struct TileLayout<64> {
-  static constexpr int LD = 72;
-  static __device__ __forceinline__ int off(int r, int c) { return r * 72 + (c << 3); }
+  static __device__ __forceinline__ int swz(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+  static __device__ __forceinline__ int off(int r, int c) { return r * 64 + ((c ^ swz(r)) << 3); }
 };
+
+// ---- asynchronous global -> LDS copies.  Each lane supplies its own global address; the wave's
+// 64 x 16 bytes (or 64 x 4 bytes) land contiguously at the wave-uniform LDS address.  Completion is
+// tracked by the wave's vmcnt counter, in issue order; nothing else waits for them, so the kernels
+// below count their outstanding copies explicitly and use a bare s_barrier (no implied vmcnt(0)).
+typedef __attribute__((address_space(3))) void* lds_vptr;
+typedef __attribute__((address_space(1))) const void* glb_vptr;
+__device__ __forceinline__ void dma16(const void* g, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((glb_vptr)g, (lds_vptr)lds_wave_base, 16, 0, 0);
+}
+__device__ __forceinline__ void dma4(const void* g, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((glb_vptr)g, (lds_vptr)lds_wave_base, 4, 0, 0);
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// workgroup barrier that orders LDS traffic only (the caller has waited for the copies it needs)
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 // A-operand fragment of the TRANSPOSE of a row-major LDS tile: for lane (n = l % 32, hh = l / 32),
 // element e of the result is tile[rowbase + 4*hh + (e % 4) + 8*(e / 4)][32*cb + n].

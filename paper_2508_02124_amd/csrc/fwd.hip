@@ -1,15 +1,18 @@
 // Forward pass (Eq. 5-6; online softmax of Alg. 1, query-stationary so O, l, m stay in registers).
 //
-// One workgroup = one block of BQ query rows of one head; wave w owns rows 32w .. 32w+31.  The
-// keys a block needs are gathered, KT at a time, into LDS: first the slot table row of the block
-// (residents active for every row of the block: no mask needed, empty slots carry z = -inf), then
-// the block's partial list (keys entering or expiring inside the block: masked per element with
-// j <= i < e_j).
+// One workgroup = one block of BQ = 256 query rows of one head; wave w owns rows 64w .. 64w+63 as
+// two 32-row MFMA column blocks.  The keys a block needs are gathered, KT at a time, into a ring of
+// LDS stages by asynchronous global->LDS copies issued NS-1 tiles ahead (no staging registers):
+// first the slot table row of the block (residents active for every row of the block: no mask
+// needed, empty slots carry z = -inf), then the block's partial list (keys entering or expiring
+// inside the block: masked per element with j <= i < e_j).  The key ids of a tile are themselves
+// copied into an LDS ring NS-1 tiles before the tile's K/V copies are issued, so no register ever
+// waits on a load.
 //
-// Per tile the wave computes S^T = K Q^T (keys x queries) so that each lane holds one query column:
-// the softmax statistics are per lane, and the exponentiated block is already laid out as the B
-// operand of O^T += V^T P^T.  V^T fragments come from the row-major LDS tile through transposing
-// LDS reads.
+// Per tile the wave computes S^T = K Q^T (keys x queries) so that each lane holds one query column
+// per block: the softmax statistics are per lane, and the exponentiated block is already laid out
+// as the B operand of O^T += V^T P^T.  Every K fragment and every transposed V fragment read from
+// LDS feeds two MFMAs (the wave's two query blocks).
 #include "common.h"
 
 namespace dma {
@@ -17,31 +20,33 @@ namespace dma {
 struct FwdArgs {
   const uint16_t *Q, *K, *V;
   uint16_t* O;
-  const float* z;
+  const float* z2;      // z * log2(e)
   float* LSE;
   const int32_t* expiry;
   const int4* blk;
   const int32_t* slot_tab;
   const int32_t* pcnt;
   const int32_t* plist;
+  const char* consts;   // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1
   int T, H_q, H_kv, k, nblk_cap, kpad;
   float c2;  // softmax scale * log2(e)
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
+__global__ __launch_bounds__(256, 1) void fwd_kernel(FwdArgs p) {
   using TL = TileLayout<D>;
-  constexpr int LDK = TL::LD;     // LDS row stride in elements
-  constexpr int KS = D / 16;      // contraction steps of K Q^T
-  constexpr int CB = D / 32;      // 32-channel blocks of O^T
-  constexpr int CPR = D / 8;      // 16-byte chunks per row
-  constexpr int NCH = KT * CPR / 256;  // chunks per thread per tile
-  __shared__ __align__(16) uint16_t smem[2 * KT * LDK];
-  __shared__ __align__(16) float zs[KT];
-  __shared__ __align__(16) int js[KT];
-  __shared__ __align__(16) int es[KT];
-  uint16_t* Ks = smem;
-  uint16_t* Vs = smem + KT * LDK;
+  constexpr int KS = D / 16;          // contraction steps of K Q^T
+  constexpr int CB = D / 32;          // 32-channel blocks of O^T
+  constexpr int CPR = D / 8;          // 16-byte chunks per row
+  constexpr int RPL = 64 / CPR;       // rows covered by one wave-wide 16-byte copy
+  constexpr int WL = KT / RPL / 4;    // such copies per wave per K (or V) tile
+  constexpr int NS = 4;               // ring stages
+  constexpr int TILE = KT * D;        // elements of one K or V tile
+  __shared__ __align__(16) uint16_t ringK[NS * TILE];
+  __shared__ __align__(16) uint16_t ringV[NS * TILE];
+  __shared__ __align__(16) int ids_ring[2 * NS][KT];
+  __shared__ __align__(16) float z_ring[NS][KT];
+  __shared__ __align__(16) int e_ring[NS][KT];
 
   int h, item;
   if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
@@ -50,178 +55,212 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
   if (info.x < 0) return;
   const int row0 = info.y, row1 = info.z, doc0 = info.w;
   const int g = h / (p.H_q / p.H_kv);
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int ncol = min(p.k, row0 - doc0);
   const int nc = (ncol + KT - 1) / KT;
   const int np_keys = p.pcnt[(size_t)h * p.nblk_cap + bi];
   const int nt = nc + (np_keys + KT - 1) / KT;
   const int32_t* slot_row = p.slot_tab + ((size_t)h * p.nblk_cap + bi) * p.kpad;
   const int32_t* plist_row = p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART;
-  const float* zh = p.z + (size_t)h * p.T;
+  const float* z2h = p.z2 + (size_t)h * p.T;
   const int32_t* eh = p.expiry + (size_t)h * p.T;
+  const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
+  const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
+  const int32_t* c_zero = reinterpret_cast<const int32_t*>(p.consts + 260);
+  const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
 
-  // query fragments (B operand of K Q^T): lane holds row qi, channels 16*ks + 8*hh .. +8
-  const int qi = row0 + 32 * w + n;
-  bf16x8 qreg[KS];
-  {
-    const uint16_t* qrow = p.Q + ((size_t)qi * p.H_q + h) * D + 8 * hh;
+  // ---- asynchronous producers (every wave issues the same number of copies for every tile index,
+  // real or past the end, so the outstanding-copy counts below are constants)
+  auto issue_ids = [&](int tt) {
+    if (w == 0) {
+      const int32_t* src = c_m1;
+      if (tt < nc) {
+        src = slot_row + tt * KT + l;
+      } else if (tt < nt) {
+        const int q = (tt - nc) * KT + l;
+        if (q < np_keys) src = plist_row + q;
+      }
+      dma4(src, &ids_ring[tt % (2 * NS)][0]);
+    }
+  };
+  auto issue_kv = [&](int tt) {
+    const int* idr = ids_ring[tt % (2 * NS)];
+    uint16_t* kd = ringK + (tt % NS) * TILE;
+    uint16_t* vd = ringV + (tt % NS) * TILE;
+#pragma unroll
+    for (int j = 0; j < WL; j++) {
+      const int rbase = (w * WL + j) * RPL;
+      const int r = rbase + l / CPR;
+      const int c = (l % CPR) ^ TL::swz(r);
+      const int id = idr[r];
+      const uint16_t* ks = zero_row + 8 * c;
+      const uint16_t* vs = ks;
+      if (id >= 0) {
+        const size_t off = ((size_t)id * p.H_kv + g) * D + 8 * c;
+        ks = p.K + off;
+        vs = p.V + off;
+      }
+      dma16(ks, kd + rbase * D);
+      dma16(vs, vd + rbase * D);
+    }
+    if (w == 1) {
+      const int id = idr[l];
+      dma4(id >= 0 ? z2h + id : c_ninf, &z_ring[tt % NS][0]);
+      dma4(id >= 0 ? (const void*)(eh + id) : (const void*)c_zero, &e_ring[tt % NS][0]);
+    }
+  };
+  // copies a wave issues per tile step, and how many may still be in flight when tile t is needed
+  auto wait_tile = [&]() {
+    if (w == 0) wait_vmcnt<(NS - 2) * (2 * WL + 1)>();
+    else if (w == 1) wait_vmcnt<(NS - 2) * (2 * WL + 2)>();
+    else wait_vmcnt<(NS - 2) * (2 * WL)>();
+  };
+
+  for (int tt = 0; tt < NS - 1; tt++) issue_ids(tt);
+  wait_vmcnt<0>();
+  lds_barrier();
+  for (int i = 0; i < NS - 1; i++) {
+    issue_ids(NS - 1 + i);
+    issue_kv(i);
+  }
+
+  // query fragments (B operand of K Q^T): lane holds rows qi[qb], channels 16*ks + 8*hh .. +8
+  int qi[2];
+  bf16x8 qreg[2][KS];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+    qi[qb] = row0 + 64 * w + 32 * qb + n;
+    const uint16_t* qrow = p.Q + ((size_t)qi[qb] * p.H_q + h) * D + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       uint4 raw = make_uint4(0, 0, 0, 0);
-      if (qi < row1) raw = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
-      qreg[ks] = __builtin_bit_cast(bf16x8, raw);
+      if (qi[qb] < row1) raw = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+      qreg[qb][ks] = __builtin_bit_cast(bf16x8, raw);
     }
   }
+  f32x16 oacc[2][CB];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) oacc[qb][cb][v] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
+  // the query loads above are ordinary loads issued after the prologue copies; wait for them here so
+  // that the per-tile counts below only ever see copies
+  wait_vmcnt<0>();
 
-  f32x16 oacc[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-    for (int v = 0; v < 16; v++) oacc[cb][v] = 0.f;
-  float m_run = -INFINITY, lsum = 0.f;
-
-  uint4 kst[NCH], vst[NCH];
-  float z_st = 0.f;
-  int j_st = 0, e_st = 0;
-  int idn[NCH], idz = -1;  // key ids of the tile about to be loaded (rows of this thread's chunks; row tid)
-  auto tile_id = [&](int t, int r) -> int {
-    if (t >= nt) return -1;
-    if (t < nc) return slot_row[t * KT + r];
-    const int q = (t - nc) * KT + r;
-    return q < np_keys ? plist_row[q] : -1;
-  };
-  auto load_ids = [&](int t) {
-#pragma unroll
-    for (int it = 0; it < NCH; it++) idn[it] = tile_id(t, (tid + 256 * it) / CPR);
-    if (tid < KT) idz = tile_id(t, tid);
-  };
-  auto load_tile = [&]() {  // gathers the tile whose ids are in idn / idz
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int col = (tid + 256 * it) % CPR;
-      const int id = idn[it];
-      kst[it] = make_uint4(0, 0, 0, 0);
-      vst[it] = make_uint4(0, 0, 0, 0);
-      if (id >= 0) {
-        const size_t off = ((size_t)id * p.H_kv + g) * D + 8 * col;
-        kst[it] = *reinterpret_cast<const uint4*>(p.K + off);
-        vst[it] = *reinterpret_cast<const uint4*>(p.V + off);
-      }
-    }
-    if (tid < KT) {
-      const int id = idz;
-      z_st = id >= 0 ? zh[id] * LOG2E : -INFINITY;
-      j_st = id >= 0 ? id : 0x7fffffff;
-      e_st = id >= 0 ? eh[id] : 0;
-    }
-  };
-
-  load_ids(0);
-  load_tile();
-  load_ids(1);
   for (int t = 0; t < nt; t++) {
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < NCH; it++) {
-      const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
-      *reinterpret_cast<uint4*>(&Ks[TL::off(r, col)]) = kst[it];
-      *reinterpret_cast<uint4*>(&Vs[TL::off(r, col)]) = vst[it];
-    }
-    if (tid < KT) {
-      zs[tid] = z_st;
-      js[tid] = j_st;
-      es[tid] = e_st;
-    }
-    __syncthreads();
-    if (t + 1 < nt) {
-      load_tile();
-      load_ids(t + 2);
-    }
+    if (t > 0) wait_tile();  // (t == 0: the wait above already drained everything)
+    lds_barrier();
+    issue_ids(t + 2 * NS - 2);
+    issue_kv(t + NS - 1);
+    const uint16_t* Ks = ringK + (t % NS) * TILE;
+    const uint16_t* Vs = ringV + (t % NS) * TILE;
+    const float* zs = z_ring[t % NS];
+    const int* js = ids_ring[t % (2 * NS)];
+    const int* es = e_ring[t % NS];
     const bool masked = t >= nc;
 
-    // S^T = K Q^T for the two 32-key halves of the tile
-    f32x16 sacc[2];
-#pragma unroll
+    // each 32-key half of the tile is one online-softmax step
+#pragma unroll 1
     for (int kb = 0; kb < 2; kb++) {
+      f32x16 sacc[2];
 #pragma unroll
-      for (int v = 0; v < 16; v++) sacc[kb][v] = 0.f;
+      for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) sacc[qb][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
-        sacc[kb] = mfma32(a, qreg[ks], sacc[kb]);
+        sacc[0] = mfma32(a, qreg[0][ks], sacc[0]);
+        sacc[1] = mfma32(a, qreg[1][ks], sacc[1]);
       }
-    }
-    // scores in log2 units, bias, mask, running max
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
+      // scores in log2 units, bias, mask, running max
+      float mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
       for (int gq = 0; gq < 4; gq++) {
         const int r = 32 * kb + 8 * gq + 4 * hh;
         const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
 #pragma unroll
-        for (int u = 0; u < 4; u++) sacc[kb][4 * gq + u] = fmaf(sacc[kb][4 * gq + u], p.c2, zz[u]);
+        for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+          for (int u = 0; u < 4; u++) sacc[qb][4 * gq + u] = fmaf(sacc[qb][4 * gq + u], p.c2, zz[u]);
         if (masked) {
           const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
           const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
           const int jv[4] = {jj.x, jj.y, jj.z, jj.w}, ev[4] = {ee.x, ee.y, ee.z, ee.w};
 #pragma unroll
-          for (int u = 0; u < 4; u++)
-            if (!(qi >= jv[u] && qi < ev[u])) sacc[kb][4 * gq + u] = -INFINITY;
+          for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+              const bool ok = (jv[u] >= 0) & (qi[qb] >= jv[u]) & (qi[qb] < ev[u]);
+              sacc[qb][4 * gq + u] = ok ? sacc[qb][4 * gq + u] : -INFINITY;
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 4; u++) mx = fmaxf(mx, sacc[kb][4 * gq + u]);
+        for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+          for (int u = 0; u < 4; u++) mx[qb] = fmaxf(mx[qb], sacc[qb][4 * gq + u]);
       }
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_safe);
-    m_run = m_new;
-    float psum = 0.f;
-    bf16x8 pb[2][2];
+      bf16x8 pb[2][2];  // [qb][16-key half]
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++)
+      for (int qb = 0; qb < 2; qb++) {
+        const float mxx = fmaxf(mx[qb], __shfl_xor(mx[qb], 32));
+        const float m_new = fmaxf(m_run[qb], mxx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run[qb] - m_safe);
+        m_run[qb] = m_new;
+        float psum = 0.f;
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const float pv = fast_exp2(sacc[kb][v] - m_safe);
-        psum += pv;
-        pb[kb][v >> 3][v & 7] = (__bf16)pv;
+        for (int v = 0; v < 16; v++) {
+          const float pv = fast_exp2(sacc[qb][v] - m_safe);
+          psum += pv;
+          pb[qb][v >> 3][v & 7] = (__bf16)pv;
+        }
+        lsum[qb] = lsum[qb] * alpha + psum;
+        if (!__all(alpha == 1.0f)) {  // the running maximum rarely moves after the first tiles
+#pragma unroll
+          for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) oacc[qb][cb][v] *= alpha;
+        }
       }
-    lsum = lsum * alpha + psum;
-    if (!__all(alpha == 1.0f)) {  // the running maximum rarely moves after the first tiles
-#pragma unroll
-      for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) oacc[cb][v] *= alpha;
-    }
-
-    // O^T += V^T P^T
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++)
+      // O^T += V^T P^T
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++)
-          oacc[cb] = mfma32(tr_frag<D>(Vs, 32 * kb + 16 * c, cb, l), pb[kb][c], oacc[cb]);
+        for (int cb = 0; cb < CB; cb++) {
+          const bf16x8 a = tr_frag<D>(Vs, 32 * kb + 16 * c, cb, l);
+          oacc[0][cb] = mfma32(a, pb[0][c], oacc[0][cb]);
+          oacc[1][cb] = mfma32(a, pb[1][c], oacc[1][cb]);
+        }
+    }
   }
 
-  // epilogue: normalise, stage O through LDS for coalesced rows, write LSE
-  const float ltot = lsum + __shfl_xor(lsum, 32);
-  const float inv = 1.f / ltot;
-  if (hh == 0 && qi < row1) p.LSE[(size_t)h * p.T + qi] = (m_run + __builtin_amdgcn_logf(ltot)) * LN2;
-  __syncthreads();
-  uint16_t* Os = smem;  // [BQ][LDK]
+  // epilogue: drain the (dummy) copies still in flight, normalise, stage O through LDS for
+  // coalesced rows, write LSE
+  wait_vmcnt<0>();
+  lds_barrier();
+  uint16_t* Os = ringK;  // [BQ][D] with the tile swizzle; NS * KT == BQ rows
+  static_assert(NS * KT == BQ, "O staging aliases the K ring");
 #pragma unroll
-  for (int cb = 0; cb < CB; cb++)
+  for (int qb = 0; qb < 2; qb++) {
+    const float ltot = lsum[qb] + __shfl_xor(lsum[qb], 32);
+    const float inv = 1.f / ltot;
+    if (hh == 0 && qi[qb] < row1)
+      p.LSE[(size_t)h * p.T + qi[qb]] = (m_run[qb] + __builtin_amdgcn_logf(ltot)) * LN2;
 #pragma unroll
-    for (int gq = 0; gq < 4; gq++) {
-      bf16x4 o4;
+    for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-      for (int u = 0; u < 4; u++) o4[u] = (__bf16)(oacc[cb][4 * gq + u] * inv);
-      *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
-    }
-  __syncthreads();
+      for (int gq = 0; gq < 4; gq++) {
+        bf16x4 o4;
+#pragma unroll
+        for (int u = 0; u < 4; u++) o4[u] = (__bf16)(oacc[qb][cb][4 * gq + u] * inv);
+        *reinterpret_cast<bf16x4*>(&Os[TL::off(64 * w + 32 * qb + n, 4 * cb + gq) + 4 * hh]) = o4;
+      }
+  }
+  lds_barrier();
 #pragma unroll
   for (int it = 0; it < BQ * CPR / 256; it++) {
     const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
@@ -234,15 +273,17 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs p) {
 int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const float* z, const int32_t* expiry,
                const int32_t* cu, void* O, float* LSE, hipStream_t st) {
   (void)cu;
+  (void)z;
   const dma_shape& s = p.s;
   const PlanLayout& L = p.pl;
   FwdArgs a;
   a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V; a.O = (uint16_t*)O;
-  a.z = z; a.LSE = LSE; a.expiry = expiry;
+  a.z2 = (const float*)(p.plan + L.off_z2); a.LSE = LSE; a.expiry = expiry;
   a.blk = (const int4*)(p.plan + L.off_blk);
   a.slot_tab = (const int32_t*)(p.plan + L.off_slot);
   a.pcnt = (const int32_t*)(p.plan + L.off_pcnt);
   a.plist = (const int32_t*)(p.plan + L.off_plist);
+  a.consts = p.plan + L.off_consts;
   a.T = s.T; a.H_q = s.H_q; a.H_kv = s.H_kv; a.k = s.k; a.nblk_cap = L.nblk_cap; a.kpad = L.kpad;
   a.c2 = p.scale * LOG2E;
   const unsigned grid = xcd_grid(s.H_q, L.nblk_cap);

@@ -105,6 +105,22 @@ __global__ __launch_bounds__(256) void z_kernel(const TV* __restrict__ V, const 
   }
 }
 
+// z2 = z * log2(e) (the kernels work in the exp2 domain), plus the plan's constant block: a zero
+// K/V row for empty slots, -inf / 0 / -1 scalars the asynchronous copies point at for empty ids.
+__global__ __launch_bounds__(256) void z2_consts_kernel(const float* __restrict__ z, float* __restrict__ z2, size_t n,
+                                                        uint32_t* consts) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t st = (size_t)gridDim.x * blockDim.x;
+  if (i < 128) {
+    uint32_t v = 0u;
+    if (i == 64) v = 0xff800000u;       // float -inf
+    if (i == 66) v = 0xffffffffu;       // int -1
+    if (i == 67) v = 0x7f800000u;       // float +inf
+    consts[i] = v;
+  }
+  for (; i < n; i += st) z2[i] = z[i] * LOG2E;
+}
+
 // ------------------------------------------------------------------ sort + wavelet matrix
 // Ascending unsigned order of the result == descending float order of z (-0 and +0 compare equal).
 __device__ __forceinline__ uint32_t desc_key(float z) {
@@ -444,6 +460,12 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
       if (s.d == 128) z_kernel<float, 128><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
       else z_kernel<float, 64><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
     }
+  }
+  {
+    const size_t n = (size_t)s.H_q * s.T;
+    size_t grid = (n + 1023) / 1024;
+    if (grid > (1u << 20)) grid = 1u << 20;
+    z2_consts_kernel<<<(unsigned)grid, 256, 0, st>>>(z, (float*)(base + L.off_z2), n, (uint32_t*)(base + L.off_consts));
   }
   prof_end(DMA_STAGE_Z, st);
   SortArgs sa;

@@ -11,7 +11,7 @@ import torch
 from paper_2508_02124_amd import binding as B
 from paper_2508_02124_amd import workloads as wlmod
 
-BQ, SG, MAXPART = 128, 128, 256
+BQ, SG, MAXPART = 256, 128, 512
 
 
 def to_dev(x, dev, dtype=None):
@@ -90,6 +90,8 @@ class DeviceCase:
             o = (o + nbytes + 255) // 256 * 256
             return r
         off_hdr = take(64)
+        take(512)            # constants
+        take(H * T * 4)      # z * log2(e)
         off_blk = take(nblk_cap * 16)
         off_docblk = take((n_docs + 1) * 4)
         off_slot = take(H * nblk_cap * kpad * 4)
