@@ -41,9 +41,9 @@ struct BwdArgs {
 
 // ------------------------------------------------------------------ dQ (and D, LSE * log2 e)
 template <int D>
-__global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
+__global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
-  constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, WL = KT / RPL / 4;
+  constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, NW = 8, WL = KT / RPL / NW;
   constexpr int NS = 4, TILE = KT * D;
   __shared__ __align__(16) uint16_t ringK[NS * TILE];
   __shared__ __align__(16) uint16_t ringV[NS * TILE];
@@ -124,15 +124,12 @@ __global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
     issue_kv(i);
   }
 
-  int qi[2];
-  bf16x8 qreg[2][KS], doreg[2][KS];
-  float Dsum[2], lse2[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-    qi[qb] = row0 + 64 * w + 32 * qb + n;
-    const bool qvalid = qi[qb] < row1;
-    const size_t off = ((size_t)qi[qb] * p.H_q + h) * D + 8 * hh;
-    float ds = 0.f;
+  const int qi = row0 + 32 * w + n;
+  const bool qvalid = qi < row1;
+  bf16x8 qreg[KS], doreg[KS];
+  float Dsum = 0.f;
+  {
+    const size_t off = ((size_t)qi * p.H_q + h) * D + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       uint4 rq = make_uint4(0, 0, 0, 0), rd = rq, ro = rq;
@@ -141,27 +138,30 @@ __global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
         rd = *reinterpret_cast<const uint4*>(p.dO + off + 16 * ks);
         ro = *reinterpret_cast<const uint4*>(p.O + off + 16 * ks);
       }
-      qreg[qb][ks] = __builtin_bit_cast(bf16x8, rq);
-      doreg[qb][ks] = __builtin_bit_cast(bf16x8, rd);
+      qreg[ks] = __builtin_bit_cast(bf16x8, rq);
+      doreg[ks] = __builtin_bit_cast(bf16x8, rd);
       const bf16x8 ov = __builtin_bit_cast(bf16x8, ro);
 #pragma unroll
-      for (int e = 0; e < 8; e++) ds = fmaf((float)doreg[qb][ks][e], (float)ov[e], ds);
-    }
-    ds += __shfl_xor(ds, 32);
-    Dsum[qb] = ds;
-    lse2[qb] = qvalid ? p.LSE[(size_t)h * p.T + qi[qb]] * LOG2E : INFINITY;
-    if (qvalid && hh == 0) {
-      p.Dws[(size_t)h * p.T + qi[qb]] = ds;
-      p.L2ws[(size_t)h * p.T + qi[qb]] = lse2[qb];
+      for (int e = 0; e < 8; e++) Dsum = fmaf((float)doreg[ks][e], (float)ov[e], Dsum);
     }
   }
-  f32x16 dqacc[2][CB];
 #pragma unroll
-  for (int qb = 0; qb < 2; qb++)
+  for (int ks = 0; ks < KS; ks++) {
+    settle(qreg[ks]);
+    settle(doreg[ks]);
+  }
+  Dsum += __shfl_xor(Dsum, 32);
+  float lse2 = qvalid ? p.LSE[(size_t)h * p.T + qi] * LOG2E : INFINITY;
+  settle(lse2);
+  if (qvalid && hh == 0) {
+    p.Dws[(size_t)h * p.T + qi] = Dsum;
+    p.L2ws[(size_t)h * p.T + qi] = lse2;
+  }
+  f32x16 dqacc[CB];
 #pragma unroll
-    for (int cb = 0; cb < CB; cb++)
+  for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) dqacc[qb][cb][v] = 0.f;
+    for (int v = 0; v < 16; v++) dqacc[cb][v] = 0.f;
   wait_vmcnt<0>();  // the ordinary loads and stores above; from here on only copies are in flight
 
   for (int t = 0; t < nt; t++) {
@@ -178,21 +178,17 @@ __global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
 
 #pragma unroll 1
     for (int kb = 0; kb < 2; kb++) {
-      bf16x8 dsb[2][2];  // [qb][16-key half]
+      bf16x8 dsb[2];  // the two 16-key halves
       {
-        f32x16 sacc[2], dpacc[2];
+        f32x16 sacc, dpacc;
 #pragma unroll
-        for (int qb = 0; qb < 2; qb++)
-#pragma unroll
-          for (int v = 0; v < 16; v++) { sacc[qb][v] = 0.f; dpacc[qb][v] = 0.f; }
+        for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
           const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
           const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[TL::off(32 * kb + n, 2 * ks + hh)]);
-          sacc[0] = mfma32(ak, qreg[0][ks], sacc[0]);
-          sacc[1] = mfma32(ak, qreg[1][ks], sacc[1]);
-          dpacc[0] = mfma32(av, doreg[0][ks], dpacc[0]);
-          dpacc[1] = mfma32(av, doreg[1][ks], dpacc[1]);
+          sacc = mfma32(ak, qreg[ks], sacc);
+          dpacc = mfma32(av, doreg[ks], dpacc);
         }
 #pragma unroll
         for (int gq = 0; gq < 4; gq++) {
@@ -206,27 +202,22 @@ __global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
             ev[0] = ee.x; ev[1] = ee.y; ev[2] = ee.z; ev[3] = ee.w;
           }
 #pragma unroll
-          for (int qb = 0; qb < 2; qb++)
-#pragma unroll
-            for (int u = 0; u < 4; u++) {
-              const int v = 4 * gq + u;
-              float pv = fast_exp2(fmaf(sacc[qb][v], p.c2, zz[u]) - lse2[qb]);
-              const bool ok = !masked | ((jv[u] >= 0) & (qi[qb] >= jv[u]) & (qi[qb] < ev[u]));
-              pv = ok ? pv : 0.f;
-              const float ds = pv * (dpacc[qb][v] - Dsum[qb]);
-              dsb[qb][v >> 3][v & 7] = (__bf16)ds;
-            }
+          for (int u = 0; u < 4; u++) {
+            const int v = 4 * gq + u;
+            float pv = fast_exp2(fmaf(sacc[v], p.c2, zz[u]) - lse2);
+            const bool ok = !masked | ((jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]));
+            pv = ok ? pv : 0.f;
+            const float ds = pv * (dpacc[v] - Dsum);
+            dsb[v >> 3][v & 7] = (__bf16)ds;
+          }
         }
       }
       // dQ^T += K^T dS^T for this half of the tile
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++) {
-          const bf16x8 a = tr_frag<D>(Ks, 32 * kb + 16 * c, cb, l);
-          dqacc[0][cb] = mfma32(a, dsb[0][c], dqacc[0][cb]);
-          dqacc[1][cb] = mfma32(a, dsb[1][c], dqacc[1][cb]);
-        }
+        for (int cb = 0; cb < CB; cb++)
+          dqacc[cb] = mfma32(tr_frag<D>(Ks, 32 * kb + 16 * c, cb, l), dsb[c], dqacc[cb]);
     }
   }
 
@@ -235,20 +226,18 @@ __global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
   uint16_t* Os = ringK;  // [BQ][D] staging with the tile swizzle
   static_assert(NS * KT == BQ, "dQ staging aliases the K ring");
 #pragma unroll
-  for (int qb = 0; qb < 2; qb++)
+  for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-    for (int cb = 0; cb < CB; cb++)
+    for (int gq = 0; gq < 4; gq++) {
+      bf16x4 o4;
 #pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        bf16x4 o4;
-#pragma unroll
-        for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[qb][cb][4 * gq + u] * p.scale);
-        *reinterpret_cast<bf16x4*>(&Os[TL::off(64 * w + 32 * qb + n, 4 * cb + gq) + 4 * hh]) = o4;
-      }
+      for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[cb][4 * gq + u] * p.scale);
+      *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
+    }
   lds_barrier();
 #pragma unroll
-  for (int it = 0; it < BQ * CPR / 256; it++) {
-    const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
+  for (int it = 0; it < BQ * CPR / 512; it++) {
+    const int c = tid + 512 * it, r = c / CPR, col = c % CPR;
     if (row0 + r < row1)
       *reinterpret_cast<uint4*>(p.dQ + ((size_t)(row0 + r) * p.H_q + h) * D + 8 * col) =
           *reinterpret_cast<const uint4*>(&Os[TL::off(r, col)]);
@@ -256,6 +245,7 @@ __global__ __launch_bounds__(256, 1) void dq_kernel(BwdArgs p) {
 }
 
 // ------------------------------------------------------------------ dK, dV, dz
+constexpr int MAXSWEEP = 320;  // most query blocks one key-stationary work item sweeps
 // Lane (n, hh) of wave w owns column 32w + n of the workgroup's SG columns; its accumulators hold
 // channels 32cb + 8gq + 4hh + u of dK^T / dV^T for that column's key.
 template <int D, bool PARTIAL>
@@ -273,6 +263,7 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
   __shared__ __align__(16) uint16_t ringdO[NS * STILE];
   __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) D
   __shared__ __align__(16) int idbuf[2][SG];     // column ids of the current / next block
+  __shared__ __align__(16) int4 binfo[MAXSWEEP + 1];  // block table of this work item's sweep
   __shared__ __align__(16) float stage_all[4 * 32 * LDS_ST];  // per wave: [32 columns][D] fp32, flush staging
 
   // item = chunk * ngrp + group: the groups of one (head, chunk) run side by side and share Q / dO
@@ -299,34 +290,38 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
     bi_begin = chunk * p.seg;
     bi_end = min(bi_begin + p.seg, p.nblk_cap);
   }
-  // (workgroup-uniform) does block bi have any column for this group?
-  auto block_cols = [&](int bi, const int4& info) -> int {
+  // (workgroup-uniform) number of this group's columns that block bi can have
+  int np_part = 0;
+  if (PARTIAL) np_part = p.pcnt[(size_t)h * p.nblk_cap + bi_begin];
+  auto block_cols = [&](const int4& info) -> int {
     if (info.x < 0) return 0;
-    const int total = PARTIAL ? p.pcnt[(size_t)h * p.nblk_cap + bi] : min(p.k, info.y - info.w);
+    const int total = PARTIAL ? np_part : min(p.k, info.y - info.w);
     return max(0, min(SG, total - grp * SG));
   };
   if (PARTIAL) {
-    const int4 info = p.blk[bi_begin];
-    if (block_cols(bi_begin, info) == 0) return;
+    if (block_cols(p.blk[bi_begin]) == 0) return;
   } else {
     // skip leading blocks that have nothing resident in this group's columns
     while (bi_begin < bi_end) {
       const int4 info = p.blk[bi_begin];
       if (info.x < 0) return;
-      if (block_cols(bi_begin, info) > 0) break;
+      if (block_cols(info) > 0) break;
       bi_begin++;
     }
     if (bi_begin >= bi_end) return;
   }
-  const int nsteps = (bi_end - bi_begin) * NSUB;
+  const int nblocks = bi_end - bi_begin;
+  const int nsteps = nblocks * NSUB;
+  // block table of this sweep, kept in LDS so that the copy-ring loop issues no ordinary loads
+  for (int i = tid; i < MAXSWEEP + 1; i += 256) binfo[i] = i < nblocks ? p.blk[bi_begin + i] : make_int4(-1, 0, 0, 0);
+  __syncthreads();
 
   // ---- producer: copies of step v (32 query rows of Q and dO, their LSE/D, and at a block's first
   // step the block's column ids).  Steps past the end or of blocks without columns copy dummies.
   auto issue = [&](int v) {
-    const int bi = bi_begin + v / NSUB, qs = v % NSUB;
-    int4 info = make_int4(-1, 0, 0, 0);
-    if (bi < bi_end) info = p.blk[bi];
-    const int ncols = block_cols(bi, info);
+    const int bl = min(v / NSUB, MAXSWEEP), qs = v % NSUB, bi = bi_begin + bl;
+    const int4 info = binfo[bl];
+    const int ncols = block_cols(info);
     const int st = v % NS;
 #pragma unroll
     for (int j = 0; j < WLQ; j++) {
@@ -423,9 +418,9 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
     lds_barrier();
     issue(v + NS - 1);
 
-    const int bi = bi_begin + v / NSUB, qs = v % NSUB;
-    const int4 info = p.blk[bi];
-    const int ncols = block_cols(bi, info);
+    const int qs = v % NSUB;
+    const int4 info = binfo[v / NSUB];
+    const int ncols = block_cols(info);
     const int row0 = info.y, row1 = info.z;
     if (qs == 0) {
       const int cl = 32 * w + n;
@@ -451,6 +446,13 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
             if (PARTIAL) {
               kj = newid;
               ke = p.expiry[(size_t)h * p.T + newid];
+              settle(ke);
+            }
+            settle(z2);
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+              settle(kreg[ks]);
+              settle(vreg[ks]);
             }
           } else {
 #pragma unroll
@@ -570,6 +572,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
     long seg = (long)L.nblk_cap * groups / 512;
     if (seg < 2) seg = 2;
     if (seg > L.nblk_cap) seg = L.nblk_cap;
+    if (seg > MAXSWEEP) seg = MAXSWEEP;
     a.seg = (int)seg;
   }
 
@@ -582,8 +585,8 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
   const unsigned gpart = xcd_grid(s.H_q, (long)L.nblk_cap * (MAXPART / SG));
   prof_begin(DMA_STAGE_BWD_DQ, st);
-  if (s.d == 128) dq_kernel<128><<<gq, 256, 0, st>>>(a);
-  else dq_kernel<64><<<gq, 256, 0, st>>>(a);
+  if (s.d == 128) dq_kernel<128><<<gq, 512, 0, st>>>(a);
+  else dq_kernel<64><<<gq, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_DQ, st);
   prof_begin(DMA_STAGE_BWD_DKV, st);
   if (s.d == 128) dkv_kernel<128, false><<<gclean, 256, 0, st>>>(a);

@@ -165,15 +165,28 @@ template <> struct TileLayout<64> {
 // below count their outstanding copies explicitly and use a bare s_barrier (no implied vmcnt(0)).
 typedef __attribute__((address_space(3))) void* lds_vptr;
 typedef __attribute__((address_space(1))) const void* glb_vptr;
+// They are issued from inline assembly on purpose: the compiler's own model of such a copy makes
+// every later LDS read of the same array wait for ALL outstanding copies (vmcnt(0)), which would
+// serialise the ring.  M0 carries the LDS base and is restored afterwards.
 __device__ __forceinline__ void dma16(const void* g, void* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((glb_vptr)g, (lds_vptr)lds_wave_base, 16, 0, 0);
+  const uint32_t lds = (uint32_t)(uintptr_t)(lds_vptr)lds_wave_base;
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep) : "v"(g), "s"(lds) : "memory");
 }
 __device__ __forceinline__ void dma4(const void* g, void* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((glb_vptr)g, (lds_vptr)lds_wave_base, 4, 0, 0);
+  const uint32_t lds = (uint32_t)(uintptr_t)(lds_vptr)lds_wave_base;
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep) : "v"(g), "s"(lds) : "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// Pins a freshly loaded register value: the compiler must finish the load before this point, so
+// it will not place its own (full) vmcnt wait at a later first use inside a copy-ring loop.
+template <typename T> __device__ __forceinline__ void settle(T& v) { asm volatile("" : "+v"(v)); }
+
 // workgroup barrier that orders LDS traffic only (the caller has waited for the copies it needs)
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");

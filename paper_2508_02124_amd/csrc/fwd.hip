@@ -1,7 +1,7 @@
 // Forward pass (Eq. 5-6; online softmax of Alg. 1, query-stationary so O, l, m stay in registers).
 //
-// One workgroup = one block of BQ = 256 query rows of one head; wave w owns rows 64w .. 64w+63 as
-// two 32-row MFMA column blocks.  The keys a block needs are gathered, KT at a time, into a ring of
+// One workgroup (8 waves) = one block of BQ = 256 query rows of one head; wave w owns rows
+// 32w .. 32w+31, and the two waves that share a SIMD overlap each other's MFMA and softmax work.  The keys a block needs are gathered, KT at a time, into a ring of
 // LDS stages by asynchronous global->LDS copies issued NS-1 tiles ahead (no staging registers):
 // first the slot table row of the block (residents active for every row of the block: no mask
 // needed, empty slots carry z = -inf), then the block's partial list (keys entering or expiring
@@ -11,8 +11,7 @@
 //
 // Per tile the wave computes S^T = K Q^T (keys x queries) so that each lane holds one query column
 // per block: the softmax statistics are per lane, and the exponentiated block is already laid out
-// as the B operand of O^T += V^T P^T.  Every K fragment and every transposed V fragment read from
-// LDS feeds two MFMAs (the wave's two query blocks).
+// as the B operand of O^T += V^T P^T.
 #include "common.h"
 
 namespace dma {
@@ -33,13 +32,14 @@ struct FwdArgs {
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 1) void fwd_kernel(FwdArgs p) {
+__global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
   using TL = TileLayout<D>;
   constexpr int KS = D / 16;          // contraction steps of K Q^T
   constexpr int CB = D / 32;          // 32-channel blocks of O^T
   constexpr int CPR = D / 8;          // 16-byte chunks per row
   constexpr int RPL = 64 / CPR;       // rows covered by one wave-wide 16-byte copy
-  constexpr int WL = KT / RPL / 4;    // such copies per wave per K (or V) tile
+  constexpr int NW = 8;               // waves per workgroup
+  constexpr int WL = KT / RPL / NW;   // such copies per wave per K (or V) tile
   constexpr int NS = 4;               // ring stages
   constexpr int TILE = KT * D;        // elements of one K or V tile
   __shared__ __align__(16) uint16_t ringK[NS * TILE];
@@ -124,28 +124,26 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(FwdArgs p) {
     issue_kv(i);
   }
 
-  // query fragments (B operand of K Q^T): lane holds rows qi[qb], channels 16*ks + 8*hh .. +8
-  int qi[2];
-  bf16x8 qreg[2][KS];
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-    qi[qb] = row0 + 64 * w + 32 * qb + n;
-    const uint16_t* qrow = p.Q + ((size_t)qi[qb] * p.H_q + h) * D + 8 * hh;
+  // query fragments (B operand of K Q^T): lane holds row qi, channels 16*ks + 8*hh .. +8
+  const int qi = row0 + 32 * w + n;
+  bf16x8 qreg[KS];
+  {
+    const uint16_t* qrow = p.Q + ((size_t)qi * p.H_q + h) * D + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       uint4 raw = make_uint4(0, 0, 0, 0);
-      if (qi[qb] < row1) raw = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
-      qreg[qb][ks] = __builtin_bit_cast(bf16x8, raw);
+      if (qi < row1) raw = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+      qreg[ks] = __builtin_bit_cast(bf16x8, raw);
     }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) settle(qreg[ks]);
   }
-  f32x16 oacc[2][CB];
+  f32x16 oacc[CB];
 #pragma unroll
-  for (int qb = 0; qb < 2; qb++)
+  for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-    for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) oacc[qb][cb][v] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
+    for (int v = 0; v < 16; v++) oacc[cb][v] = 0.f;
+  float m_run = -INFINITY, lsum = 0.f;
   // the query loads above are ordinary loads issued after the prologue copies; wait for them here so
   // that the per-tile counts below only ever see copies
   wait_vmcnt<0>();
@@ -165,76 +163,61 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(FwdArgs p) {
     // each 32-key half of the tile is one online-softmax step
 #pragma unroll 1
     for (int kb = 0; kb < 2; kb++) {
-      f32x16 sacc[2];
+      f32x16 sacc;
 #pragma unroll
-      for (int qb = 0; qb < 2; qb++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) sacc[qb][v] = 0.f;
+      for (int v = 0; v < 16; v++) sacc[v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
-        sacc[0] = mfma32(a, qreg[0][ks], sacc[0]);
-        sacc[1] = mfma32(a, qreg[1][ks], sacc[1]);
+        sacc = mfma32(a, qreg[ks], sacc);
       }
       // scores in log2 units, bias, mask, running max
-      float mx[2] = {-INFINITY, -INFINITY};
+      float mx = -INFINITY;
 #pragma unroll
       for (int gq = 0; gq < 4; gq++) {
         const int r = 32 * kb + 8 * gq + 4 * hh;
         const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
 #pragma unroll
-        for (int qb = 0; qb < 2; qb++)
-#pragma unroll
-          for (int u = 0; u < 4; u++) sacc[qb][4 * gq + u] = fmaf(sacc[qb][4 * gq + u], p.c2, zz[u]);
+        for (int u = 0; u < 4; u++) sacc[4 * gq + u] = fmaf(sacc[4 * gq + u], p.c2, zz[u]);
         if (masked) {
           const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
           const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
           const int jv[4] = {jj.x, jj.y, jj.z, jj.w}, ev[4] = {ee.x, ee.y, ee.z, ee.w};
 #pragma unroll
-          for (int qb = 0; qb < 2; qb++)
-#pragma unroll
-            for (int u = 0; u < 4; u++) {
-              const bool ok = (jv[u] >= 0) & (qi[qb] >= jv[u]) & (qi[qb] < ev[u]);
-              sacc[qb][4 * gq + u] = ok ? sacc[qb][4 * gq + u] : -INFINITY;
-            }
+          for (int u = 0; u < 4; u++) {
+            const bool ok = (jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]);
+            sacc[4 * gq + u] = ok ? sacc[4 * gq + u] : -INFINITY;
+          }
         }
 #pragma unroll
-        for (int qb = 0; qb < 2; qb++)
-#pragma unroll
-          for (int u = 0; u < 4; u++) mx[qb] = fmaxf(mx[qb], sacc[qb][4 * gq + u]);
+        for (int u = 0; u < 4; u++) mx = fmaxf(mx, sacc[4 * gq + u]);
       }
-      bf16x8 pb[2][2];  // [qb][16-key half]
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run - m_safe);
+      m_run = m_new;
+      float psum = 0.f;
+      bf16x8 pb[2];  // the two 16-key halves
 #pragma unroll
-      for (int qb = 0; qb < 2; qb++) {
-        const float mxx = fmaxf(mx[qb], __shfl_xor(mx[qb], 32));
-        const float m_new = fmaxf(m_run[qb], mxx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run[qb] - m_safe);
-        m_run[qb] = m_new;
-        float psum = 0.f;
+      for (int v = 0; v < 16; v++) {
+        const float pv = fast_exp2(sacc[v] - m_safe);
+        psum += pv;
+        pb[v >> 3][v & 7] = (__bf16)pv;
+      }
+      lsum = lsum * alpha + psum;
+      if (!__all(alpha == 1.0f)) {  // the running maximum rarely moves after the first tiles
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const float pv = fast_exp2(sacc[qb][v] - m_safe);
-          psum += pv;
-          pb[qb][v >> 3][v & 7] = (__bf16)pv;
-        }
-        lsum[qb] = lsum[qb] * alpha + psum;
-        if (!__all(alpha == 1.0f)) {  // the running maximum rarely moves after the first tiles
+        for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-          for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) oacc[qb][cb][v] *= alpha;
-        }
+          for (int v = 0; v < 16; v++) oacc[cb][v] *= alpha;
       }
       // O^T += V^T P^T
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++) {
-          const bf16x8 a = tr_frag<D>(Vs, 32 * kb + 16 * c, cb, l);
-          oacc[0][cb] = mfma32(a, pb[0][c], oacc[0][cb]);
-          oacc[1][cb] = mfma32(a, pb[1][c], oacc[1][cb]);
-        }
+        for (int cb = 0; cb < CB; cb++)
+          oacc[cb] = mfma32(tr_frag<D>(Vs, 32 * kb + 16 * c, cb, l), pb[c], oacc[cb]);
     }
   }
 
@@ -244,26 +227,24 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(FwdArgs p) {
   lds_barrier();
   uint16_t* Os = ringK;  // [BQ][D] with the tile swizzle; NS * KT == BQ rows
   static_assert(NS * KT == BQ, "O staging aliases the K ring");
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-    const float ltot = lsum[qb] + __shfl_xor(lsum[qb], 32);
+  {
+    const float ltot = lsum + __shfl_xor(lsum, 32);
     const float inv = 1.f / ltot;
-    if (hh == 0 && qi[qb] < row1)
-      p.LSE[(size_t)h * p.T + qi[qb]] = (m_run[qb] + __builtin_amdgcn_logf(ltot)) * LN2;
+    if (hh == 0 && qi < row1) p.LSE[(size_t)h * p.T + qi] = (m_run + __builtin_amdgcn_logf(ltot)) * LN2;
 #pragma unroll
     for (int cb = 0; cb < CB; cb++)
 #pragma unroll
       for (int gq = 0; gq < 4; gq++) {
         bf16x4 o4;
 #pragma unroll
-        for (int u = 0; u < 4; u++) o4[u] = (__bf16)(oacc[qb][cb][4 * gq + u] * inv);
-        *reinterpret_cast<bf16x4*>(&Os[TL::off(64 * w + 32 * qb + n, 4 * cb + gq) + 4 * hh]) = o4;
+        for (int u = 0; u < 4; u++) o4[u] = (__bf16)(oacc[cb][4 * gq + u] * inv);
+        *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
       }
   }
   lds_barrier();
 #pragma unroll
-  for (int it = 0; it < BQ * CPR / 256; it++) {
-    const int c = tid + 256 * it, r = c / CPR, col = c % CPR;
+  for (int it = 0; it < BQ * CPR / 512; it++) {
+    const int c = tid + 512 * it, r = c / CPR, col = c % CPR;
     if (row0 + r < row1)
       *reinterpret_cast<uint4*>(p.O + ((size_t)(row0 + r) * p.H_q + h) * D + 8 * col) =
           *reinterpret_cast<const uint4*>(&Os[TL::off(r, col)]);
@@ -288,8 +269,8 @@ int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   a.c2 = p.scale * LOG2E;
   const unsigned grid = xcd_grid(s.H_q, L.nblk_cap);
   prof_begin(DMA_STAGE_FWD, st);
-  if (s.d == 128) fwd_kernel<128><<<grid, 256, 0, st>>>(a);
-  else fwd_kernel<64><<<grid, 256, 0, st>>>(a);
+  if (s.d == 128) fwd_kernel<128><<<grid, 512, 0, st>>>(a);
+  else fwd_kernel<64><<<grid, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_FWD, st);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
