@@ -475,16 +475,35 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
     const float* lses = meta[st];
     const float* Dss = meta[st] + 32;
 
+    // All operand fragments of a phase are fetched from LDS before its first MFMA, so that the
+    // wave (alone on its SIMD) pays the LDS latency once per phase instead of once per MFMA; the
+    // transposed fragments of the last phase are requested before the element-wise work.
     f32x16 sacc, dpacc;
 #pragma unroll
     for (int vv = 0; vv < 16; vv++) { sacc[vv] = 0.f; dpacc[vv] = 0.f; }
+    {
+      bf16x8 aq[KS], ad[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(&Qs[TL::off(n, 2 * ks + hh)]);
-      const bf16x8 ad = *reinterpret_cast<const bf16x8*>(&dOs[TL::off(n, 2 * ks + hh)]);
-      sacc = mfma32(aq, kreg[ks], sacc);
-      dpacc = mfma32(ad, vreg[ks], dpacc);
+      for (int ks = 0; ks < KS; ks++) {
+        aq[ks] = *reinterpret_cast<const bf16x8*>(&Qs[TL::off(n, 2 * ks + hh)]);
+        ad[ks] = *reinterpret_cast<const bf16x8*>(&dOs[TL::off(n, 2 * ks + hh)]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        sacc = mfma32(aq[ks], kreg[ks], sacc);
+        dpacc = mfma32(ad[ks], vreg[ks], dpacc);
+      }
     }
+    bf16x8 fo[2][CB], fq[2][CB];
+#pragma unroll
+    for (int c = 0; c < 2; c++)
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        fo[c][cb] = tr_frag<D>(dOs, 16 * c, cb, l);
+        fq[c][cb] = tr_frag<D>(Qs, 16 * c, cb, l);
+      }
+    __builtin_amdgcn_sched_barrier(0);
     bf16x8 pb[2], dsb[2];
 #pragma unroll
     for (int gq = 0; gq < 4; gq++) {
@@ -510,8 +529,8 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
     for (int c = 0; c < 2; c++)
 #pragma unroll
       for (int cb = 0; cb < CB; cb++) {
-        dvacc[cb] = mfma32(tr_frag<D>(dOs, 16 * c, cb, l), pb[c], dvacc[cb]);
-        dkacc[cb] = mfma32(tr_frag<D>(Qs, 16 * c, cb, l), dsb[c], dkacc[cb]);
+        dvacc[cb] = mfma32(fo[c][cb], pb[c], dvacc[cb]);
+        dkacc[cb] = mfma32(fq[c][cb], dsb[c], dkacc[cb]);
       }
   }
   wait_vmcnt<0>();
