@@ -17,4 +17,6 @@ from .dma_oracle import (  # noqa: F401
     dma_forward_gather_loop,
     dma_scalar_bruteforce,
     n_active_pairs,
+    dma_rows,
+    dma_keys,
 )

@@ -48,7 +48,7 @@ __all__ = [
     "softplus", "z_scores", "kept_mask_definition", "kept_mask_ranked",
     "expiry_from_kept", "expiry_sequential", "topk_indices", "dma_forward",
     "dma_backward", "dma_forward_gather_loop", "dma_scalar_bruteforce",
-    "n_active_pairs",
+    "n_active_pairs", "dma_rows", "dma_keys",
 ]
 
 
@@ -236,12 +236,14 @@ def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
 
 
 def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=None,
-                 mask_method="sequential", row_chunk=1024):
+                 mask_method="sequential", row_chunk=1024, return_dz_abs=False):
     """Eq. 7-10 / Alg. 2 result: dQ [T, H_q, d], dK, dV [T, H_kv, d], dz [H_q, T].
 
     dK and dV are summed over the q-heads listed in `heads` that share a
     kv-head (all heads by default).  dV is the attention-path gradient only
-    (the path V -> z is not part of this function).
+    (the path V -> z is not part of this function).  With return_dz_abs a fifth array
+    sum_i |dS_ij| [H_q, T] is returned: the magnitude of the summands of dz, against which a
+    reduced-precision dz is judged.
     """
     Q, K, V, z, dO = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO)
     T, H_q, d = Q.shape
@@ -251,6 +253,7 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     heads = range(H_q) if heads is None else heads
     dQ = np.full((T, H_q, d), np.nan)
     dz = np.full((H_q, T), np.nan)
+    dz_abs = np.full((H_q, T), np.nan)
     dK = np.zeros((T, H_kv, d))
     dV = np.zeros((T, H_kv, d))
     cu = [int(c) for c in cu_seqlens]
@@ -263,6 +266,7 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
             q, kk, v, zb, do = Q[a:b, h], K[a:b, g], V[a:b, g], z[h, a:b], dO[a:b, h]
             prov = _doc_keep_provider(zb, k, causal, mask_method)
             dzd = np.zeros(n)
+            dza = np.zeros(n)
             for r0 in range(0, n, row_chunk):
                 r1 = min(n, r0 + row_chunk)
                 S = scale * (q[r0:r1] @ kk.T) + zb[None, :]
@@ -275,7 +279,11 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
                 dQ[a + r0:a + r1, h] = scale * (dS @ kk)            # Eq. 10
                 dK[a:b, g] += scale * (dS.T @ q[r0:r1])             # Eq. 10
                 dzd += dS.sum(axis=0)                               # Eq. 9, summed over rows
+                dza += np.abs(dS).sum(axis=0)
             dz[h, a:b] = dzd
+            dz_abs[h, a:b] = dza
+    if return_dz_abs:
+        return dQ, dK, dV, dz, dz_abs
     return dQ, dK, dV, dz
 
 
@@ -340,3 +348,93 @@ def dma_scalar_bruteforce(Q, K, V, z, dO, k, scale):
                 dQ[i][c] += ds * K[j][c] * scale
                 dK[j][c] += ds * Q[i][c] * scale
     return O, LSE, dQ, dK, dV, dz
+
+
+# --------------------------------------------------------------------------- sampled outputs
+# For inputs too large for the dense path: single rows / single keys computed one by one from the
+# same definitions (pinned against the dense functions above on small inputs in the tests).
+def _doc_of(cu, t):
+    for a, b in zip(cu[:-1], cu[1:]):
+        if a <= t < b:
+            return int(a), int(b)
+    raise ValueError(t)
+
+
+class _ExpiryCache:
+    def __init__(self, z, cu, k):
+        self.z, self.cu, self.k, self.c = z, [int(c) for c in cu], k, {}
+
+    def get(self, h, a, b):
+        if (h, a) not in self.c:
+            self.c[(h, a)] = expiry_sequential(self.z[h, a:b], self.k) + a
+        return self.c[(h, a)]
+
+
+def dma_rows(Q, K, V, z, dO, cu_seqlens, k, rows, scale=None):
+    """Eq. 5-6 and the dQ half of Eq. 10 for single (head, row) pairs, causal.
+
+    rows: iterable of (h, i) with i a global row index.  Returns a list of dicts with keys
+    O [d], LSE, dQ [d] (dQ only if dO is given), kept (global key indices, ascending).
+    """
+    Q, K, V, z = _as64(Q), _as64(K), _as64(V), _as64(z)
+    dO = None if dO is None else _as64(dO)
+    T, H_q, d = Q.shape
+    G = H_q // K.shape[1]
+    scale = 1.0 / math.sqrt(d) if scale is None else float(scale)
+    cache = _ExpiryCache(z, cu_seqlens, k)
+    out = []
+    for h, i in rows:
+        a, b = _doc_of(cache.cu, i)
+        e = cache.get(h, a, b)
+        j = np.arange(a, i + 1)
+        kept = j[e[: i + 1 - a] > i]
+        g = h // G
+        s = scale * (K[kept, g] @ Q[i, h]) + z[h, kept]
+        m = s.max()
+        w = np.exp(s - m)
+        tot = w.sum()
+        p = w / tot
+        o = p @ V[kept, g]
+        rec = dict(O=o, LSE=m + math.log(tot), kept=kept)
+        if dO is not None:
+            dp = V[kept, g] @ dO[i, h]
+            ds = p * (dp - float(dO[i, h] @ o))
+            rec["dQ"] = scale * (ds @ K[kept, g])
+        out.append(rec)
+    return out
+
+
+def dma_keys(Q, K, V, z, dO, LSE, O, cu_seqlens, k, keys, scale=None):
+    """Eq. 7, 9 and the dK half of Eq. 10 for single (kv-head, key) pairs, causal, given the
+    oracle's own LSE [H_q, T] and O [T, H_q, d] for the q-heads of those kv-heads.
+
+    keys: iterable of (g, j).  Returns a list of dicts: dK [d], dV [d] (summed over the q-heads of
+    group g), dz {h: value} and dz_abs {h: sum_i |dS_ij|}.
+    """
+    Q, K, V, z, dO, LSE, O = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO), _as64(LSE), _as64(O)
+    T, H_q, d = Q.shape
+    G = H_q // K.shape[1]
+    scale = 1.0 / math.sqrt(d) if scale is None else float(scale)
+    cache = _ExpiryCache(z, cu_seqlens, k)
+    out = []
+    for g, j in keys:
+        a, b = _doc_of(cache.cu, j)
+        dK = np.zeros(d)
+        dV = np.zeros(d)
+        dz, dz_abs = {}, {}
+        for h in range(g * G, (g + 1) * G):
+            e = int(cache.get(h, a, b)[j - a])
+            rows = np.arange(j, e)
+            if rows.size == 0:
+                dz[h] = dz_abs[h] = 0.0
+                continue
+            s = scale * (Q[rows, h] @ K[j, g]) + z[h, j]
+            p = np.exp(s - LSE[h, rows])
+            D = (dO[rows, h] * O[rows, h]).sum(axis=1)
+            ds = p * (dO[rows, h] @ V[j, g] - D)
+            dz[h] = float(ds.sum())
+            dz_abs[h] = float(np.abs(ds).sum())
+            dV += p @ dO[rows, h]
+            dK += scale * (ds @ Q[rows, h])
+        out.append(dict(dK=dK, dV=dV, dz=dz, dz_abs=dz_abs))
+    return out

@@ -109,19 +109,30 @@ class DeviceCase:
         )
 
 
-def check_close(name, got, ref, atol, rtol, frob):
+def check_close(name, got, ref, atol, rtol, frob, summand_abs=None, srel=0.0):
+    """summand_abs / srel: for an output that is a long sum with cancellation (dz), the oracle's
+    sum of |summands| and the relative error each summand may carry; the element-wise bound grows
+    by srel * summand_abs."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{name}: non-finite values in the GPU result"
     err = np.abs(got - ref)
     bound = atol + rtol * np.abs(ref)
+    if summand_abs is not None:
+        bound = bound + srel * np.asarray(summand_abs, dtype=np.float64)
     worst = int(np.argmax(err - bound))
     assert (err <= bound).all(), (
         f"{name}: max|err|={err.max():.3e} at flat index {worst}: gpu={got.flat[worst]:.6g} ref={ref.flat[worst]:.6g}")
     fr = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
     assert fr <= frob, f"{name}: relative Frobenius error {fr:.3e} > {frob}"
     return float(err.max()), float(fr)
+
+
+# dz_j = sum_i dS_ij, dS_ij = P_ij (dP_ij - D_i).  In the bf16 path D_i = dO_i . O_i uses the stored
+# bf16 O (as Alg. 2 does), so every summand carries a relative error of order 2^-8 that does not
+# shrink with |dz_j| when the summands cancel: judge dz against 2e-2 + 1e-2 |ref| + DZ_SREL sum_i |dS_ij|.
+DZ_SREL = 5e-3
 
 
 def tol(is_bf16):

@@ -304,3 +304,25 @@ def test_heads_subset_matches_full():
     assert np.allclose(sub[1][:, 1], full[1][:, 1], atol=1e-14)
     assert np.allclose(sub[2][:, 1], full[2][:, 1], atol=1e-14)
     assert (sub[1][:, 0] == 0).all()
+
+
+def test_sampled_rows_and_keys_match_dense_oracle():
+    """The one-by-one functions used at full size are the same mathematics as the dense path."""
+    n1, n2, H_q, H_kv, d, k = 37, 50, 4, 2, 8, 6
+    Q, K, V, dO, z = rand_case(n1 + n2, H_q, H_kv, d, seed=41, ties=True)
+    cu = [0, n1, n1 + n2]
+    O, LSE = orc.dma_forward(Q, K, V, z, cu, k)
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, cu, k)
+    rows = [(h, i) for h in range(H_q) for i in (0, 5, n1 - 1, n1, n1 + 7, n1 + n2 - 1)]
+    for (h, i), rec in zip(rows, orc.dma_rows(Q, K, V, z, dO, cu, k, rows)):
+        assert np.allclose(rec["O"], O[i, h], atol=1e-13)
+        assert rec["LSE"] == pytest.approx(LSE[h, i], abs=1e-13)
+        assert np.allclose(rec["dQ"], dQ[i, h], atol=1e-13)
+        a = 0 if i < n1 else n1
+        assert rec["kept"].tolist() == (np.flatnonzero(orc.kept_mask_definition(z[h, a:cu[1 if i < n1 else 2]], k)[i - a]) + a).tolist()
+    keys = [(g, j) for g in range(H_kv) for j in (0, 3, n1 - 1, n1, n1 + 11, n1 + n2 - 1)]
+    for (g, j), rec in zip(keys, orc.dma_keys(Q, K, V, z, dO, LSE, O, cu, k, keys)):
+        assert np.allclose(rec["dK"], dK[j, g], atol=1e-12)
+        assert np.allclose(rec["dV"], dV[j, g], atol=1e-12)
+        for h, val in rec["dz"].items():
+            assert val == pytest.approx(dz[h, j], abs=1e-12)
