@@ -246,25 +246,34 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
 
 // ------------------------------------------------------------------ dK, dV, dz
 constexpr int MAXSWEEP = 320;  // most query blocks one key-stationary work item sweeps
-// Lane (n, hh) of wave w owns column 32w + n of the workgroup's SG columns; its accumulators hold
-// channels 32cb + 8gq + 4hh + u of dK^T / dV^T for that column's key.
+
+// Eight waves.  Wave w serves columns 32 * (w % 4) .. +31 of the workgroup's SG columns in one of two
+// roles (w / 4); the two waves of a column block share a SIMD and overlap each other's MFMA and
+// element-wise work, and each wave's state fits the register budget of two waves per SIMD:
+//   role 0 ("P"):  S = Q K^T, P = exp2(S c2 + z2 - LSE2) (masked in partial mode), dV^T += dO^T P;
+//                  holds K fragments and dV^T; hands P (fp32) to its partner through LDS.
+//   role 1 ("dS"): one step behind: dP = dO V^T, dS = P o (dP - D), dz += colsum(dS),
+//                  dK^T += Q^T dS; holds V fragments and dK^T.
+// Lane (n, hh) owns column 32 * (w % 4) + n; its accumulator holds channels 32cb + 8gq + 4hh + u.
 template <int D, bool PARTIAL>
-__global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
+__global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
   constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR;
   constexpr int SUB = 32;                 // query rows per pipeline step
   constexpr int NSUB = BQ / SUB;          // steps per query block
-  constexpr int WLQ = SUB / RPL / 4;      // 16-byte wave copies per wave per Q (or dO) step tile
+  constexpr int NWL = 2 * (SUB / RPL);    // 16-byte wave copies per step (Q rows, then dO rows)
+  constexpr int WLW = NWL / 8;            // ... per wave
   constexpr int NS = 5;                   // ring stages
   constexpr int STILE = SUB * D;
-  constexpr int LDS_ST = D + 4;
-  static_assert(WLQ >= 1, "tile too small for four waves");
+  constexpr int LDS_ST = 32 + 4;          // staging row: the 32 channels of one flush pass, padded
+  static_assert(WLW >= 1, "tile too small for eight waves");
   __shared__ __align__(16) uint16_t ringQ[NS * STILE];
   __shared__ __align__(16) uint16_t ringdO[NS * STILE];
   __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) D
   __shared__ __align__(16) int idbuf[2][SG];     // column ids of the current / next block
   __shared__ __align__(16) int4 binfo[MAXSWEEP + 1];  // block table of this work item's sweep
-  __shared__ __align__(16) float stage_all[4 * 32 * LDS_ST];  // per wave: [32 columns][D] fp32, flush staging
+  __shared__ __align__(16) float stage_all[8 * 32 * LDS_ST];  // per wave: [32 columns][32 channels] fp32, flush staging
+  __shared__ __align__(16) f32x4 pbuf[2][4][4][64];  // P hand-off (fp32): [step parity][column block][row group][lane]
 
   // item = chunk * ngrp + group: the groups of one (head, chunk) run side by side and share Q / dO
   const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
@@ -274,6 +283,7 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
   const int chunk = item / ngrp, grp = item - chunk * ngrp;
   const int g = h / (p.H_q / p.H_kv);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
+  const int kb4 = w & 3, role = w >> 2;
   const float* z2h = p.z2 + (size_t)h * p.T;
   const float* Dh = p.Dws + (size_t)h * p.T;
   const float* L2h = p.L2ws + (size_t)h * p.T;
@@ -313,7 +323,7 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
   const int nblocks = bi_end - bi_begin;
   const int nsteps = nblocks * NSUB;
   // block table of this sweep, kept in LDS so that the copy-ring loop issues no ordinary loads
-  for (int i = tid; i < MAXSWEEP + 1; i += 256) binfo[i] = i < nblocks ? p.blk[bi_begin + i] : make_int4(-1, 0, 0, 0);
+  for (int i = tid; i < MAXSWEEP + 1; i += 512) binfo[i] = i < nblocks ? p.blk[bi_begin + i] : make_int4(-1, 0, 0, 0);
   __syncthreads();
 
   // ---- producer: copies of step v (32 query rows of Q and dO, their LSE/D, and at a block's first
@@ -324,20 +334,16 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
     const int ncols = block_cols(info);
     const int st = v % NS;
 #pragma unroll
-    for (int j = 0; j < WLQ; j++) {
-      const int rbase = (w * WLQ + j) * RPL;
+    for (int j = 0; j < WLW; j++) {
+      const int li = w + 8 * j;                 // copy index: Q rows first, then dO rows
+      const bool is_do = li >= NWL / 2;
+      const int rbase = (is_do ? li - NWL / 2 : li) * RPL;
       const int r = rbase + l / CPR;
       const int c = (l % CPR) ^ TL::swz(r);
       const int row = info.y + SUB * qs + r;
-      const uint16_t* sq = zero_row + 8 * c;
-      const uint16_t* sd = sq;
-      if (ncols > 0 && row < info.z) {
-        const size_t off = ((size_t)row * p.H_q + h) * D + 8 * c;
-        sq = p.Q + off;
-        sd = p.dO + off;
-      }
-      dma16(sq, ringQ + st * STILE + rbase * D);
-      dma16(sd, ringdO + st * STILE + rbase * D);
+      const uint16_t* src = zero_row + 8 * c;
+      if (ncols > 0 && row < info.z) src = (is_do ? p.dO : p.Q) + ((size_t)row * p.H_q + h) * D + 8 * c;
+      dma16(src, (is_do ? ringdO : ringQ) + st * STILE + rbase * D);
     }
     if (w == 0) {
       const int row = info.y + SUB * qs + n;
@@ -358,72 +364,74 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
 
   int curid = -1, kj = 0x7fffffff, ke = 0;
   float z2 = -INFINITY;
-  bf16x8 kreg[KS], vreg[KS];
+  bf16x8 breg[KS];  // B-operand fragments of this lane's key: K rows (role 0) or V rows (role 1)
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    kreg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-    vreg[ks] = kreg[ks];
-  }
-  f32x16 dkacc[CB], dvacc[CB];
+  for (int ks = 0; ks < KS; ks++) breg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+  f32x16 acc[CB];   // dV^T (role 0) or dK^T (role 1) of this lane's column
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-    for (int v = 0; v < 16; v++) { dkacc[cb][v] = 0.f; dvacc[cb][v] = 0.f; }
+    for (int v = 0; v < 16; v++) acc[cb][v] = 0.f;
   float dzacc = 0.f;
 
   float* stage = stage_all + w * 32 * LDS_ST;
-  // Flush the columns whose lanes pass doit = true (wave-uniform call).  The accumulators are
-  // transposed through the wave's LDS staging area so that each atomic instruction adds 64
-  // consecutive channels of one key.
+  // Flush the columns whose lanes pass doit = true (wave-uniform call).  The accumulator is
+  // transposed through the wave's LDS staging area, 32 channels at a time, so that
+  // each atomic instruction adds consecutive channels of one key.
   auto flush = [&](bool doit) {
     const float dzt = dzacc + __shfl_xor(dzacc, 32);
     doit = doit && curid >= 0;
     const unsigned fm = (unsigned)(__ballot(doit) & 0xffffffffull);
     if (fm == 0) return;
-    if (doit && hh == 0) atomicAdd(p.dz + (size_t)h * p.T + curid, dzt);
+    if (role == 1 && doit && hh == 0) atomicAdd(p.dz + (size_t)h * p.T + curid, dzt);
+    const float mul = role == 1 ? p.scale : 1.f;
+    float* dst = role == 1 ? p.dK32 : p.dV32;
 #pragma unroll
-    for (int which = 0; which < 2; which++) {
+    for (int cb = 0; cb < CB; cb++) {
       if (doit) {
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++)
+        for (int gq = 0; gq < 4; gq++) {
+          f32x4 v4;
 #pragma unroll
-          for (int gq = 0; gq < 4; gq++) {
-            f32x4 v4;
-#pragma unroll
-            for (int u = 0; u < 4; u++)
-              v4[u] = which == 0 ? dkacc[cb][4 * gq + u] * p.scale : dvacc[cb][4 * gq + u];
-            *reinterpret_cast<f32x4*>(&stage[n * LDS_ST + 32 * cb + 8 * gq + 4 * hh]) = v4;
-          }
+          for (int u = 0; u < 4; u++) v4[u] = acc[cb][4 * gq + u] * mul;
+          *reinterpret_cast<f32x4*>(&stage[n * LDS_ST + 8 * gq + 4 * hh]) = v4;
+        }
       }
-      float* dst = which == 0 ? p.dK32 : p.dV32;
       unsigned m = fm;
-      while (m) {
-        const int c = __ffs(m) - 1;
+      while (m) {  // two flushed columns per pass: lanes 0-31 and 32-63 take one column each
+        const int c0 = __ffs(m) - 1;
         m &= m - 1;
+        int c1 = c0;
+        if (m) {
+          c1 = __ffs(m) - 1;
+          m &= m - 1;
+        }
+        const int c = hh == 0 ? c0 : c1;
         const int id = __shfl(curid, c);
-        float* row = dst + ((size_t)id * p.H_kv + g) * D;
-#pragma unroll
-        for (int u = 0; u < D / 64; u++) atomicAdd(row + l + 64 * u, stage[c * LDS_ST + l + 64 * u]);
+        if (hh == 0 || c1 != c0)
+          atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
       }
     }
   };
 
-  for (int v = 0; v < NS - 1; v++) issue(v);
+  for (int v = 0; v < NS - 2; v++) issue(v);
 
-  for (int v = 0; v < nsteps; v++) {
-    // copies of step v must have landed: at most NS-2 later steps' worth may still be in flight
+  for (int it = 0; it <= nsteps; it++) {
+    // copies of step `it` must have landed: at most NS-3 later steps' worth may still be in flight
     // (the occasional id copies and the flush traffic only make this wait more conservative)
-    if (w == 0) wait_vmcnt<(NS - 2) * (2 * WLQ + 1)>();
-    else wait_vmcnt<(NS - 2) * (2 * WLQ)>();
+    if (w == 0) wait_vmcnt<(NS - 3) * (WLW + 1)>();
+    else wait_vmcnt<(NS - 3) * WLW>();
     lds_barrier();
-    issue(v + NS - 1);
+    issue(it + NS - 2);
 
+    const int v = it - role;  // the dS role runs one step behind the P role
+    if (v < 0 || v >= nsteps) continue;
     const int qs = v % NSUB;
     const int4 info = binfo[v / NSUB];
     const int ncols = block_cols(info);
     const int row0 = info.y, row1 = info.z;
     if (qs == 0) {
-      const int cl = 32 * w + n;
+      const int cl = 32 * kb4 + n;
       const int newid = (cl < ncols) ? idbuf[(v / NSUB) & 1][cl] : -1;
       const bool changed = newid != curid;
       if (__any(changed)) {
@@ -432,16 +440,14 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
 #pragma unroll
           for (int cb = 0; cb < CB; cb++)
 #pragma unroll
-            for (int vv = 0; vv < 16; vv++) { dkacc[cb][vv] = 0.f; dvacc[cb][vv] = 0.f; }
+            for (int vv = 0; vv < 16; vv++) acc[cb][vv] = 0.f;
           dzacc = 0.f;
           curid = newid;
           if (newid >= 0) {
-            const size_t off = ((size_t)newid * p.H_kv + g) * D + 8 * hh;
+            const uint16_t* src = (role == 0 ? p.K : p.V) + ((size_t)newid * p.H_kv + g) * D + 8 * hh;
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-              kreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.K + off + 16 * ks));
-              vreg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p.V + off + 16 * ks));
-            }
+            for (int ks = 0; ks < KS; ks++)
+              breg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + 16 * ks));
             z2 = z2h[newid];
             if (PARTIAL) {
               kj = newid;
@@ -450,16 +456,10 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
             }
             settle(z2);
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-              settle(kreg[ks]);
-              settle(vreg[ks]);
-            }
+            for (int ks = 0; ks < KS; ks++) settle(breg[ks]);
           } else {
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-              kreg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-              vreg[ks] = kreg[ks];
-            }
+            for (int ks = 0; ks < KS; ks++) breg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
             z2 = -INFINITY;
             kj = 0x7fffffff;
             ke = 0;
@@ -467,71 +467,66 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(BwdArgs p) {
         }
       }
     }
-    if (ncols == 0 || row0 + SUB * qs >= row1) continue;  // workgroup-uniform: nothing to do this step
+    if (ncols == 0 || row0 + SUB * qs >= row1) continue;  // nothing to do this step (same for both roles)
 
     const int st = v % NS;
     const uint16_t* Qs = ringQ + st * STILE;
     const uint16_t* dOs = ringdO + st * STILE;
-    const float* lses = meta[st];
-    const float* Dss = meta[st] + 32;
+    f32x4* ph = &pbuf[v & 1][kb4][0][l];  // row group gq at ph[64 * gq]
 
-    // All operand fragments of a phase are fetched from LDS before its first MFMA, so that the
-    // wave (alone on its SIMD) pays the LDS latency once per phase instead of once per MFMA; the
-    // transposed fragments of the last phase are requested before the element-wise work.
-    f32x16 sacc, dpacc;
+    // role 0: S = Q K^T ; role 1: dP = dO V^T   (this lane's key column against the step's 32 rows)
+    const uint16_t* As = role == 0 ? Qs : dOs;
+    f32x16 sacc;
 #pragma unroll
-    for (int vv = 0; vv < 16; vv++) { sacc[vv] = 0.f; dpacc[vv] = 0.f; }
-    {
-      bf16x8 aq[KS], ad[KS];
+    for (int vv = 0; vv < 16; vv++) sacc[vv] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        aq[ks] = *reinterpret_cast<const bf16x8*>(&Qs[TL::off(n, 2 * ks + hh)]);
-        ad[ks] = *reinterpret_cast<const bf16x8*>(&dOs[TL::off(n, 2 * ks + hh)]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        sacc = mfma32(aq[ks], kreg[ks], sacc);
-        dpacc = mfma32(ad[ks], vreg[ks], dpacc);
-      }
+    for (int ks = 0; ks < KS; ks++) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[TL::off(n, 2 * ks + hh)]);
+      sacc = mfma32(a, breg[ks], sacc);
     }
-    bf16x8 fo[2][CB], fq[2][CB];
+    bf16x8 bb[2];  // P (role 0) or dS (role 1): the B operand of the accumulation
+    if (role == 0) {
+      const float* lses = meta[st];
 #pragma unroll
-    for (int c = 0; c < 2; c++)
+      for (int gq = 0; gq < 4; gq++) {
+        const int r = 8 * gq + 4 * hh;
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lses[r]);
+        f32x4 pq;
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) {
-        fo[c][cb] = tr_frag<D>(dOs, 16 * c, cb, l);
-        fq[c][cb] = tr_frag<D>(Qs, 16 * c, cb, l);
-      }
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 pb[2], dsb[2];
-#pragma unroll
-    for (int gq = 0; gq < 4; gq++) {
-      const int r = 8 * gq + 4 * hh;
-      const f32x4 ls = *reinterpret_cast<const f32x4*>(&lses[r]);
-      const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
-#pragma unroll
-      for (int u = 0; u < 4; u++) {
-        const int vv = 4 * gq + u;
-        float pv = fast_exp2(fmaf(sacc[vv], p.c2, z2) - ls[u]);
-        if (PARTIAL) {
-          const int row = row0 + SUB * qs + r + u;
-          pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
+        for (int u = 0; u < 4; u++) {
+          const int vv = 4 * gq + u;
+          float pv = fast_exp2(fmaf(sacc[vv], p.c2, z2) - ls[u]);
+          if (PARTIAL) {
+            const int row = row0 + SUB * qs + r + u;
+            pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
+          }
+          pq[u] = pv;
+          bb[vv >> 3][vv & 7] = (__bf16)pv;
         }
-        const float ds = pv * (dpacc[vv] - dd[u]);
-        dzacc += ds;
-        pb[vv >> 3][vv & 7] = (__bf16)pv;
-        dsb[vv >> 3][vv & 7] = (__bf16)ds;
+        ph[64 * gq] = pq;
+      }
+    } else {
+      const float* Dss = meta[st] + 32;
+#pragma unroll
+      for (int gq = 0; gq < 4; gq++) {
+        const int r = 8 * gq + 4 * hh;
+        const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
+        const f32x4 pq = ph[64 * gq];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          const int vv = 4 * gq + u;
+          const float ds = pq[u] * (sacc[vv] - dd[u]);
+          dzacc += ds;
+          bb[vv >> 3][vv & 7] = (__bf16)ds;
+        }
       }
     }
-    // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this step)
+    // role 0: dV^T += dO^T P ; role 1: dK^T += Q^T dS   (contraction over the step's 32 rows)
+    const uint16_t* Ts = role == 0 ? dOs : Qs;
 #pragma unroll
     for (int c = 0; c < 2; c++)
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) {
-        dvacc[cb] = mfma32(fo[c][cb], pb[c], dvacc[cb]);
-        dkacc[cb] = mfma32(fq[c][cb], dsb[c], dkacc[cb]);
-      }
+      for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(tr_frag<D>(Ts, 16 * c, cb, l), bb[c], acc[cb]);
   }
   wait_vmcnt<0>();
   flush(true);
@@ -608,12 +603,12 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   else dq_kernel<64><<<gq, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_DQ, st);
   prof_begin(DMA_STAGE_BWD_DKV, st);
-  if (s.d == 128) dkv_kernel<128, false><<<gclean, 256, 0, st>>>(a);
-  else dkv_kernel<64, false><<<gclean, 256, 0, st>>>(a);
+  if (s.d == 128) dkv_kernel<128, false><<<gclean, 512, 0, st>>>(a);
+  else dkv_kernel<64, false><<<gclean, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_DKV, st);
   prof_begin(DMA_STAGE_BWD_PART, st);
-  if (s.d == 128) dkv_kernel<128, true><<<gpart, 256, 0, st>>>(a);
-  else dkv_kernel<64, true><<<gpart, 256, 0, st>>>(a);
+  if (s.d == 128) dkv_kernel<128, true><<<gpart, 512, 0, st>>>(a);
+  else dkv_kernel<64, true><<<gpart, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_PART, st);
   prof_begin(DMA_STAGE_BWD_CVT, st);
   cvt_bf16_kernel<<<grid_for(nkv / 4, 1024), 256, 0, st>>>(a.dK32, a.dV32, (uint16_t*)dK, (uint16_t*)dV, nkv / 4);
