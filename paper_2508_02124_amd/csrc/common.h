@@ -44,6 +44,7 @@ struct PlanLayout {
   size_t off_wbits;    // uint64[H_q][nbits_cap][wcap]: zero-bit masks of each wavelet level
   size_t off_wcnt;     // uint32[H_q][nbits_cap][wcap]: zeros before each word
   size_t off_wzero;    // uint32[H_q][n_docs][nbits_cap]: total zeros of each level
+  size_t off_zq;       // float[H_q][T]: z / softmax_scale, the bias as an initial value of the Q K^T accumulator
   size_t total;
 };
 
@@ -82,6 +83,7 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   p.off_wbits = take(H * p.nbits_cap * (size_t)p.wcap * 8);
   p.off_wcnt = take(H * p.nbits_cap * (size_t)p.wcap * 4);
   p.off_wzero = take(H * (size_t)s.n_docs * p.nbits_cap * 4);
+  p.off_zq = take(H * T * 4);
   p.total = o;
   return p;
 }

@@ -19,7 +19,7 @@ namespace dma {
 struct FwdArgs {
   const uint16_t *Q, *K, *V;
   uint16_t* O;
-  const float* z2;      // z * log2(e)
+  const float* zq;      // z / softmax_scale
   float* LSE;
   const int32_t* expiry;
   const int4* blk;
@@ -30,6 +30,8 @@ struct FwdArgs {
   int T, H_q, H_kv, k, nblk_cap, kpad;
   float c2;  // softmax scale * log2(e)
 };
+
+constexpr float MSLACK = 8.f;  // log2 slack of the lazily updated softmax reference maximum
 
 template <int D>
 __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
   const int nt = nc + (np_keys + KT - 1) / KT;
   const int32_t* slot_row = p.slot_tab + ((size_t)h * p.nblk_cap + bi) * p.kpad;
   const int32_t* plist_row = p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART;
-  const float* z2h = p.z2 + (size_t)h * p.T;
+  const float* zqh = p.zq + (size_t)h * p.T;
   const int32_t* eh = p.expiry + (size_t)h * p.T;
   const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
   const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
     }
     if (w == 1) {
       const int id = idr[l];
-      dma4(id >= 0 ? z2h + id : c_ninf, &z_ring[tt % NS][0]);
+      dma4(id >= 0 ? zqh + id : c_ninf, &z_ring[tt % NS][0]);
       dma4(id >= 0 ? (const void*)(eh + id) : (const void*)c_zero, &e_ring[tt % NS][0]);
     }
   };
@@ -156,69 +158,78 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
     const uint16_t* Ks = ringK + (t % NS) * TILE;
     const uint16_t* Vs = ringV + (t % NS) * TILE;
     const float* zs = z_ring[t % NS];
-    const int* js = ids_ring[t % (2 * NS)];
-    const int* es = e_ring[t % NS];
-    const bool masked = t >= nc;
 
-    // each 32-key half of the tile is one online-softmax step
-#pragma unroll 1
-    for (int kb = 0; kb < 2; kb++) {
-      f32x16 sacc;
+    // The accumulator of S^T = K Q^T starts at z / scale, so that scale * acc is the biased score;
+    // in a partial tile, pairs outside [j, e_j) start (and stay) at -inf.
+    f32x16 sacc[2];
 #pragma unroll
-      for (int v = 0; v < 16; v++) sacc[v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
-        sacc = mfma32(a, qreg[ks], sacc);
-      }
-      // scores in log2 units, bias, mask, running max
-      float mx = -INFINITY;
+    for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int gq = 0; gq < 4; gq++) {
         const int r = 32 * kb + 8 * gq + 4 * hh;
         const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
 #pragma unroll
-        for (int u = 0; u < 4; u++) sacc[4 * gq + u] = fmaf(sacc[4 * gq + u], p.c2, zz[u]);
-        if (masked) {
+        for (int u = 0; u < 4; u++) sacc[kb][4 * gq + u] = zz[u];
+      }
+    if (t >= nc) {
+      const int* js = ids_ring[t % (2 * NS)];
+      const int* es = e_ring[t % NS];
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int gq = 0; gq < 4; gq++) {
+          const int r = 32 * kb + 8 * gq + 4 * hh;
           const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
           const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
           const int jv[4] = {jj.x, jj.y, jj.z, jj.w}, ev[4] = {ee.x, ee.y, ee.z, ee.w};
 #pragma unroll
           for (int u = 0; u < 4; u++) {
             const bool ok = (jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]);
-            sacc[4 * gq + u] = ok ? sacc[4 * gq + u] : -INFINITY;
+            sacc[kb][4 * gq + u] = ok ? sacc[kb][4 * gq + u] : -INFINITY;
           }
         }
+    }
+    // two independent accumulation chains (the tile's two 32-key halves), interleaved
 #pragma unroll
-        for (int u = 0; u < 4; u++) mx = fmaxf(mx, sacc[4 * gq + u]);
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
+        sacc[kb] = mfma32(a, qreg[ks], sacc[kb]);
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run - m_safe);
+    // Online softmax in the exp2 domain with a lazily updated reference maximum: m_run moves only
+    // when the tile's maximum exceeds it by more than MSLACK, so that the rescaling of O and l is
+    // rare; until then the exponentials are at most 2^MSLACK, which fp32 accumulation absorbs.
+    float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+    for (int v = 1; v < 16; v++) mx = fmaxf(mx, fmaxf(sacc[0][v], sacc[1][v]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.c2;
+    const bool grow = mx > m_run + MSLACK;
+    if (__any(grow)) {
+      const float m_new = grow ? mx : m_run;
+      const float alpha = grow ? fast_exp2(m_run - m_new) : 1.f;  // m_run = -inf: 0, nothing accumulated yet
       m_run = m_new;
-      float psum = 0.f;
-      bf16x8 pb[2];  // the two 16-key halves
+      lsum *= alpha;
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) oacc[cb][v] *= alpha;
+    }
+    const float msub = (m_run == -INFINITY) ? 0.f : m_run;  // row with nothing kept so far: exp2(-inf - 0) = 0
+    bf16x8 pb[4];  // the four 16-key quarters
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
-        const float pv = fast_exp2(sacc[v] - m_safe);
-        psum += pv;
-        pb[v >> 3][v & 7] = (__bf16)pv;
+        const float pv = fast_exp2(fmaf(sacc[kb][v], p.c2, -msub));
+        lsum += pv;
+        pb[2 * kb + (v >> 3)][v & 7] = (__bf16)pv;
       }
-      lsum = lsum * alpha + psum;
-      if (!__all(alpha == 1.0f)) {  // the running maximum rarely moves after the first tiles
+    // O^T += V^T P^T
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++)
+    for (int c = 0; c < 4; c++)
 #pragma unroll
-          for (int v = 0; v < 16; v++) oacc[cb][v] *= alpha;
-      }
-      // O^T += V^T P^T
-#pragma unroll
-      for (int c = 0; c < 2; c++)
-#pragma unroll
-        for (int cb = 0; cb < CB; cb++)
-          oacc[cb] = mfma32(tr_frag<D>(Vs, 32 * kb + 16 * c, cb, l), pb[c], oacc[cb]);
-    }
+      for (int cb = 0; cb < CB; cb++) oacc[cb] = mfma32(tr_frag<D>(Vs, 16 * c, cb, l), pb[c], oacc[cb]);
   }
 
   // epilogue: drain the (dummy) copies still in flight, normalise, stage O through LDS for
@@ -259,7 +270,7 @@ int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   const PlanLayout& L = p.pl;
   FwdArgs a;
   a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V; a.O = (uint16_t*)O;
-  a.z2 = (const float*)(p.plan + L.off_z2); a.LSE = LSE; a.expiry = expiry;
+  a.zq = (const float*)(p.plan + L.off_zq); a.LSE = LSE; a.expiry = expiry;
   a.blk = (const int4*)(p.plan + L.off_blk);
   a.slot_tab = (const int32_t*)(p.plan + L.off_slot);
   a.pcnt = (const int32_t*)(p.plan + L.off_pcnt);
