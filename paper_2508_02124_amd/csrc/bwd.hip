@@ -326,35 +326,67 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   for (int i = tid; i < MAXSWEEP + 1; i += 512) binfo[i] = i < nblocks ? p.blk[bi_begin + i] : make_int4(-1, 0, 0, 0);
   __syncthreads();
 
+  // Block cursor: the table entry of one block of the sweep, held in scalar registers and
+  // refreshed only when a stream (producer or consumer) enters the next block.
+  struct Cursor {
+    int row0, row1, ncols;
+  };
+  auto load_cursor = [&](int bl) -> Cursor {
+    const int4 info = binfo[min(bl, MAXSWEEP)];
+    int4 u;
+    u.x = __builtin_amdgcn_readfirstlane(info.x);
+    u.y = __builtin_amdgcn_readfirstlane(info.y);
+    u.z = __builtin_amdgcn_readfirstlane(info.z);
+    u.w = __builtin_amdgcn_readfirstlane(info.w);
+    Cursor c;
+    c.row0 = u.y;
+    c.row1 = u.z;
+    c.ncols = block_cols(u);
+    return c;
+  };
+
   // ---- producer: copies of step v (32 query rows of Q and dO, their LSE/D, and at a block's first
-  // step the block's column ids).  Steps past the end or of blocks without columns copy dummies.
+  // step the block's column ids).  Every wave issues the same number of copies for every step.
+  // Rows past the end of the block (or every row of a block without columns) re-read a valid row:
+  // their LSE is +inf and their D is 0, so whatever Q / dO they hold contributes exactly 0.
+  const uint32_t row_stride = (uint32_t)p.H_q * D * 2;  // bytes between consecutive rows of Q / dO
+  int lane_r[WLW];        // tile row this lane copies
+  uint32_t lane_c[WLW];   // byte offset of its 16-byte chunk within the row
+  bool lane_do[WLW];
+#pragma unroll
+  for (int j = 0; j < WLW; j++) {
+    const int li = w + 8 * j;  // copy index: Q rows first, then dO rows
+    lane_do[j] = li >= NWL / 2;
+    const int rbase = (lane_do[j] ? li - NWL / 2 : li) * RPL;
+    lane_r[j] = rbase + l / CPR;
+    lane_c[j] = (uint32_t)(((l % CPR) ^ TL::swz(lane_r[j])) * 16);
+  }
+  Cursor pc = {0, 0, 0};
   auto issue = [&](int v) {
-    const int bl = min(v / NSUB, MAXSWEEP), qs = v % NSUB, bi = bi_begin + bl;
-    const int4 info = binfo[bl];
-    const int ncols = block_cols(info);
+    const int qs = v % NSUB;
+    if (qs == 0) pc = load_cursor(v / NSUB);
     const int st = v % NS;
+    const int rowb = pc.row0 + SUB * qs;
+    const int nvalid = pc.ncols > 0 ? min(max(pc.row1 - rowb, 0), SUB) : 0;
+    const int rb = nvalid > 0 ? rowb : 0;  // base row of the copies (row 0 when nothing is valid)
+    const size_t boff = ((size_t)rb * p.H_q + h) * D;
 #pragma unroll
     for (int j = 0; j < WLW; j++) {
-      const int li = w + 8 * j;                 // copy index: Q rows first, then dO rows
-      const bool is_do = li >= NWL / 2;
-      const int rbase = (is_do ? li - NWL / 2 : li) * RPL;
-      const int r = rbase + l / CPR;
-      const int c = (l % CPR) ^ TL::swz(r);
-      const int row = info.y + SUB * qs + r;
-      const uint16_t* src = zero_row + 8 * c;
-      if (ncols > 0 && row < info.z) src = (is_do ? p.dO : p.Q) + ((size_t)row * p.H_q + h) * D + 8 * c;
-      dma16(src, (is_do ? ringdO : ringQ) + st * STILE + rbase * D);
+      const int r = min(lane_r[j], max(nvalid - 1, 0));
+      const int rbase = ((lane_do[j] ? w + 8 * j - NWL / 2 : w + 8 * j)) * RPL;
+      dma16s((lane_do[j] ? p.dO : p.Q) + boff, (uint32_t)r * row_stride + lane_c[j],
+             (lane_do[j] ? ringdO : ringQ) + st * STILE + rbase * D);
     }
     if (w == 0) {
-      const int row = info.y + SUB * qs + n;
-      const bool ok = ncols > 0 && row < info.z;
-      const float* src = hh == 0 ? (ok ? L2h + row : c_pinf) : (ok ? Dh + row : c_zero_f);
+      const bool ok = n < nvalid;
+      const float* src = hh == 0 ? (ok ? L2h + rowb + n : c_pinf) : (ok ? Dh + rowb + n : c_zero_f);
       dma4(src, &meta[st][0]);
     }
     if (qs == 0 && (w == 1 || w == 2)) {
+      const int bi = bi_begin + min(v / NSUB, MAXSWEEP);
       const int cl = (w - 1) * 64 + l;
       const int32_t* src = c_m1;
-      if (cl < ncols) {
+      if (cl < pc.ncols) {
         src = PARTIAL ? p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART + grp * SG + cl
                       : p.slot_tab + ((size_t)h * p.nblk_cap + bi) * p.kpad + grp * SG + cl;
       }
@@ -414,6 +446,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     }
   };
 
+  Cursor cc = {0, 0, 0};
   for (int v = 0; v < NS - 2; v++) issue(v);
 
   for (int it = 0; it <= nsteps; it++) {
@@ -427,9 +460,8 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     const int v = it - role;  // the dS role runs one step behind the P role
     if (v < 0 || v >= nsteps) continue;
     const int qs = v % NSUB;
-    const int4 info = binfo[v / NSUB];
-    const int ncols = block_cols(info);
-    const int row0 = info.y, row1 = info.z;
+    if (qs == 0) cc = load_cursor(v / NSUB);
+    const int ncols = cc.ncols, row0 = cc.row0, row1 = cc.row1;
     if (qs == 0) {
       const int cl = 32 * kb4 + n;
       const int newid = (cl < ncols) ? idbuf[(v / NSUB) & 1][cl] : -1;

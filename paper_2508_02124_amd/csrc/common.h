@@ -182,6 +182,14 @@ __device__ __forceinline__ void dma4(const void* g, void* lds_wave_base) {
   asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
                : "=&s"(keep) : "v"(g), "s"(lds) : "memory");
 }
+// Same copy with the address split into a wave-uniform 64-bit base (scalar registers) and a
+// per-lane unsigned 32-bit byte offset: no 64-bit vector arithmetic per copy.
+__device__ __forceinline__ void dma16s(const void* uniform_base, uint32_t lane_off, void* lds_wave_base) {
+  const uint32_t lds = (uint32_t)(uintptr_t)(lds_vptr)lds_wave_base;
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep) : "v"(lane_off), "s"(uniform_base), "s"(lds) : "memory");
+}
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
