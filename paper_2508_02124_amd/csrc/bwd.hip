@@ -252,8 +252,9 @@ constexpr int MAXSWEEP = 320;  // most query blocks one key-stationary work item
 // element-wise work, and each wave's state fits the register budget of two waves per SIMD:
 //   role 0 ("P"):  S = Q K^T, P = exp2(S c2 + z2 - LSE2) (masked in partial mode), dV^T += dO^T P;
 //                  holds K fragments and dV^T; hands P (fp32) to its partner through LDS.
-//   role 1 ("dS"): one step behind: dP = dO V^T, dS = P o (dP - D), dz += colsum(dS),
-//                  dK^T += Q^T dS; holds V fragments and dK^T.
+//   role 1 ("dS"): dP = dO V^T in the same period as role 0's S, then, one period later (so that
+//                  its element-wise work overlaps role 0's MFMAs and vice versa),
+//                  dS = P o (dP - D), dz += colsum(dS), dK^T += Q^T dS; holds V fragments and dK^T.
 // Lane (n, hh) owns column 32 * (w % 4) + n; its accumulator holds channels 32cb + 8gq + 4hh + u.
 template <int D, bool PARTIAL>
 __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
@@ -447,6 +448,11 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   };
 
   Cursor cc = {0, 0, 0};
+  f32x16 sacc;        // role 0: S of the current step; role 1: dP of the step it has in flight
+  bool pend = false;  // role 1: step pstep has its dP computed; dS, dz and dK^T are still due
+  int pstep = 0;
+#pragma unroll
+  for (int vv = 0; vv < 16; vv++) sacc[vv] = 0.f;
   for (int v = 0; v < NS - 2; v++) issue(v);
 
   for (int it = 0; it <= nsteps; it++) {
@@ -457,8 +463,37 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     lds_barrier();
     issue(it + NS - 2);
 
-    const int v = it - role;  // the dS role runs one step behind the P role
-    if (v < 0 || v >= nsteps) continue;
+    // role 1 first finishes the step whose dP it computed at the end of the previous period
+    // (dS, dz, dK^T): its element-wise work then runs while role 0 is in its S = Q K^T MFMAs, and
+    // its dK^T MFMAs while role 0 computes P.
+    if (role == 1 && pend) {
+      const int st = pstep % NS;
+      const float* Dss = meta[st] + 32;
+      const f32x4* ph = &pbuf[pstep & 1][kb4][0][l];  // row group gq at ph[64 * gq]
+      bf16x8 bb[2];
+#pragma unroll
+      for (int gq = 0; gq < 4; gq++) {
+        const int r = 8 * gq + 4 * hh;
+        const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
+        const f32x4 pq = ph[64 * gq];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          const int vv = 4 * gq + u;
+          const float ds = pq[u] * (sacc[vv] - dd[u]);
+          dzacc += ds;
+          bb[vv >> 3][vv & 7] = (__bf16)ds;
+        }
+      }
+      const uint16_t* Qs = ringQ + st * STILE;
+#pragma unroll
+      for (int c = 0; c < 2; c++)
+#pragma unroll
+        for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(tr_frag<D>(Qs, 16 * c, cb, l), bb[c], acc[cb]);
+    }
+    pend = false;
+
+    const int v = it;
+    if (v >= nsteps) continue;
     const int qs = v % NSUB;
     if (qs == 0) cc = load_cursor(v / NSUB);
     const int ncols = cc.ncols, row0 = cc.row0, row1 = cc.row1;
@@ -504,11 +539,9 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     const int st = v % NS;
     const uint16_t* Qs = ringQ + st * STILE;
     const uint16_t* dOs = ringdO + st * STILE;
-    f32x4* ph = &pbuf[v & 1][kb4][0][l];  // row group gq at ph[64 * gq]
 
     // role 0: S = Q K^T ; role 1: dP = dO V^T   (this lane's key column against the step's 32 rows)
     const uint16_t* As = role == 0 ? Qs : dOs;
-    f32x16 sacc;
 #pragma unroll
     for (int vv = 0; vv < 16; vv++) sacc[vv] = 0.f;
 #pragma unroll
@@ -516,49 +549,36 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
       const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[TL::off(n, 2 * ks + hh)]);
       sacc = mfma32(a, breg[ks], sacc);
     }
-    bf16x8 bb[2];  // P (role 0) or dS (role 1): the B operand of the accumulation
-    if (role == 0) {
-      const float* lses = meta[st];
-#pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        const int r = 8 * gq + 4 * hh;
-        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lses[r]);
-        f32x4 pq;
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-          const int vv = 4 * gq + u;
-          float pv = fast_exp2(fmaf(sacc[vv], p.c2, z2) - ls[u]);
-          if (PARTIAL) {
-            const int row = row0 + SUB * qs + r + u;
-            pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
-          }
-          pq[u] = pv;
-          bb[vv >> 3][vv & 7] = (__bf16)pv;
-        }
-        ph[64 * gq] = pq;
-      }
-    } else {
-      const float* Dss = meta[st] + 32;
-#pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        const int r = 8 * gq + 4 * hh;
-        const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
-        const f32x4 pq = ph[64 * gq];
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-          const int vv = 4 * gq + u;
-          const float ds = pq[u] * (sacc[vv] - dd[u]);
-          dzacc += ds;
-          bb[vv >> 3][vv & 7] = (__bf16)ds;
-        }
-      }
+    if (role == 1) {  // the rest of this step follows the next barrier
+      pend = true;
+      pstep = v;
+      continue;
     }
-    // role 0: dV^T += dO^T P ; role 1: dK^T += Q^T dS   (contraction over the step's 32 rows)
-    const uint16_t* Ts = role == 0 ? dOs : Qs;
+    f32x4* ph = &pbuf[v & 1][kb4][0][l];
+    bf16x8 bb[2];  // P: the B operand of the dV^T accumulation
+    const float* lses = meta[st];
+#pragma unroll
+    for (int gq = 0; gq < 4; gq++) {
+      const int r = 8 * gq + 4 * hh;
+      const f32x4 ls = *reinterpret_cast<const f32x4*>(&lses[r]);
+      f32x4 pq;
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const int vv = 4 * gq + u;
+        float pv = fast_exp2(fmaf(sacc[vv], p.c2, z2) - ls[u]);
+        if (PARTIAL) {
+          const int row = row0 + SUB * qs + r + u;
+          pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
+        }
+        pq[u] = pv;
+        bb[vv >> 3][vv & 7] = (__bf16)pv;
+      }
+      ph[64 * gq] = pq;
+    }
 #pragma unroll
     for (int c = 0; c < 2; c++)
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(tr_frag<D>(Ts, 16 * c, cb, l), bb[c], acc[cb]);
+      for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(tr_frag<D>(dOs, 16 * c, cb, l), bb[c], acc[cb]);
   }
   wait_vmcnt<0>();
   flush(true);
