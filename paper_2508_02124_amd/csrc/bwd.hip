@@ -35,7 +35,8 @@ struct BwdArgs {
   const int32_t* plist;
   const char* consts;  // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1; +268: float +inf
   int T, H_q, H_kv, k, nblk_cap, kpad;
-  int seg;  // query blocks swept by one clean-mode work item of dkv_kernel
+  int seg;       // query blocks swept by one clean-mode work item of dkv_kernel
+  int seg_part;  // ... by one partial-mode work item
   float scale, c2;
 };
 
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 
   // item = chunk * ngrp + group: the groups of one (head, chunk) run side by side and share Q / dO
   const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
-  const int nchunk = PARTIAL ? p.nblk_cap : (p.nblk_cap + p.seg - 1) / p.seg;
+  const int nchunk = (p.nblk_cap + (PARTIAL ? p.seg_part : p.seg) - 1) / (PARTIAL ? p.seg_part : p.seg);
   int h, item;
   if (!xcd_map(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
   const int chunk = item / ngrp, grp = item - chunk * ngrp;
@@ -293,56 +294,51 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
   const float* c_pinf = reinterpret_cast<const float*>(p.consts + 268);
 
-  int bi_begin, bi_end;
-  if (PARTIAL) {
-    bi_begin = chunk;
-    bi_end = bi_begin + 1;
-  } else {
-    bi_begin = chunk * p.seg;
-    bi_end = min(bi_begin + p.seg, p.nblk_cap);
-  }
-  // (workgroup-uniform) number of this group's columns that block bi can have
-  int np_part = 0;
-  if (PARTIAL) np_part = p.pcnt[(size_t)h * p.nblk_cap + bi_begin];
-  auto block_cols = [&](const int4& info) -> int {
-    if (info.x < 0) return 0;
-    const int total = PARTIAL ? np_part : min(p.k, info.y - info.w);
-    return max(0, min(SG, total - grp * SG));
-  };
-  if (PARTIAL) {
-    if (block_cols(p.blk[bi_begin]) == 0) return;
-  } else {
-    // skip leading blocks that have nothing resident in this group's columns
-    while (bi_begin < bi_end) {
-      const int4 info = p.blk[bi_begin];
-      if (info.x < 0) return;
-      if (block_cols(info) > 0) break;
-      bi_begin++;
-    }
-    if (bi_begin >= bi_end) return;
-  }
-  const int nblocks = bi_end - bi_begin;
-  const int nsteps = nblocks * NSUB;
-  // block table of this sweep, kept in LDS so that the copy-ring loop issues no ordinary loads
-  for (int i = tid; i < MAXSWEEP + 1; i += 512) binfo[i] = i < nblocks ? p.blk[bi_begin + i] : make_int4(-1, 0, 0, 0);
+  const int seg = PARTIAL ? p.seg_part : p.seg;
+  const int bi_begin = chunk * seg, bi_end = min(bi_begin + seg, p.nblk_cap);
+  // Block table of this sweep, kept in LDS so that the copy-ring loop issues no ordinary loads:
+  // {block index, first row, end row, columns of this group} of every block of the chunk in which
+  // the group has at least one column (clean mode: resident slots; partial mode: listed keys).
+  __shared__ int nblocks_s;
+  for (int i = tid; i < MAXSWEEP + 1; i += 512) binfo[i] = make_int4(-1, 0, 0, 0);
   __syncthreads();
+  if (w == 0) {
+    int cnt = 0;
+    for (int base = bi_begin; base < bi_end; base += 64) {
+      const int bi = base + l;
+      int4 info = make_int4(-1, 0, 0, 0);
+      int nc = 0;
+      if (bi < bi_end) {
+        info = p.blk[bi];
+        if (info.x >= 0) {
+          const int total = PARTIAL ? p.pcnt[(size_t)h * p.nblk_cap + bi] : min(p.k, info.y - info.w);
+          nc = max(0, min(SG, total - grp * SG));
+        }
+      }
+      const unsigned long long m = __ballot(nc > 0);
+      if (nc > 0) binfo[cnt + __popcll(m & ((1ull << l) - 1ull))] = make_int4(bi, info.y, info.z, nc);
+      cnt += __popcll(m);
+    }
+    if (l == 0) nblocks_s = cnt;
+  }
+  __syncthreads();
+  const int nblocks = nblocks_s;
+  if (nblocks == 0) return;
+  const int nsteps = nblocks * NSUB;
 
   // Block cursor: the table entry of one block of the sweep, held in scalar registers and
-  // refreshed only when a stream (producer or consumer) enters the next block.
+  // refreshed only when a stream (producer or consumer) enters the next block.  Past the end of
+  // the sweep it is a dummy without columns.
   struct Cursor {
-    int row0, row1, ncols;
+    int bi, row0, row1, ncols;
   };
   auto load_cursor = [&](int bl) -> Cursor {
     const int4 info = binfo[min(bl, MAXSWEEP)];
-    int4 u;
-    u.x = __builtin_amdgcn_readfirstlane(info.x);
-    u.y = __builtin_amdgcn_readfirstlane(info.y);
-    u.z = __builtin_amdgcn_readfirstlane(info.z);
-    u.w = __builtin_amdgcn_readfirstlane(info.w);
     Cursor c;
-    c.row0 = u.y;
-    c.row1 = u.z;
-    c.ncols = block_cols(u);
+    c.bi = __builtin_amdgcn_readfirstlane(info.x);
+    c.row0 = __builtin_amdgcn_readfirstlane(info.y);
+    c.row1 = __builtin_amdgcn_readfirstlane(info.z);
+    c.ncols = __builtin_amdgcn_readfirstlane(info.w);
     return c;
   };
 
@@ -362,7 +358,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     lane_r[j] = rbase + l / CPR;
     lane_c[j] = (uint32_t)(((l % CPR) ^ TL::swz(lane_r[j])) * 16);
   }
-  Cursor pc = {0, 0, 0};
+  Cursor pc = {-1, 0, 0, 0};
   auto issue = [&](int v) {
     const int qs = v % NSUB;
     if (qs == 0) pc = load_cursor(v / NSUB);
@@ -384,7 +380,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
       dma4(src, &meta[st][0]);
     }
     if (qs == 0 && (w == 1 || w == 2)) {
-      const int bi = bi_begin + min(v / NSUB, MAXSWEEP);
+      const int bi = pc.bi;
       const int cl = (w - 1) * 64 + l;
       const int32_t* src = c_m1;
       if (cl < pc.ncols) {
@@ -447,7 +443,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     }
   };
 
-  Cursor cc = {0, 0, 0};
+  Cursor cc = {-1, 0, 0, 0};
   f32x16 sacc;        // role 0: S of the current step; role 1: dP of the step it has in flight
   bool pend = false;  // role 1: step pstep has its dP computed; dS, dz and dK^T are still due
   int pstep = 0;
@@ -535,6 +531,12 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
       }
     }
     if (ncols == 0 || row0 + SUB * qs >= row1) continue;  // nothing to do this step (same for both roles)
+    if (PARTIAL) {
+      // none of this wave's keys is active on these rows (entering keys are listed by ascending
+      // first row, expiring ones by ascending end row); both roles of a column block agree
+      const int rf = row0 + SUB * qs;
+      if (!__any((kj < rf + SUB) & (ke > rf))) continue;
+    }
 
     const int st = v % NS;
     const uint16_t* Qs = ringQ + st * STILE;
@@ -640,6 +642,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
     if (seg > L.nblk_cap) seg = L.nblk_cap;
     if (seg > MAXSWEEP) seg = MAXSWEEP;
     a.seg = (int)seg;
+    a.seg_part = L.nblk_cap < 4 ? L.nblk_cap : 4;  // blocks per partial-mode work item: amortises the pipeline fill
   }
 
   const size_t nkv = (size_t)s.T * s.H_kv * s.d;
@@ -649,7 +652,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   prof_end(DMA_STAGE_BWD_ZERO, st);
   const unsigned gq = xcd_grid(s.H_q, L.nblk_cap);
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
-  const unsigned gpart = xcd_grid(s.H_q, (long)L.nblk_cap * (MAXPART / SG));
+  const unsigned gpart = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg_part - 1) / a.seg_part) * (MAXPART / SG));
   prof_begin(DMA_STAGE_BWD_DQ, st);
   if (s.d == 128) dq_kernel<128><<<gq, 512, 0, st>>>(a);
   else dq_kernel<64><<<gq, 512, 0, st>>>(a);
