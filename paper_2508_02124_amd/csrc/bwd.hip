@@ -415,6 +415,9 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     if (role == 1 && doit && hh == 0) atomicAdd(p.dz + (size_t)h * p.T + curid, dzt);
     const float mul = role == 1 ? p.scale : 1.f;
     float* dst = role == 1 ? p.dK32 : p.dV32;
+    const bool dense = __popc(fm) > 6;  // many columns (a partial-mode block change, the end of a sweep)
+    int* stage_id = reinterpret_cast<int*>(stage);
+    if (dense && hh == 0) stage_id[n * LDS_ST + 32] = doit ? curid : -1;
 #pragma unroll
     for (int cb = 0; cb < CB; cb++) {
       if (doit) {
@@ -426,19 +429,30 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
           *reinterpret_cast<f32x4*>(&stage[n * LDS_ST + 8 * gq + 4 * hh]) = v4;
         }
       }
-      unsigned m = fm;
-      while (m) {  // two flushed columns per pass: lanes 0-31 and 32-63 take one column each
-        const int c0 = __ffs(m) - 1;
-        m &= m - 1;
-        int c1 = c0;
-        if (m) {
-          c1 = __ffs(m) - 1;
-          m &= m - 1;
+      if (dense) {
+        // every pass handles the column pair (2i, 2i+1): the ids sit in the padding of the staging
+        // rows, so the 16 passes are independent of each other and pipeline
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+          const int c = 2 * i + hh;
+          const int id = stage_id[c * LDS_ST + 32];
+          if (id >= 0) atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
         }
-        const int c = hh == 0 ? c0 : c1;
-        const int id = __shfl(curid, c);
-        if (hh == 0 || c1 != c0)
-          atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
+      } else {
+        unsigned m = fm;
+        while (m) {  // two flushed columns per pass: lanes 0-31 and 32-63 take one column each
+          const int c0 = __ffs(m) - 1;
+          m &= m - 1;
+          int c1 = c0;
+          if (m) {
+            c1 = __ffs(m) - 1;
+            m &= m - 1;
+          }
+          const int c = hh == 0 ? c0 : c1;
+          const int id = __shfl(curid, c);
+          if (hh == 0 || c1 != c0)
+            atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
+        }
       }
     }
   };
@@ -642,7 +656,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
     if (seg > L.nblk_cap) seg = L.nblk_cap;
     if (seg > MAXSWEEP) seg = MAXSWEEP;
     a.seg = (int)seg;
-    a.seg_part = L.nblk_cap < 4 ? L.nblk_cap : 4;  // blocks per partial-mode work item: amortises the pipeline fill
+    a.seg_part = L.nblk_cap < 8 ? L.nblk_cap : 8;  // blocks per partial-mode work item: amortises the pipeline fill
   }
 
   const size_t nkv = (size_t)s.T * s.H_kv * s.d;

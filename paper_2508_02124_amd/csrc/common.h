@@ -186,9 +186,12 @@ __device__ __forceinline__ void dma4(const void* g, void* lds_wave_base) {
 // per-lane unsigned 32-bit byte offset: no 64-bit vector arithmetic per copy.
 __device__ __forceinline__ void dma16s(const void* uniform_base, uint32_t lane_off, void* lds_wave_base) {
   const uint32_t lds = (uint32_t)(uintptr_t)(lds_vptr)lds_wave_base;
+  const uint64_t b = (uint64_t)(uintptr_t)uniform_base;
+  const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                      (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
   uint32_t keep;
   asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
-               : "=&s"(keep) : "v"(lane_off), "s"(uniform_base), "s"(lds) : "memory");
+               : "=&s"(keep) : "v"(lane_off), "s"(sb), "s"(lds) : "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
