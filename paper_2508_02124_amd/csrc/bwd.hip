@@ -26,7 +26,7 @@ namespace dma {
 struct BwdArgs {
   const uint16_t *Q, *K, *V, *O, *dO;
   uint16_t* dQ;
-  const float *z2, *LSE;
+  const float *zq, *LSE;  // zq = z / softmax_scale
   float *Dws, *L2ws, *dK32, *dV32, *dz;
   const int32_t* expiry;
   const int4* blk;
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   const int nt = nc + (np_keys + KT - 1) / KT;
   const int32_t* slot_row = p.slot_tab + ((size_t)h * p.nblk_cap + bi) * p.kpad;
   const int32_t* plist_row = p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART;
-  const float* z2h = p.z2 + (size_t)h * p.T;
+  const float* zqh = p.zq + (size_t)h * p.T;
   const int32_t* eh = p.expiry + (size_t)h * p.T;
   const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
   const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     }
     if (w == 1) {
       const int id = idr[l];
-      dma4(id >= 0 ? z2h + id : c_ninf, &z_ring[tt % NS][0]);
+      dma4(id >= 0 ? zqh + id : c_ninf, &z_ring[tt % NS][0]);
       dma4(id >= 0 ? (const void*)(eh + id) : (const void*)c_zero, &e_ring[tt % NS][0]);
     }
   };
@@ -181,9 +181,33 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     for (int kb = 0; kb < 2; kb++) {
       bf16x8 dsb[2];  // the two 16-key halves
       {
+        // S^T starts at z / scale (so that scale * acc is the biased score) and, in a partial
+        // tile, at -inf for pairs outside [j, e_j): those get P = 0 and dS = 0 exactly.
         f32x16 sacc, dpacc;
 #pragma unroll
-        for (int v = 0; v < 16; v++) { sacc[v] = 0.f; dpacc[v] = 0.f; }
+        for (int gq = 0; gq < 4; gq++) {
+          const int r = 32 * kb + 8 * gq + 4 * hh;
+          const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
+#pragma unroll
+          for (int u = 0; u < 4; u++) {
+            sacc[4 * gq + u] = zz[u];
+            dpacc[4 * gq + u] = 0.f;
+          }
+        }
+        if (masked) {
+#pragma unroll
+          for (int gq = 0; gq < 4; gq++) {
+            const int r = 32 * kb + 8 * gq + 4 * hh;
+            const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
+            const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
+            const int jv[4] = {jj.x, jj.y, jj.z, jj.w}, ev[4] = {ee.x, ee.y, ee.z, ee.w};
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+              const bool ok = (jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]);
+              sacc[4 * gq + u] = ok ? sacc[4 * gq + u] : -INFINITY;
+            }
+          }
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
           const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
@@ -192,25 +216,10 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
           dpacc = mfma32(av, doreg[ks], dpacc);
         }
 #pragma unroll
-        for (int gq = 0; gq < 4; gq++) {
-          const int r = 32 * kb + 8 * gq + 4 * hh;
-          const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
-          int jv[4] = {0, 0, 0, 0}, ev[4] = {0, 0, 0, 0};
-          if (masked) {
-            const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
-            const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
-            jv[0] = jj.x; jv[1] = jj.y; jv[2] = jj.z; jv[3] = jj.w;
-            ev[0] = ee.x; ev[1] = ee.y; ev[2] = ee.z; ev[3] = ee.w;
-          }
-#pragma unroll
-          for (int u = 0; u < 4; u++) {
-            const int v = 4 * gq + u;
-            float pv = fast_exp2(fmaf(sacc[v], p.c2, zz[u]) - lse2);
-            const bool ok = !masked | ((jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]));
-            pv = ok ? pv : 0.f;
-            const float ds = pv * (dpacc[v] - Dsum);
-            dsb[v >> 3][v & 7] = (__bf16)ds;
-          }
+        for (int v = 0; v < 16; v++) {
+          const float pv = fast_exp2(fmaf(sacc[v], p.c2, -lse2));
+          const float ds = pv * (dpacc[v] - Dsum);
+          dsb[v >> 3][v & 7] = (__bf16)ds;
         }
       }
       // dQ^T += K^T dS^T for this half of the tile
@@ -251,7 +260,7 @@ constexpr int MAXSWEEP = 320;  // most query blocks one key-stationary work item
 // Eight waves.  Wave w serves columns 32 * (w % 4) .. +31 of the workgroup's SG columns in one of two
 // roles (w / 4); the two waves of a column block share a SIMD and overlap each other's MFMA and
 // element-wise work, and each wave's state fits the register budget of two waves per SIMD:
-//   role 0 ("P"):  S = Q K^T, P = exp2(S c2 + z2 - LSE2) (masked in partial mode), dV^T += dO^T P;
+//   role 0 ("P"):  S = Q K^T + z / scale, P = exp2(S c2 - LSE2) (masked in partial mode), dV^T += dO^T P;
 //                  holds K fragments and dV^T; hands P (fp32) to its partner through LDS.
 //   role 1 ("dS"): dP = dO V^T in the same period as role 0's S, then, one period later (so that
 //                  its element-wise work overlaps role 0's MFMAs and vice versa),
@@ -286,7 +295,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   const int g = h / (p.H_q / p.H_kv);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int kb4 = w & 3, role = w >> 2;
-  const float* z2h = p.z2 + (size_t)h * p.T;
+  const float* zqh = p.zq + (size_t)h * p.T;
   const float* Dh = p.Dws + (size_t)h * p.T;
   const float* L2h = p.L2ws + (size_t)h * p.T;
   const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
@@ -392,7 +401,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   };
 
   int curid = -1, kj = 0x7fffffff, ke = 0;
-  float z2 = -INFINITY;
+  float zq = -INFINITY;  // z / scale of this lane's key: the start value of its S accumulator
   bf16x8 breg[KS];  // B-operand fragments of this lane's key: K rows (role 0) or V rows (role 1)
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) breg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
@@ -525,19 +534,19 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 #pragma unroll
             for (int ks = 0; ks < KS; ks++)
               breg[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + 16 * ks));
-            z2 = z2h[newid];
+            zq = zqh[newid];
             if (PARTIAL) {
               kj = newid;
               ke = p.expiry[(size_t)h * p.T + newid];
               settle(ke);
             }
-            settle(z2);
+            settle(zq);
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) settle(breg[ks]);
           } else {
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) breg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-            z2 = -INFINITY;
+            zq = -INFINITY;
             kj = 0x7fffffff;
             ke = 0;
           }
@@ -558,8 +567,9 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 
     // role 0: S = Q K^T ; role 1: dP = dO V^T   (this lane's key column against the step's 32 rows)
     const uint16_t* As = role == 0 ? Qs : dOs;
+    const float s0 = role == 0 ? zq : 0.f;  // S starts at z / scale, so that scale * S is the biased score
 #pragma unroll
-    for (int vv = 0; vv < 16; vv++) sacc[vv] = 0.f;
+    for (int vv = 0; vv < 16; vv++) sacc[vv] = s0;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[TL::off(n, 2 * ks + hh)]);
@@ -581,7 +591,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 #pragma unroll
       for (int u = 0; u < 4; u++) {
         const int vv = 4 * gq + u;
-        float pv = fast_exp2(fmaf(sacc[vv], p.c2, z2) - ls[u]);
+        float pv = fast_exp2(fmaf(sacc[vv], p.c2, -ls[u]));
         if (PARTIAL) {
           const int row = row0 + SUB * qs + r + u;
           pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
@@ -639,7 +649,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   BwdArgs a;
   a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
   a.O = (const uint16_t*)O; a.dO = (const uint16_t*)dO; a.dQ = (uint16_t*)dQ;
-  a.z2 = (const float*)(p.plan + L.off_z2); a.LSE = LSE; a.expiry = expiry;
+  a.zq = (const float*)(p.plan + L.off_zq); a.LSE = LSE; a.expiry = expiry;
   a.Dws = (float*)(ws + wl.off_D); a.L2ws = (float*)(ws + wl.off_L2);
   a.dK32 = (float*)(ws + wl.off_dK); a.dV32 = (float*)(ws + wl.off_dV); a.dz = dz;
   a.blk = (const int4*)(p.plan + L.off_blk);

@@ -31,7 +31,7 @@ struct PlanLayout {
   int wcap;        // 64-bit words per wavelet level per head: T / 64 + 2 * n_docs
   size_t off_hdr;      // int32[16]: [0] number of blocks
   size_t off_consts;   // 512 B: [0,256) zeros (a dummy K/V row); then float -inf, int32 0, int32 -1, float +inf
-  size_t off_z2;       // float[H_q][T]: z * log2(e), the bias in the exp2 domain of the kernels
+  size_t off_zq;       // float[H_q][T]: z / softmax_scale, the bias as the start value of a Q K^T accumulator
   size_t off_blk;      // int4[nblk_cap]: {doc, row0, row1, doc_start}; doc = -1 past the end
   size_t off_docblk;   // int32[n_docs + 1]: first block of each document
   size_t off_slot;     // int32[H_q][nblk_cap][kpad]: clean resident key of each slot, or -1
@@ -44,7 +44,6 @@ struct PlanLayout {
   size_t off_wbits;    // uint64[H_q][nbits_cap][wcap]: zero-bit masks of each wavelet level
   size_t off_wcnt;     // uint32[H_q][nbits_cap][wcap]: zeros before each word
   size_t off_wzero;    // uint32[H_q][n_docs][nbits_cap]: total zeros of each level
-  size_t off_zq;       // float[H_q][T]: z / softmax_scale, the bias as an initial value of the Q K^T accumulator
   size_t total;
 };
 
@@ -68,7 +67,7 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   p.off_hdr = take(64);
   p.off_consts = take(512);
-  p.off_z2 = take(H * T * 4);
+  p.off_zq = take(H * T * 4);
   p.off_blk = take((size_t)p.nblk_cap * 16);
   p.off_docblk = take((size_t)(s.n_docs + 1) * 4);
   p.off_slot = take(H * p.nblk_cap * (size_t)p.kpad * 4);
@@ -83,7 +82,6 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   p.off_wbits = take(H * p.nbits_cap * (size_t)p.wcap * 8);
   p.off_wcnt = take(H * p.nbits_cap * (size_t)p.wcap * 4);
   p.off_wzero = take(H * (size_t)s.n_docs * p.nbits_cap * 4);
-  p.off_zq = take(H * T * 4);
   p.total = o;
   return p;
 }

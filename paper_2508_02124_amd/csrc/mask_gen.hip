@@ -105,12 +105,11 @@ __global__ __launch_bounds__(256) void z_kernel(const TV* __restrict__ V, const 
   }
 }
 
-// z2 = z * log2(e) (the kernels work in the exp2 domain) and zq = z / softmax_scale (the bias as
-// the initial value of a Q K^T accumulator), plus the plan's constant block: a zero K/V row for
+// zq = z / softmax_scale (the attention kernels start their Q K^T accumulators at it, so that
+// scale * accumulator is the biased score), plus the plan's constant block: a zero K/V row for
 // empty slots, -inf / 0 / -1 scalars the asynchronous copies point at for empty ids.
-__global__ __launch_bounds__(256) void z2_consts_kernel(const float* __restrict__ z, float* __restrict__ z2,
-                                                        float* __restrict__ zq, float inv_scale, size_t n,
-                                                        uint32_t* consts) {
+__global__ __launch_bounds__(256) void zq_consts_kernel(const float* __restrict__ z, float* __restrict__ zq,
+                                                        float inv_scale, size_t n, uint32_t* consts) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   const size_t st = (size_t)gridDim.x * blockDim.x;
   if (i < 128) {
@@ -120,11 +119,7 @@ __global__ __launch_bounds__(256) void z2_consts_kernel(const float* __restrict_
     if (i == 67) v = 0x7f800000u;       // float +inf
     consts[i] = v;
   }
-  for (; i < n; i += st) {
-    const float zi = z[i];
-    z2[i] = zi * LOG2E;
-    zq[i] = zi * inv_scale;
-  }
+  for (; i < n; i += st) zq[i] = z[i] * inv_scale;
 }
 
 // ------------------------------------------------------------------ sort + wavelet matrix
@@ -471,7 +466,7 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
     const size_t n = (size_t)s.H_q * s.T;
     size_t grid = (n + 1023) / 1024;
     if (grid > (1u << 20)) grid = 1u << 20;
-    z2_consts_kernel<<<(unsigned)grid, 256, 0, st>>>(z, (float*)(base + L.off_z2), (float*)(base + L.off_zq), 1.0f / p.scale, n,
+    zq_consts_kernel<<<(unsigned)grid, 256, 0, st>>>(z, (float*)(base + L.off_zq), 1.0f / p.scale, n,
                                                      (uint32_t*)(base + L.off_consts));
   }
   prof_end(DMA_STAGE_Z, st);

@@ -91,7 +91,7 @@ class DeviceCase:
             return r
         off_hdr = take(64)
         take(512)            # constants
-        take(H * T * 4)      # z * log2(e)
+        take(H * T * 4)      # z / softmax_scale
         off_blk = take(nblk_cap * 16)
         off_docblk = take((n_docs + 1) * 4)
         off_slot = take(H * nblk_cap * kpad * 4)
