@@ -80,7 +80,10 @@ size_t dma_workspace_bytes(const dma_shape* shape);
  *                   keys by (z descending, index ascending).
  *   topk_idx   out, nullable: [H_q, T, k] int32, the kept keys of each row as global
  *                   indices in ascending order, padded with -1 (debug; O(T k) memory).
- *   mask       out  dma_mask_bytes(shape) bytes; consumed by dma_fwd / dma_bwd.
+ *   mask       out  dma_mask_bytes(shape) bytes; consumed by dma_fwd / dma_bwd.  It also holds
+ *                   z / softmax_scale (the attention kernels start their score accumulators
+ *                   at it), so dma_fwd / dma_bwd must be called with the same shape,
+ *                   softmax_scale included, and z must not change in between.
  */
 int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
                  const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,

@@ -298,7 +298,6 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   const float* zqh = p.zq + (size_t)h * p.T;
   const float* Dh = p.Dws + (size_t)h * p.T;
   const float* L2h = p.L2ws + (size_t)h * p.T;
-  const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
   const float* c_zero_f = reinterpret_cast<const float*>(p.consts + 260);
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
   const float* c_pinf = reinterpret_cast<const float*>(p.consts + 268);
