@@ -162,6 +162,7 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
     k0[j] = desc_key(p.z[hb + j]);
     i0[j] = j;
   }
+  constexpr int NB = 16;           // chunk loads kept in flight per wave
   __shared__ uint32_t hist[4096];  // [digit][wave]
   __shared__ uint32_t wsum[16];
   const int nchunks = (n + 63) / 64, cpw = (nchunks + 15) / 16;
@@ -174,9 +175,18 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
     const int shift = 8 * pass;
     for (int i = tid; i < 4096; i += 1024) hist[i] = 0;
     __syncthreads();
-    for (int c = c_begin; c < c_end; c++) {
-      const int j = c * 64 + l;
-      if (j < n) atomicAdd(&hist[((sk[j] >> shift) & 255u) * 16 + w], 1u);
+    for (int cb = c_begin; cb < c_end; cb += NB) {  // NB chunk loads in flight at a time
+      uint32_t kk[NB];
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (cb + i) * 64 + l;
+        kk[i] = (cb + i < c_end && j < n) ? sk[j] : 0u;
+      }
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (cb + i) * 64 + l;
+        if (cb + i < c_end && j < n) atomicAdd(&hist[((kk[i] >> shift) & 255u) * 16 + w], 1u);
+      }
     }
     __syncthreads();
     {  // exclusive scan of hist[4096] in (digit, wave) order
@@ -199,24 +209,35 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
       hist[4 * tid + 3] = ex + v0 + v1 + v2;
     }
     __syncthreads();
-    for (int c = c_begin; c < c_end; c++) {
-      const int j = c * 64 + l;
-      const bool valid = j < n;
-      const uint32_t key = valid ? sk[j] : 0u, idx = valid ? si[j] : 0u;
-      const uint32_t dig = (key >> shift) & 255u;
-      unsigned long long m = __ballot(valid);
+    for (int cb = c_begin; cb < c_end; cb += NB) {
+      uint32_t kk[NB], ii[NB];
 #pragma unroll
-      for (int bit = 0; bit < 8; bit++) {
-        const bool one = (dig >> bit) & 1u;
-        const unsigned long long bm = __ballot(one);
-        m &= one ? bm : ~bm;
+      for (int i = 0; i < NB; i++) {
+        const int j = (cb + i) * 64 + l;
+        const bool valid = cb + i < c_end && j < n;
+        kk[i] = valid ? sk[j] : 0u;
+        ii[i] = valid ? si[j] : 0u;
       }
-      const uint32_t rank = __popcll(m & lt);
-      const uint32_t base = hist[dig * 16 + w];
-      if (valid) {
-        dk[base + rank] = key;
-        di[base + rank] = idx;
-        if (rank == 0) hist[dig * 16 + w] = base + (uint32_t)__popcll(m);
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (cb + i) * 64 + l;
+        const bool valid = cb + i < c_end && j < n;
+        const uint32_t key = kk[i], idx = ii[i];
+        const uint32_t dig = (key >> shift) & 255u;
+        unsigned long long m = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; bit++) {
+          const bool one = (dig >> bit) & 1u;
+          const unsigned long long bm = __ballot(one);
+          m &= one ? bm : ~bm;
+        }
+        const uint32_t rank = __popcll(m & lt);
+        const uint32_t base = hist[dig * 16 + w];
+        if (valid) {
+          dk[base + rank] = key;
+          di[base + rank] = idx;
+          if (rank == 0) hist[dig * 16 + w] = base + (uint32_t)__popcll(m);
+        }
       }
     }
     __syncthreads();
@@ -238,10 +259,15 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
     unsigned long long* wb = p.wbits + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
     uint32_t* wc = p.wcnt + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
     uint32_t zc = 0;
-    for (int c = c_begin; c < c_end; c++) {
-      const int j = c * 64 + l;
-      const bool zero = (j < n) && !((src[j] >> sh) & 1u);
-      zc += (uint32_t)__popcll(__ballot(zero));
+    for (int cb = c_begin; cb < c_end; cb += NB) {
+      uint32_t vv[NB];
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (cb + i) * 64 + l;
+        vv[i] = (cb + i < c_end && j < n) ? src[j] : 0xffffffffu;  // all-ones: never counted as a zero bit
+      }
+#pragma unroll
+      for (int i = 0; i < NB; i++) zc += (uint32_t)__popcll(__ballot(!((vv[i] >> sh) & 1u)));
     }
     if (l == 0) wsum[w] = zc;
     __syncthreads();
@@ -251,19 +277,28 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
       if (i < w) run += x;
       Z += x;
     }
-    for (int c = c_begin; c < c_end; c++) {
-      const int j = c * 64 + l;
-      const bool valid = j < n;
-      const uint32_t v = valid ? src[j] : 0u;
-      const bool zero = valid && !((v >> sh) & 1u);
-      const unsigned long long zm = __ballot(zero);
-      const uint32_t zb = run + (uint32_t)__popcll(zm & lt);  // zeros before position j
-      if (l == 0) {
-        wb[c] = zm;
-        wc[c] = run;
+    for (int cb = c_begin; cb < c_end; cb += NB) {
+      uint32_t vv[NB];
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (cb + i) * 64 + l;
+        vv[i] = (cb + i < c_end && j < n) ? src[j] : 0u;
       }
-      if (valid) dst[zero ? zb : Z + ((uint32_t)j - zb)] = v;
-      run += (uint32_t)__popcll(zm);
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int c = cb + i, j = c * 64 + l;
+        const bool valid = c < c_end && j < n;
+        const uint32_t v = vv[i];
+        const bool zero = valid && !((v >> sh) & 1u);
+        const unsigned long long zm = __ballot(zero);
+        const uint32_t zb = run + (uint32_t)__popcll(zm & lt);  // zeros before position j
+        if (l == 0 && c < c_end) {
+          wb[c] = zm;
+          wc[c] = run;
+        }
+        if (valid) dst[zero ? zb : Z + ((uint32_t)j - zb)] = v;
+        run += (uint32_t)__popcll(zm);
+      }
     }
     if (tid == 0) {
       wb[nchunks] = 0ull;
