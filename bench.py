@@ -81,6 +81,21 @@ def cpu_baseline(inp, wl, flops_per_head):
             "seconds": dt}
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` at the headline shape, from the committed rocprofv3 counter
+    summary (FETCH_SIZE / WRITE_SIZE runs scaled by a copy of known size); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "hotpath_cfg3_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                cols = line.split()
+                if cols and cols[0] == kernel and cols[-1].isdigit():
+                    return int(cols[-1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +104,8 @@ def main():
     ap.add_argument("--config", default=HEADLINE, help="cfg1..cfg5 (default: the headline shape)")
     ap.add_argument("--k", type=int, default=0, help="override the keep-window (cfg4 sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; rerun with --gpus 1", file=sys.stderr)
@@ -124,6 +141,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 256 MiB, writes 256 MiB: the yardstick for the HBM byte counters
+        torch.cuda.synchronize()
+        del src, dst
 
     nst = len(B.STAGES)
     evsets = [HipEvents(2 * nst) for _ in range(args.steps)]
@@ -172,7 +195,8 @@ def main():
     achieved = stage_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
     kernel_names = {"fwd": "fwd_kernel", "bwd_dq": "dq_kernel", "bwd_dkv": "dkv_kernel<clean>"}
     roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": measured_traffic(kernel_names[dom]) if wl.name == HEADLINE and not args.k else None,
                 "launch_ms": stage_ms[dom], "flops_per_launch": stage_flops[dom]}
 
     value = flops / (ms_per_step * 1e-3) / 1e12
