@@ -158,6 +158,8 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     p.Dws[(size_t)h * p.T + qi] = Dsum;
     p.L2ws[(size_t)h * p.T + qi] = lse2;
   }
+  FragOffsets<D> fo;
+  fo.init(l);
   f32x16 dqacc[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
@@ -210,10 +212,8 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
-          const bf16x8 av = *reinterpret_cast<const bf16x8*>(&Vs[TL::off(32 * kb + n, 2 * ks + hh)]);
-          sacc = mfma32(ak, qreg[ks], sacc);
-          dpacc = mfma32(av, doreg[ks], dpacc);
+          sacc = mfma32(fo.row_frag(Ks, 32 * kb, ks), qreg[ks], sacc);
+          dpacc = mfma32(fo.row_frag(Vs, 32 * kb, ks), doreg[ks], dpacc);
         }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
       for (int c = 0; c < 2; c++)
 #pragma unroll
         for (int cb = 0; cb < CB; cb++)
-          dqacc[cb] = mfma32(tr_frag<D>(Ks, 32 * kb + 16 * c, cb, l), dsb[c], dqacc[cb]);
+          dqacc[cb] = mfma32(fo.tr_frag(Ks, 32 * kb + 16 * c, cb), dsb[c], dqacc[cb]);
     }
   }
 
@@ -465,6 +465,8 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     }
   };
 
+  FragOffsets<D> fo;
+  fo.init(l);
   Cursor cc = {-1, 0, 0, 0};
   f32x16 sacc;        // role 0: S of the current step; role 1: dP of the step it has in flight
   bool pend = false;  // role 1: step pstep has its dP computed; dS, dz and dK^T are still due
@@ -506,7 +508,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(tr_frag<D>(Qs, 16 * c, cb, l), bb[c], acc[cb]);
+        for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(fo.tr_frag(Qs, 16 * c, cb), bb[c], acc[cb]);
     }
     pend = false;
 
@@ -571,8 +573,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     for (int vv = 0; vv < 16; vv++) sacc[vv] = s0;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[TL::off(n, 2 * ks + hh)]);
-      sacc = mfma32(a, breg[ks], sacc);
+      sacc = mfma32(fo.row_frag(As, 0, ks), breg[ks], sacc);
     }
     if (role == 1) {  // the rest of this step follows the next barrier
       pend = true;
@@ -603,7 +604,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 #pragma unroll
     for (int c = 0; c < 2; c++)
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(tr_frag<D>(dOs, 16 * c, cb, l), bb[c], acc[cb]);
+      for (int cb = 0; cb < CB; cb++) acc[cb] = mfma32(fo.tr_frag(dOs, 16 * c, cb), bb[c], acc[cb]);
   }
   wait_vmcnt<0>();
   flush(true);

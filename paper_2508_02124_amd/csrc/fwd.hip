@@ -140,6 +140,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) settle(qreg[ks]);
   }
+  FragOffsets<D> fo;
+  fo.init(l);
   f32x16 oacc[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
@@ -194,8 +196,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
       for (int kb = 0; kb < 2; kb++) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[TL::off(32 * kb + n, 2 * ks + hh)]);
-        sacc[kb] = mfma32(a, qreg[ks], sacc[kb]);
+        sacc[kb] = mfma32(fo.row_frag(Ks, 32 * kb, ks), qreg[ks], sacc[kb]);
       }
     // Online softmax in the exp2 domain with a lazily updated reference maximum: m_run moves only
     // when the tile's maximum exceeds it by more than MSLACK, so that the rescaling of O and l is
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
 #pragma unroll
     for (int c = 0; c < 4; c++)
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) oacc[cb] = mfma32(tr_frag<D>(Vs, 16 * c, cb, l), pb[c], oacc[cb]);
+      for (int cb = 0; cb < CB; cb++) oacc[cb] = mfma32(fo.tr_frag(Vs, 16 * c, cb), pb[c], oacc[cb]);
   }
 
   // epilogue: drain the (dummy) copies still in flight, normalise, stage O through LDS for
