@@ -158,16 +158,160 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
     return;
   }
   uint32_t *k0 = p.sk0 + hb, *k1 = p.sk1 + hb, *i0 = p.si0 + hb, *i1 = p.si1 + hb;
-  for (int j = tid; j < n; j += 1024) {
-    k0[j] = desc_key(p.z[hb + j]);
-    i0[j] = j;
-  }
-  constexpr int NB = 16;           // chunk loads kept in flight per wave
   __shared__ uint32_t hist[4096];  // [digit][wave]
   __shared__ uint32_t wsum[16];
   const int nchunks = (n + 63) / 64, cpw = (nchunks + 15) / 16;
   const int c_begin = w * cpw, c_end = min(nchunks, c_begin + cpw);
   const unsigned long long lt = (1ull << l) - 1ull;
+  constexpr int NB = 16;           // chunk loads kept in flight per wave
+  constexpr int LDS_N = 16384;     // longest document sorted entirely in LDS
+
+  if (n <= LDS_N) {
+    // ---- whole document in registers (16 elements per thread, chunk c of a wave = elements
+    // 64c + lane) and LDS: every pass scatters from registers into LDS and reads its chunks back.
+    __shared__ __align__(16) uint32_t lk[LDS_N];
+    __shared__ __align__(16) uint32_t li[LDS_N];
+    uint32_t kk[NB], ii[NB];
+#pragma unroll
+    for (int i = 0; i < NB; i++) {
+      const int j = (c_begin + i) * 64 + l;
+      const bool valid = i < cpw && j < n;
+      kk[i] = valid ? desc_key(p.z[hb + j]) : 0u;
+      ii[i] = (uint32_t)j;
+    }
+    for (int pass = 0; pass < 4; pass++) {
+      const int shift = 8 * pass;
+      for (int i = tid; i < 4096; i += 1024) hist[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        if (i < cpw && j < n) atomicAdd(&hist[((kk[i] >> shift) & 255u) * 16 + w], 1u);
+      }
+      __syncthreads();
+      {  // exclusive scan of hist[4096] in (digit, wave) order
+        const uint32_t v0 = hist[4 * tid], v1 = hist[4 * tid + 1], v2 = hist[4 * tid + 2], v3 = hist[4 * tid + 3];
+        const uint32_t sm = v0 + v1 + v2 + v3;
+        uint32_t inc = sm;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const uint32_t t = __shfl_up(inc, off);
+          if (l >= off) inc += t;
+        }
+        if (l == 63) wsum[w] = inc;
+        __syncthreads();
+        uint32_t wbase = 0;
+        for (int i = 0; i < w; i++) wbase += wsum[i];
+        const uint32_t ex = wbase + inc - sm;
+        hist[4 * tid] = ex;
+        hist[4 * tid + 1] = ex + v0;
+        hist[4 * tid + 2] = ex + v0 + v1;
+        hist[4 * tid + 3] = ex + v0 + v1 + v2;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        const bool valid = i < cpw && j < n;
+        const uint32_t dig = (kk[i] >> shift) & 255u;
+        unsigned long long m = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; bit++) {
+          const bool one = (dig >> bit) & 1u;
+          const unsigned long long bm = __ballot(one);
+          m &= one ? bm : ~bm;
+        }
+        const uint32_t rank = __popcll(m & lt);
+        const uint32_t base = hist[dig * 16 + w];
+        if (valid) {
+          lk[base + rank] = kk[i];
+          li[base + rank] = ii[i];
+          if (rank == 0) hist[dig * 16 + w] = base + (uint32_t)__popcll(m);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        if (i < cpw && j < n) {
+          kk[i] = lk[j];
+          ii[i] = li[j];
+        }
+      }
+    }
+    // sorted: ii holds the key indices in rank order; the expiry kernel reads them from si0
+#pragma unroll
+    for (int i = 0; i < NB; i++) {
+      const int j = (c_begin + i) * 64 + l;
+      if (i < cpw && j < n) i0[j] = ii[i];
+    }
+    // wavelet matrix over ii (see below), partitioned through LDS; the level tables are collected
+    // in the (now free) key buffer and written out once at the end, so no level waits on a store
+    const int nbits = dev_ceil_log2(n);
+    const int woff = a / 64 + 2 * d;
+    const int lrow = nchunks + 1;  // entries per level
+    unsigned long long* lwb = reinterpret_cast<unsigned long long*>(lk);  // [nbits][lrow]
+    uint32_t* lwc = lk + 2 * 14 * (LDS_N / 64 + 1);                        // [nbits][lrow]
+    static_assert(3 * 14 * (LDS_N / 64 + 1) <= LDS_N, "level tables must fit the key buffer");
+    for (int lev = 0; lev < nbits; lev++) {
+      const int sh = nbits - 1 - lev;
+      unsigned long long* wb = lwb + lev * lrow;
+      uint32_t* wc = lwc + lev * lrow;
+      uint32_t zc = 0;
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        const bool zero = i < cpw && j < n && !((ii[i] >> sh) & 1u);
+        zc += (uint32_t)__popcll(__ballot(zero));
+      }
+      __syncthreads();  // the previous level's reads of wsum / li are done
+      if (l == 0) wsum[w] = zc;
+      __syncthreads();
+      uint32_t run = 0, Z = 0;
+      for (int i = 0; i < 16; i++) {
+        const uint32_t x = wsum[i];
+        if (i < w) run += x;
+        Z += x;
+      }
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int c = c_begin + i, j = c * 64 + l;
+        const bool valid = i < cpw && j < n;
+        const bool zero = valid && !((ii[i] >> sh) & 1u);
+        const unsigned long long zm = __ballot(zero);
+        const uint32_t zb = run + (uint32_t)__popcll(zm & lt);  // zeros before position j
+        if (l == 0 && i < cpw && c < nchunks) {
+          wb[c] = zm;
+          wc[c] = run;
+        }
+        if (valid) li[zero ? zb : Z + ((uint32_t)j - zb)] = ii[i];
+        run += (uint32_t)__popcll(zm);
+      }
+      if (tid == 0) {
+        wb[nchunks] = 0ull;
+        wc[nchunks] = Z;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        if (i < cpw && j < n) ii[i] = li[j];
+      }
+    }
+    for (int i = tid; i < nbits * lrow; i += 1024) {
+      const int lev = i / lrow, c = i - lev * lrow;
+      const size_t o = ((size_t)h * p.nbits_cap + lev) * p.wcap + woff + c;
+      p.wbits[o] = lwb[i];
+      p.wcnt[o] = lwc[i];
+      if (c == nchunks) p.wzero[((size_t)h * p.n_docs + d) * p.nbits_cap + lev] = lwc[i];
+    }
+    return;
+  }
+
+  for (int j = tid; j < n; j += 1024) {
+    k0[j] = desc_key(p.z[hb + j]);
+    i0[j] = j;
+  }
   __syncthreads();
 
   uint32_t *sk = k0, *dk = k1, *si = i0, *di = i1;
