@@ -178,6 +178,12 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     const int* js = ids_ring[t % (2 * NS)];
     const int* es = e_ring[t % NS];
     const bool masked = t >= nc;
+    if (masked) {
+      // partial tile: skip it if none of its keys is active on any of this wave's 32 rows
+      const int jl = js[l], el = es[l];
+      const int rfirst = row0 + 32 * w;
+      if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) continue;
+    }
 
 #pragma unroll 1
     for (int kb = 0; kb < 2; kb++) {

@@ -160,6 +160,13 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
     const uint16_t* Ks = ringK + (t % NS) * TILE;
     const uint16_t* Vs = ringV + (t % NS) * TILE;
     const float* zs = z_ring[t % NS];
+    if (t >= nc) {
+      // partial tile: skip it if none of its keys is active on any of this wave's 32 rows (the
+      // lists are ordered by first / last active row, so about half of the wave-tiles drop out)
+      const int jl = ids_ring[t % (2 * NS)][l], el = e_ring[t % NS][l];
+      const int rfirst = row0 + 32 * w;
+      if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) continue;
+    }
 
     // The accumulator of S^T = K Q^T starts at z / scale, so that scale * acc is the biased score;
     // in a partial tile, pairs outside [j, e_j) start (and stay) at -inf.
