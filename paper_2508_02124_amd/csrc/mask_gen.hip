@@ -521,7 +521,24 @@ __global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ 
   }
   __syncthreads();
   const int rounds = dev_ceil_log2(n);
-  for (int r = 0; r < rounds; r++) {  // pointer jumping towards the chain root (< k)
+  constexpr int LDS_N = 16384;
+  __shared__ int32_t ls[LDS_N];
+  if (n <= LDS_N) {  // pointer jumping towards the chain root (< k), in LDS
+    for (int j = tid; j < n; j += 1024) ls[j] = sid[j];
+    __syncthreads();
+    for (int r = 0; r < rounds; r++) {
+      // (a thread may read an entry another thread has already advanced this round: still an
+      // ancestor on the same chain, so the jumping only converges faster)
+      for (int j = tid; j < n; j += 1024) {
+        const int q = ls[j];
+        if (q >= k) ls[j] = ls[q];
+      }
+      __syncthreads();
+    }
+    for (int j = tid; j < n; j += 1024) sid[j] = ls[j];
+    return;
+  }
+  for (int r = 0; r < rounds; r++) {
     for (int j = tid; j < n; j += 1024) {
       const int q = sid[j];
       if (q >= k) sid[j] = sid[q];
