@@ -19,4 +19,5 @@ from .dma_oracle import (  # noqa: F401
     n_active_pairs,
     dma_rows,
     dma_keys,
+    mask_backward,
 )

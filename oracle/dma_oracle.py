@@ -35,7 +35,9 @@ Pins (tests/test_oracle_*.py): reduction to textbook causal softmax attention
 and to torch SDPA (k >= L, constant z), sliding-window / sink closed forms,
 k = 1, all-equal z (tie rule), row sums, exact zeros, finite differences for
 all four gradients, algebraic identities, scalar triple-loop brute force, and
-the gather-loop formulation of Listing 1.  No function here is unpinned.
+the gather-loop formulation of Listing 1; mask_backward: central finite
+differences of Eq. 3 and torch autograd of the forward formula.  No function
+here is unpinned.
 """
 from __future__ import annotations
 
@@ -48,7 +50,7 @@ __all__ = [
     "softplus", "z_scores", "kept_mask_definition", "kept_mask_ranked",
     "expiry_from_kept", "expiry_sequential", "topk_indices", "dma_forward",
     "dma_backward", "dma_forward_gather_loop", "dma_scalar_bruteforce",
-    "n_active_pairs", "dma_rows", "dma_keys",
+    "n_active_pairs", "dma_rows", "dma_keys", "mask_backward",
 ]
 
 
@@ -74,6 +76,41 @@ def z_scores(V, W, A, H_q):
         x = V[:, h // G, :] @ W[h]
         z[h] = np.exp(A[h] * softplus(x))
     return z
+
+
+def mask_backward(V, W, A, dz, H_q):
+    """Gradient of Eq. 3 by the chain rule, given dz [H_q, T] (the gradient that reaches the
+    scores through the attention bias, Eq. 9 / Alg. 2).  With x = w_h . v_{g(h), j},
+    z = exp(A_h softplus(x)) and softplus' = logistic sigmoid:
+
+        dx[h, j]  = dz[h, j] z[h, j] A_h sigmoid(x[h, j])
+        dA[h]     = sum_j dz[h, j] z[h, j] softplus(x[h, j])
+        dW[h, :]  = sum_j dx[h, j] v_{g(h), j}
+        dVz[j, g] = sum_{h in group g} dx[h, j] w_h     (the part of dV that flows through z)
+
+    Returns dW [H_q, d], dA [H_q], dVz [T, H_kv, d] (float64).  No gradient flows through the
+    top-k selection (Section 6).
+    """
+    V = np.asarray(V, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    dz = np.asarray(dz, dtype=np.float64)
+    T, H_kv, d = V.shape
+    G = H_q // H_kv
+    dW = np.zeros((H_q, d))
+    dA = np.zeros(H_q)
+    dVz = np.zeros((T, H_kv, d))
+    for h in range(H_q):
+        g = h // G
+        x = V[:, g, :] @ W[h]
+        sp = softplus(x)
+        z = np.exp(A[h] * sp)
+        sig = 1.0 / (1.0 + np.exp(-x))
+        dx = dz[h] * z * A[h] * sig
+        dA[h] = np.sum(dz[h] * z * sp)
+        dW[h] = dx @ V[:, g, :]
+        dVz[:, g, :] += np.outer(dx, W[h])
+    return dW, dA, dVz
 
 
 # --------------------------------------------------------------------------- kept sets

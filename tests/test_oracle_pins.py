@@ -326,3 +326,63 @@ def test_sampled_rows_and_keys_match_dense_oracle():
         assert np.allclose(rec["dV"], dV[j, g], atol=1e-12)
         for h, val in rec["dz"].items():
             assert val == pytest.approx(dz[h, j], abs=1e-12)
+
+
+# ----------------------------------------------------------------------------- mask-path backward (chain rule of Eq. 3)
+def _mask_case(seed=3, T=23, H_q=6, H_kv=2, d=5):
+    r = np.random.default_rng(seed)
+    V = r.standard_normal((T, H_kv, d))
+    W = r.standard_normal((H_q, d)) / math.sqrt(d)
+    A = -r.uniform(0.5, 2.0, H_q)
+    dz = r.standard_normal((H_q, T))
+    return V, W, A, dz, H_q
+
+
+def test_mask_backward_matches_finite_differences():
+    """Catches: a dropped factor (A, z or the sigmoid), softplus' taken as 1, a wrong head -> kv-head
+    map, dVz not summed over the q-heads of a group, dA using x instead of softplus(x)."""
+    V, W, A, dz, H_q = _mask_case()
+    dW, dA, dVz = orc.mask_backward(V, W, A, dz, H_q)
+
+    def loss(V_, W_, A_):
+        return float(np.sum(dz * orc.z_scores(V_, W_, A_, H_q)))
+
+    eps = 1e-6
+    r = np.random.default_rng(11)
+    for _ in range(12):
+        h, c = int(r.integers(H_q)), int(r.integers(W.shape[1]))
+        Wp, Wm = W.copy(), W.copy(); Wp[h, c] += eps; Wm[h, c] -= eps
+        assert abs((loss(V, Wp, A) - loss(V, Wm, A)) / (2 * eps) - dW[h, c]) <= 1e-6 * (1 + abs(dW[h, c]))
+        t, g = int(r.integers(V.shape[0])), int(r.integers(V.shape[1]))
+        Vp, Vm = V.copy(), V.copy(); Vp[t, g, c] += eps; Vm[t, g, c] -= eps
+        assert abs((loss(Vp, W, A) - loss(Vm, W, A)) / (2 * eps) - dVz[t, g, c]) <= 1e-6 * (1 + abs(dVz[t, g, c]))
+    for h in range(H_q):
+        Ap, Am = A.copy(), A.copy(); Ap[h] += eps; Am[h] -= eps
+        assert abs((loss(V, W, Ap) - loss(V, W, Am)) / (2 * eps) - dA[h]) <= 1e-6 * (1 + abs(dA[h]))
+
+
+def test_mask_backward_matches_autograd_of_the_forward_formula():
+    """Independent derivation: torch differentiates exp(A * softplus(V w)) itself."""
+    V, W, A, dz, H_q = _mask_case(seed=5, T=40, H_q=4, H_kv=4, d=7)
+    dW, dA, dVz = orc.mask_backward(V, W, A, dz, H_q)
+    Vt = torch.tensor(V, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    At = torch.tensor(A, requires_grad=True)
+    G = H_q // V.shape[1]
+    z = torch.stack([torch.exp(At[h] * torch.nn.functional.softplus(Vt[:, h // G, :] @ Wt[h])) for h in range(H_q)])
+    (z * torch.tensor(dz)).sum().backward()
+    assert np.allclose(Wt.grad.numpy(), dW, rtol=1e-10, atol=1e-12)
+    assert np.allclose(At.grad.numpy(), dA, rtol=1e-10, atol=1e-12)
+    assert np.allclose(Vt.grad.numpy(), dVz, rtol=1e-10, atol=1e-12)
+
+
+def test_mask_backward_special_cases():
+    """dz = 0 gives zero gradients; A = 0 makes z constant in V and W (dW = dVz = 0) while
+    dA = sum dz * softplus(x); one q-head per kv-head gives dVz = outer(dx, w)."""
+    V, W, A, dz, H_q = _mask_case(seed=8, H_q=2, H_kv=2)
+    dW, dA, dVz = orc.mask_backward(V, W, A, np.zeros_like(dz), H_q)
+    assert not dW.any() and not dA.any() and not dVz.any()
+    dW, dA, dVz = orc.mask_backward(V, W, np.zeros_like(A), dz, H_q)
+    assert not dW.any() and not dVz.any()
+    sp = np.stack([orc.softplus(V[:, h, :] @ W[h]) for h in range(H_q)])
+    assert np.allclose(dA, (dz * sp).sum(1))
