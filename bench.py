@@ -215,6 +215,21 @@ def main():
         "stage_ms": stage_ms, "algorithmic_gflop": flops / 1e9,
         "roofline": roofline,
     }
+    if wl.backward:
+        # not part of the step: the gradient of the content scores (dz -> dW, dA, dV += dVz), HBM-bound
+        dW = torch.empty((wl.H_q, wl.d), device=dev)
+        dA = torch.empty((wl.H_q,), device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        B.dma_mask_bwd(case.shape, case.V, case.W, case.A, case.dz, dW, dA, case.dV, True)
+        for i in range(5):
+            ev[i].record()
+            B.dma_mask_bwd(case.shape, case.V, case.W, case.A, case.dz, dW, dA, case.dV, True)
+        ev[5].record()
+        torch.cuda.synchronize()
+        mb_ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
+        mb_bytes = 3 * inp.T * wl.H_kv * wl.d * 2 + 4 * wl.H_q * inp.T   # V read, dV read + write, dz read
+        out["mask_bwd"] = {"ms": mb_ms, "algorithmic_bytes": mb_bytes, "GB/s": mb_bytes / (mb_ms * 1e-3) / 1e9,
+                           "hbm_peak_GB/s": 8000.0}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, wl, flops / wl.H_q)
     print(json.dumps(out))

@@ -112,6 +112,21 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
             void* dQ, void* dK, void* dV, float* dz, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Gradient of the content scores (the chain rule of Eq. 3; Section 6: the bias is the path by
+ * which gradients reach the score parameters).  With x = w_h . v_{g(h), j}, z = exp(A_h softplus(x)):
+ *   dz  in  [H_q, T]        the gradient that dma_bwd returned for the bias
+ *   dW  out [H_q, d] f32    dW_h = sum_j dx_{h,j} v_{g(h),j},  dx = dz z A_h sigmoid(x)
+ *   dA  out [H_q]    f32    dA_h = sum_j dz z softplus(x)
+ *   dV  [T, H_kv, d], dtype of V: the part of dV that flows through z,
+ *       sum over the q-heads h of kv-head g of dx_{h,j} w_h; written if accumulate == 0, added
+ *       to the existing contents (e.g. the dV of dma_bwd; one rounding of the sum) otherwise.
+ * z is recomputed from V, W, A.  dW and dA are accumulated with floating-point atomics.  No
+ * workspace; shape->k, n_docs and softmax_scale are not used.  Errors as for the other entry points.
+ */
+int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const float* A, const float* dz,
+                 float* dW, float* dA, void* dV, int accumulate, void* stream);
+
+/*
  * Per-stage timing aid.  dma_mask_gen, dma_fwd and dma_bwd each launch several kernels, so a
  * caller cannot bracket one of them with events from outside.  `events` is a HOST array of
  * 2 * DMA_N_STAGES hipEvent_t handles (as void*) owned by the caller, or NULL to switch the aid

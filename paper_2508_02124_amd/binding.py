@@ -55,6 +55,8 @@ def lib():
         L.dma_fwd.restype = i32
         L.dma_bwd.argtypes = [shp] + [vp] * 15 + [sz, vp]
         L.dma_bwd.restype = i32
+        L.dma_mask_bwd.argtypes = [shp] + [vp] * 7 + [i32, vp]
+        L.dma_mask_bwd.restype = i32
         L.dma_profile_events.argtypes = [vp]
         L.dma_profile_events.restype = None
         L.dma_strerror.argtypes = [i32]
@@ -124,6 +126,11 @@ def dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, topk_idx, mask, stream=N
 def dma_fwd(shape, Q, K, V, z, expiry, mask, cu_seqlens, O, LSE, ws, ws_bytes, stream=None):
     _check(lib().dma_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(z), _ptr(expiry), _ptr(mask),
                          _ptr(cu_seqlens), _ptr(O), _ptr(LSE), _ptr(ws), int(ws_bytes), _stream(stream)), "dma_fwd")
+
+
+def dma_mask_bwd(shape, V, W, A, dz, dW, dA, dV, accumulate, stream=None):
+    _check(lib().dma_mask_bwd(ctypes.byref(shape), _ptr(V), _ptr(W), _ptr(A), _ptr(dz), _ptr(dW), _ptr(dA), _ptr(dV),
+                              int(bool(accumulate)), _stream(stream)), "dma_mask_bwd")
 
 
 def dma_bwd(shape, Q, K, V, O, dO, LSE, z, expiry, mask, cu_seqlens, dQ, dK, dV, dz, ws, ws_bytes, stream=None):

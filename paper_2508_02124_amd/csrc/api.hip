@@ -110,6 +110,15 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
   return launch_bwd(p, Q, K, V, O, dO, LSE, z, expiry, cu_seqlens, dQ, dK, dV, dz, (char*)ws, (hipStream_t)stream);
 }
 
+int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const float* A, const float* dz,
+                 float* dW, float* dA, void* dV, int accumulate, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!V || !W || !A || !dz || !dW || !dA || !dV) return DMA_EINVAL;
+  if (!aligned16(V) || !aligned16(W) || !aligned16(dz) || !aligned16(dW) || !aligned16(dV)) return DMA_EINVAL;
+  return launch_mask_bwd(*shape, V, W, A, dz, dW, dA, dV, accumulate != 0, (hipStream_t)stream);
+}
+
 void dma_profile_events(void** events) { dma::g_stage_events = events; }
 
 const char* dma_strerror(int status) {

@@ -123,6 +123,9 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
                    const float* dO, const float* LSE, const float* z, const int32_t* expiry,
                    const int32_t* cu, float* dQ, float* dK, float* dV, float* dz, char* ws, hipStream_t st);
 
+int launch_mask_bwd(const dma_shape& s, const void* V, const float* W, const float* A, const float* dz,
+                    float* dW, float* dA, void* dV, int accumulate, hipStream_t st);
+
 // stage events (see dma_profile_events): no-ops unless the caller armed them on this thread
 void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);

@@ -145,3 +145,25 @@ def test_cfg5_varlen(gpu):
     print("  dz", check_close("dz", case.host("dz")[0], dz[0], summand_abs=dza[0], srel=DZ_SREL, **T_BF16), flush=True)
     rows = sample_rows(np.random.default_rng(5), inp, [3, 9, 15], 6)
     check_rows(case, zg, rows, "cfg5", backward=True)
+
+
+def test_cfg3_mask_backward_full(gpu):
+    print("[case] cfg3 gradient of the content scores, dense", flush=True)
+    import torch
+    from paper_2508_02124_amd import binding as B
+    inp = wlmod.make_inputs(wlmod.CONFIGS["cfg3"])
+    wl = inp.wl
+    case = DeviceCase(inp, gpu)
+    r = np.random.default_rng(33)
+    dz = (r.standard_normal((wl.H_q, inp.T)) * 0.1).astype(np.float32)
+    dzd = torch.from_numpy(dz).to(gpu)
+    dW = torch.empty((wl.H_q, wl.d), device=gpu)
+    dA = torch.empty((wl.H_q,), device=gpu)
+    dV = torch.empty_like(case.V)
+    B.dma_mask_bwd(case.shape, case.V, case.W, case.A, dzd, dW, dA, dV, False)
+    rW, rA, rV = orc.mask_backward(inp.V, inp.W, inp.A, dz, wl.H_q)
+    # fp32 sums over 16384 tokens with atomics: error ~ sqrt(T) ulp of the summands
+    t32 = dict(atol=2e-3, rtol=1e-3, frob=1e-4)
+    print("  dW", check_close("dW", dW.cpu().numpy(), rW, **t32), flush=True)
+    print("  dA", check_close("dA", dA.cpu().numpy(), rA, **t32), flush=True)
+    print("  dVz", check_close("dVz", dV.float().cpu().numpy(), rV, **T_BF16), flush=True)

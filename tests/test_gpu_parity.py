@@ -11,6 +11,7 @@ import pytest
 import torch
 
 import oracle as orc
+from paper_2508_02124_amd import binding as B
 from paper_2508_02124_amd import workloads as wlmod
 from gpu_harness import BQ, DeviceCase, check_close, tol
 
@@ -170,3 +171,51 @@ def test_backward_heavy_ties(gpu):
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, z.astype(np.float64), inp.dO, inp.cu_seqlens, wl.k)
     for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, **tol(True)), flush=True)
+
+
+# ----------------------------------------------------------------------------- gradient of the content scores
+MASK_BWD_CASES = {
+    # name: (T, H_q, H_kv, d)  -- several 64-token tiles with a ragged tail, G = 1, 2, 4, 8
+    "tail_d64": (333, 4, 2, 64),
+    "g1_d128": (200, 3, 3, 128),
+    "g8_d128": (1000, 8, 1, 128),
+    "tiny": (5, 2, 1, 64),
+}
+
+
+@pytest.mark.parametrize("name", list(MASK_BWD_CASES))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_mask_backward(gpu, name, dtype):
+    print(f"[case] mask_bwd {name} {dtype}", flush=True)
+    import torch
+    T, H_q, H_kv, d = MASK_BWD_CASES[name]
+    r = np.random.default_rng(100 + list(MASK_BWD_CASES).index(name))
+    V = r.standard_normal((T, H_kv, d)).astype(np.float32)
+    if dtype == "bf16":
+        V = wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(V))
+    W = (r.standard_normal((H_q, d)) / np.sqrt(d)).astype(np.float32)
+    A = (-r.uniform(0.5, 2.0, H_q)).astype(np.float32)
+    dz = r.standard_normal((H_q, T)).astype(np.float32)
+    dV0 = r.standard_normal((T, H_kv, d)).astype(np.float32)
+    if dtype == "bf16":
+        dV0 = wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(dV0))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    shape = B.make_shape(T=T, n_docs=1, H_q=H_q, H_kv=H_kv, d=d, k=1,
+                         dtype=B.DMA_BF16 if dtype == "bf16" else B.DMA_F32)
+    dev = lambda x, dt=None: torch.from_numpy(np.ascontiguousarray(x)).to(gpu).to(dt or torch.float32)
+    Vd, Wd, Ad, dzd = dev(V, tdt), dev(W), dev(A), dev(dz)
+    dWd = torch.full((H_q, d), 7.0, device=gpu)          # outputs are overwritten, whatever they held
+    dAd = torch.full((H_q,), -3.0, device=gpu)
+    dVd = torch.full((T, H_kv, d), 5.0, device=gpu, dtype=tdt)
+    B.dma_mask_bwd(shape, Vd, Wd, Ad, dzd, dWd, dAd, dVd, False)
+    dW, dA, dVz = orc.mask_backward(V, W, A, dz, H_q)
+    t = tol(dtype == "bf16")
+    t32 = dict(atol=1e-4, rtol=1e-4, frob=1e-5)           # fp32 sums over T rows, fp32 exp / log
+    print("  dW", check_close("dW", dWd.cpu().numpy(), dW, **t32), flush=True)
+    print("  dA", check_close("dA", dAd.cpu().numpy(), dA, **t32), flush=True)
+    print("  dVz", check_close("dVz", dVd.float().cpu().numpy(), dVz, **(t if dtype == "bf16" else t32)), flush=True)
+    # accumulate into an existing dV
+    dVd2 = dev(dV0, tdt)
+    B.dma_mask_bwd(shape, Vd, Wd, Ad, dzd, dWd, dAd, dVd2, True)
+    print("  dV+=", check_close("dV+dVz", dVd2.float().cpu().numpy(), dV0 + dVz, **(t if dtype == "bf16" else t32)), flush=True)
+    print("  dW again", check_close("dW", dWd.cpu().numpy(), dW, **t32), flush=True)
