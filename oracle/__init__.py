@@ -20,4 +20,5 @@ from .dma_oracle import (  # noqa: F401
     dma_rows,
     dma_keys,
     mask_backward,
+    dma_decode,
 )

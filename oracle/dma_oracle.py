@@ -36,7 +36,8 @@ and to torch SDPA (k >= L, constant z), sliding-window / sink closed forms,
 k = 1, all-equal z (tie rule), row sums, exact zeros, finite differences for
 all four gradients, algebraic identities, scalar triple-loop brute force, and
 the gather-loop formulation of Listing 1; mask_backward: central finite
-differences of Eq. 3 and torch autograd of the forward formula.  No function
+differences of Eq. 3 and torch autograd of the forward formula; dma_decode:
+the last rows of the dense forward oracle and of topk_indices.  No function
 here is unpinned.
 """
 from __future__ import annotations
@@ -50,7 +51,7 @@ __all__ = [
     "softplus", "z_scores", "kept_mask_definition", "kept_mask_ranked",
     "expiry_from_kept", "expiry_sequential", "topk_indices", "dma_forward",
     "dma_backward", "dma_forward_gather_loop", "dma_scalar_bruteforce",
-    "n_active_pairs", "dma_rows", "dma_keys", "mask_backward",
+    "n_active_pairs", "dma_rows", "dma_keys", "mask_backward", "dma_decode",
 ]
 
 
@@ -475,3 +476,42 @@ def dma_keys(Q, K, V, z, dO, LSE, O, cu_seqlens, k, keys, scale=None):
             dK += scale * (ds @ Q[rows, h])
         out.append(dict(dK=dK, dV=dV, dz=dz, dz_abs=dz_abs))
     return out
+
+
+# --------------------------------------------------------------------------- decode (one new row per sequence)
+def dma_decode(q, K, V, z, cu_seqlens, k, scale=None):
+    """Eq. 4-6 for the newest row of every sequence: the row is the last one of its document, so
+    its candidates are all n keys of the document; it keeps the min(k, n) best by (z descending,
+    index ascending), and o = softmax(scale q.K_kept + z_kept) V_kept.
+
+    q [n_docs, H_q, d]; K, V [T, H_kv, d]; z [H_q, T].  Returns o [n_docs, H_q, d],
+    lse [H_q, n_docs] and kept: list over documents of int arrays [H_q, min(k, n)] (global row
+    indices, ascending).  An empty document gives o = 0 and lse = -inf.
+    """
+    q, K, V, z = _as64(q), _as64(K), _as64(V), _as64(z)
+    n_docs, H_q, d = q.shape
+    H_kv = K.shape[1]
+    G = H_q // H_kv
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    o = np.zeros((n_docs, H_q, d))
+    lse = np.full((H_q, n_docs), -np.inf)
+    kept = []
+    for b in range(n_docs):
+        a, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        n = e - a
+        kk = min(k, n)
+        kept_b = np.zeros((H_q, kk), dtype=np.int64)
+        for h in range(H_q):
+            if n == 0:
+                continue
+            zz = z[h, a:e]
+            order = sorted(range(n), key=lambda j: (-zz[j], j))   # larger z first, lower index on ties
+            idx = np.array(sorted(order[:kk]), dtype=np.int64)
+            s = scale * (K[a + idx, h // G, :] @ q[b, h]) + zz[idx]
+            mx = s.max()
+            p = np.exp(s - mx)
+            lse[h, b] = mx + math.log(p.sum())
+            o[b, h] = (p / p.sum()) @ V[a + idx, h // G, :]
+            kept_b[h] = a + idx
+        kept.append(kept_b)
+    return o, lse, kept

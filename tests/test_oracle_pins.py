@@ -386,3 +386,26 @@ def test_mask_backward_special_cases():
     assert not dW.any() and not dVz.any()
     sp = np.stack([orc.softplus(V[:, h, :] @ W[h]) for h in range(H_q)])
     assert np.allclose(dA, (dz * sp).sum(1))
+
+
+# ----------------------------------------------------------------------------- decode (last row of every document)
+@pytest.mark.parametrize("ties", [False, True])
+def test_decode_equals_last_rows_of_the_dense_forward(ties):
+    """Catches: candidates not being the whole document, a wrong tie rule in the selection, the bias
+    left out, a kv-head mix-up under GQA, k larger than a document."""
+    Q, K, V, dO, z = rand_case(n=90, H_q=4, H_kv=2, d=8, seed=21, ties=ties)
+    cu = np.array([0, 37, 37, 60, 90])            # includes an empty document and one shorter than k
+    k = 25
+    last = [int(e) - 1 for a, e in zip(cu[:-1], cu[1:])]
+    q = np.stack([Q[max(i, 0)] for i in last])     # (the empty document's query is never used)
+    o, lse, kept = orc.dma_decode(q, K, V, z, cu, k)
+    O, LSE = orc.dma_forward(Q, K, V, z, cu, k)
+    for b, (a, e) in enumerate(zip(cu[:-1], cu[1:])):
+        if e == a:
+            assert not o[b].any() and np.isneginf(lse[:, b]).all() and kept[b].shape[1] == 0
+            continue
+        assert np.allclose(o[b], O[e - 1], rtol=1e-12, atol=1e-14)
+        assert np.allclose(lse[:, b], LSE[:, e - 1], rtol=1e-12, atol=1e-14)
+        for h in range(4):
+            ref = orc.topk_indices(z[h, a:e], k)[-1]
+            assert (kept[b][h] == ref[ref >= 0] + a).all()
