@@ -230,6 +230,31 @@ def main():
         mb_bytes = 3 * inp.T * wl.H_kv * wl.d * 2 + 4 * wl.H_q * inp.T   # V read, dV read + write, dz read
         out["mask_bwd"] = {"ms": mb_ms, "algorithmic_bytes": mb_bytes, "GB/s": mb_bytes / (mb_ms * 1e-3) / 1e9,
                            "hbm_peak_GB/s": 8000.0}
+    if wl.name == HEADLINE and not args.k:
+        # not part of the step: decode of one new row against a 65536-token cache (HBM-bound)
+        Ld, kd = 65536, 2048
+        dshape = B.make_shape(T=Ld, n_docs=1, H_q=wl.H_q, H_kv=wl.H_kv, d=wl.d, k=kd)
+        g = torch.Generator(device=dev).manual_seed(5)
+        Kc = torch.randn((Ld, wl.H_kv, wl.d), device=dev, generator=g).to(torch.bfloat16)
+        Vc = torch.randn((Ld, wl.H_kv, wl.d), device=dev, generator=g).to(torch.bfloat16)
+        qc = torch.randn((1, wl.H_q, wl.d), device=dev, generator=g).to(torch.bfloat16)
+        zc = torch.rand((wl.H_q, Ld), device=dev, generator=g)
+        cuc = torch.tensor([0, Ld], dtype=torch.int32, device=dev)
+        oc = torch.empty_like(qc)
+        lc = torch.empty((wl.H_q, 1), device=dev)
+        kb = B.dma_decode_kept_bytes(dshape)
+        kc = torch.empty(kb // 4, dtype=torch.int32, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        B.dma_decode(dshape, qc, Kc, Vc, zc, cuc, oc, lc, kc, kb)
+        for i in range(5):
+            ev[i].record()
+            B.dma_decode(dshape, qc, Kc, Vc, zc, cuc, oc, lc, kc, kb)
+        ev[5].record()
+        torch.cuda.synchronize()
+        d_ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
+        d_bytes = 4 * wl.H_q * Ld + wl.H_q * kd * (2 * wl.d * 2 + 4)     # z once; K, V rows and z of the kept keys
+        out["decode"] = {"workload": f"1 x {Ld}-token cache, H_q={wl.H_q} H_kv={wl.H_kv} d={wl.d} k={kd}", "ms": d_ms,
+                         "algorithmic_bytes": d_bytes, "GB/s": d_bytes / (d_ms * 1e-3) / 1e9, "hbm_peak_GB/s": 8000.0}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, wl, flops / wl.H_q)
     print(json.dumps(out))

@@ -127,6 +127,27 @@ int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const fl
                  float* dW, float* dA, void* dV, int accumulate, void* stream);
 
 /*
+ * Decode: the newest row of every sequence against its KV cache (Eq. 4-6 for one query row; the
+ * regime of the paper's largest speed-ups, Section 5).  Sequence b occupies rows
+ * [cu_seqlens[b], cu_seqlens[b+1]) of K, V and z, its last row being the new token; that row's
+ * candidates are all n keys of the sequence, of which it keeps the min(k, n) best by
+ * (z descending, index ascending).
+ *   q     in  [n_docs, H_q, d]   the query of the last row of each sequence
+ *   K, V  in  [T, H_kv, d];  z in [H_q, T] (the caller appends the new token's score, e.g. with
+ *             dma_mask_gen on the new row or its own Eq. 3)
+ *   o     out [n_docs, H_q, d];  lse out [H_q, n_docs] (natural log; -inf and o = 0 for an empty sequence)
+ *   kept  out [n_docs, H_q, min(k, T)] int32: the kept keys of each (sequence, head) as global row
+ *             indices, ascending, the first min(k, n) entries valid.  The buffer also carries
+ *             the kernels' scratch behind that array (per-chunk partial outputs), so it is
+ *             required and must hold dma_decode_kept_bytes(shape) bytes (DMA_EWORKSPACE otherwise).
+ * Stateless: the selection is redone from z on every call (z is n floats per head, the gathered
+ * K/V rows are min(k, n) d-vectors; both are read once or a few times).  No mask plan is needed.
+ */
+size_t dma_decode_kept_bytes(const dma_shape* shape);
+int dma_decode(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
+               const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, size_t kept_bytes, void* stream);
+
+/*
  * Per-stage timing aid.  dma_mask_gen, dma_fwd and dma_bwd each launch several kernels, so a
  * caller cannot bracket one of them with events from outside.  `events` is a HOST array of
  * 2 * DMA_N_STAGES hipEvent_t handles (as void*) owned by the caller, or NULL to switch the aid

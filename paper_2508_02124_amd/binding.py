@@ -57,6 +57,10 @@ def lib():
         L.dma_bwd.restype = i32
         L.dma_mask_bwd.argtypes = [shp] + [vp] * 7 + [i32, vp]
         L.dma_mask_bwd.restype = i32
+        L.dma_decode_kept_bytes.argtypes = [shp]
+        L.dma_decode_kept_bytes.restype = sz
+        L.dma_decode.argtypes = [shp] + [vp] * 8 + [sz, vp]
+        L.dma_decode.restype = i32
         L.dma_profile_events.argtypes = [vp]
         L.dma_profile_events.restype = None
         L.dma_strerror.argtypes = [i32]
@@ -126,6 +130,15 @@ def dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, topk_idx, mask, stream=N
 def dma_fwd(shape, Q, K, V, z, expiry, mask, cu_seqlens, O, LSE, ws, ws_bytes, stream=None):
     _check(lib().dma_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(z), _ptr(expiry), _ptr(mask),
                          _ptr(cu_seqlens), _ptr(O), _ptr(LSE), _ptr(ws), int(ws_bytes), _stream(stream)), "dma_fwd")
+
+
+def dma_decode_kept_bytes(shape):
+    return int(lib().dma_decode_kept_bytes(ctypes.byref(shape)))
+
+
+def dma_decode(shape, q, K, V, z, cu_seqlens, o, lse, kept, kept_bytes, stream=None):
+    _check(lib().dma_decode(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(z), _ptr(cu_seqlens), _ptr(o),
+                            _ptr(lse), _ptr(kept), int(kept_bytes), _stream(stream)), "dma_decode")
 
 
 def dma_mask_bwd(shape, V, W, A, dz, dW, dA, dV, accumulate, stream=None):

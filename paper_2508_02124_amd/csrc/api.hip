@@ -119,6 +119,24 @@ int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const fl
   return launch_mask_bwd(*shape, V, W, A, dz, dW, dA, dV, accumulate != 0, (hipStream_t)stream);
 }
 
+size_t dma_decode_kept_bytes(const dma_shape* shape) {
+  if (check_shape(shape) != DMA_OK) return 0;
+  const size_t kcap = (size_t)(shape->k < shape->T ? shape->k : shape->T);
+  return align_up((size_t)shape->n_docs * shape->H_q * kcap * 4, 256) + align_up(decode_part_floats(*shape) * 4, 256);
+}
+
+int dma_decode(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
+               const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, size_t kept_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!q || !K || !V || !z || !cu_seqlens || !o || !lse) return DMA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(z) || !aligned16(o) || !aligned16(kept))
+    return DMA_EINVAL;
+  if (!kept || kept_bytes < dma_decode_kept_bytes(shape)) return DMA_EWORKSPACE;
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->d);
+  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, o, lse, kept, (hipStream_t)stream);
+}
+
 void dma_profile_events(void** events) { dma::g_stage_events = events; }
 
 const char* dma_strerror(int status) {

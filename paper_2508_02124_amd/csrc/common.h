@@ -126,6 +126,10 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
 int launch_mask_bwd(const dma_shape& s, const void* V, const float* W, const float* A, const float* dz,
                     float* dW, float* dA, void* dV, int accumulate, hipStream_t st);
 
+size_t decode_part_floats(const dma_shape& s);
+int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
+                  const int32_t* cu, void* o, float* lse, int32_t* kept, hipStream_t st);
+
 // stage events (see dma_profile_events): no-ops unless the caller armed them on this thread
 void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);

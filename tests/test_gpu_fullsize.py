@@ -167,3 +167,29 @@ def test_cfg3_mask_backward_full(gpu):
     print("  dW", check_close("dW", dW.cpu().numpy(), rW, **t32), flush=True)
     print("  dA", check_close("dA", dA.cpu().numpy(), rA, **t32), flush=True)
     print("  dVz", check_close("dVz", dV.float().cpu().numpy(), rV, **T_BF16), flush=True)
+
+
+def test_decode_long_cache(gpu):
+    print("[case] decode against a 65536-token cache (cfg4 shape, k = 2048): kept sets exact, outputs vs oracle", flush=True)
+    import torch
+    from paper_2508_02124_amd import binding as B
+    wl = wlmod.CONFIGS["cfg4"].with_k(2048)
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen()                                    # only for z (Eq. 3 on the device)
+    zg = case.host("z").astype(np.float64)
+    q = inp.Q[-1:].copy()                              # the query of the last row, [1, H_q, d]
+    qd = case.Q[-1:].contiguous()
+    shape = case.shape
+    kept = torch.empty(B.dma_decode_kept_bytes(shape) // 4, dtype=torch.int32, device=gpu)
+    o = torch.empty((1, wl.H_q, wl.d), dtype=torch.bfloat16, device=gpu)
+    lse = torch.empty((wl.H_q, 1), device=gpu)
+    B.dma_decode(shape, qd, case.K, case.V, case.z, case.cu, o, lse, kept, kept.numel() * 4)
+    ro, rl, rk = orc.dma_decode(q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k)
+    got_k = kept.cpu().numpy()[: wl.H_q * wl.k].reshape(1, wl.H_q, wl.k)
+    assert (got_k[0] == rk[0]).all()
+    print("  o", check_close("o", o.float().cpu().numpy(), ro, **T_BF16), flush=True)
+    print("  lse", check_close("lse", lse.cpu().numpy(), rl, **T_BF16), flush=True)
+    # the same row through the prefill path
+    case.fwd()
+    print("  o vs dma_fwd last row", check_close("o", o.float().cpu().numpy()[0], case.host("O")[-1], **T_BF16), flush=True)

@@ -219,3 +219,59 @@ def test_mask_backward(gpu, name, dtype):
     B.dma_mask_bwd(shape, Vd, Wd, Ad, dzd, dWd, dAd, dVd2, True)
     print("  dV+=", check_close("dV+dVz", dVd2.float().cpu().numpy(), dV0 + dVz, **(t if dtype == "bf16" else t32)), flush=True)
     print("  dW again", check_close("dW", dWd.cpu().numpy(), dW, **t32), flush=True)
+
+
+# ----------------------------------------------------------------------------- decode (newest row of every sequence)
+DECODE_CASES = {
+    # name: (doc lengths, H_q, H_kv, d, k, tie levels or 0)
+    "varlen_d64": ((300, 0, 1, 70, 1500), 4, 2, 64, 64, 0),
+    "gqa_d128": ((2500, 129), 8, 2, 128, 128, 0),
+    "ties": ((900, 400), 2, 2, 64, 100, 5),
+    "k_ge_len": ((50, 200), 2, 1, 128, 512, 0),
+}
+
+
+@pytest.mark.parametrize("name", list(DECODE_CASES))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode(gpu, name, dtype):
+    print(f"[case] decode {name} {dtype}", flush=True)
+    lens, H_q, H_kv, d, k, levels = DECODE_CASES[name]
+    r = np.random.default_rng(200 + list(DECODE_CASES).index(name))
+    T, n_docs = sum(lens), len(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rnd = lambda *s: r.standard_normal(s).astype(np.float32)
+    q, K, V = rnd(n_docs, H_q, d), rnd(T, H_kv, d), rnd(T, H_kv, d)
+    z = r.uniform(0.05, 1.0, size=(H_q, T)).astype(np.float32)
+    if levels:
+        z = (np.round(z * levels) / levels + 0.125).astype(np.float32)     # heavy ties across the threshold
+    if dtype == "bf16":
+        q, K, V = (wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(x)) for x in (q, K, V))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    shape = B.make_shape(T=T, n_docs=n_docs, H_q=H_q, H_kv=H_kv, d=d, k=k,
+                         dtype=B.DMA_BF16 if dtype == "bf16" else B.DMA_F32)
+    dev = lambda x, dt=torch.float32: torch.from_numpy(np.ascontiguousarray(x)).to(gpu).to(dt)
+    kcap = min(k, T)
+    kept = torch.full((n_docs, H_q, kcap), -7, dtype=torch.int32, device=gpu)
+    o = torch.full((n_docs, H_q, d), 3.0, dtype=tdt, device=gpu)
+    lse = torch.full((H_q, n_docs), 3.0, device=gpu)
+    nb = B.dma_decode_kept_bytes(shape)
+    assert nb >= kept.numel() * 4
+    pad = torch.empty(nb, dtype=torch.uint8, device=gpu)                  # buffer of exactly the requested size
+    kept_buf = pad[:kept.numel() * 4].view(torch.int32).view(n_docs, H_q, kcap)
+    B.dma_decode(shape, dev(q, tdt), dev(K, tdt), dev(V, tdt), dev(z), torch.from_numpy(cu).to(gpu), o, lse,
+                 kept_buf, nb)
+    ro, rl, rk = orc.dma_decode(q, K, V, z, cu, k)
+    got_k = kept_buf.cpu().numpy()
+    for b in range(n_docs):
+        kk = rk[b].shape[1]
+        assert (got_k[b, :, :kk] == rk[b]).all(), f"kept set of sequence {b}"     # bit-exact, ascending
+    t = tol(dtype == "bf16")
+    print("  o", check_close("o", o.float().cpu().numpy(), ro, **t), flush=True)
+    got_l = lse.cpu().numpy()
+    fin = np.isfinite(rl)
+    assert (np.isneginf(got_l) == ~fin).all()
+    print("  lse", check_close("lse", got_l[fin], rl[fin], **(t if dtype == "bf16" else tol(False))), flush=True)
+    with pytest.raises(B.DmaError) as e:                                    # kept buffer too small
+        B.dma_decode(shape, dev(q, tdt), dev(K, tdt), dev(V, tdt), dev(z), torch.from_numpy(cu).to(gpu), o, lse,
+                     kept_buf, nb - 256 if nb > 256 else 0)
+    assert e.value.status == B.DMA_EWORKSPACE
