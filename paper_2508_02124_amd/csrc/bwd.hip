@@ -185,7 +185,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
       if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) continue;
     }
 
-#pragma unroll 1
+#pragma unroll
     for (int kb = 0; kb < 2; kb++) {
       bf16x8 dsb[2];  // the two 16-key halves
       {
