@@ -14,7 +14,8 @@
 //    resident of a column changes, the finished key is flushed with a handful of fp32 atomics (dK
 //    and dV are shared by the q-heads of a group) and the column is re-armed.  The same kernel, in
 //    "partial" mode, handles the keys that enter or expire inside a block: columns come from the
-//    block's partial list, elements are masked with j <= i < e_j, and the sweep is that one block.
+//    blocks' partial lists, elements are masked with j <= i < e_j, and every column changes at
+//    every block of the (short) sweep.
 //
 // The dS / P blocks are produced in the accumulator layout of S = Q K^T (dkv) or S^T = K Q^T (dq),
 // which is exactly the B-operand layout of the products that consume them; the other operand of

@@ -8,7 +8,7 @@
 namespace dma {
 
 // ------------------------------------------------------------------ tiling constants
-constexpr int BQ = 256;        // query rows per block (one workgroup of the attention kernels: 4 waves x 64 rows)
+constexpr int BQ = 256;        // query rows per block (one workgroup of the query-stationary kernels: 8 waves x 32 rows)
 constexpr int KT = 64;         // keys per tile of the query-stationary kernels
 constexpr int MAXPART = 2 * BQ;  // a block has at most BQ entering + BQ expiring keys
 constexpr int SG = 128;        // slot columns per workgroup of the key-stationary backward

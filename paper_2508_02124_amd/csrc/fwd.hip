@@ -1,17 +1,19 @@
 // Forward pass (Eq. 5-6; online softmax of Alg. 1, query-stationary so O, l, m stay in registers).
 //
 // One workgroup (8 waves) = one block of BQ = 256 query rows of one head; wave w owns rows
-// 32w .. 32w+31, and the two waves that share a SIMD overlap each other's MFMA and softmax work.  The keys a block needs are gathered, KT at a time, into a ring of
-// LDS stages by asynchronous global->LDS copies issued NS-1 tiles ahead (no staging registers):
-// first the slot table row of the block (residents active for every row of the block: no mask
-// needed, empty slots carry z = -inf), then the block's partial list (keys entering or expiring
-// inside the block: masked per element with j <= i < e_j).  The key ids of a tile are themselves
-// copied into an LDS ring NS-1 tiles before the tile's K/V copies are issued, so no register ever
-// waits on a load.
+// 32w .. 32w+31, and the two waves that share a SIMD overlap each other's MFMA and softmax work.
+// The keys a block needs are gathered, KT at a time, into a ring of LDS stages by asynchronous
+// global->LDS copies issued NS-1 tiles ahead (no staging registers): first the slot table row of
+// the block (residents active for every row of the block: no mask needed, empty slots carry
+// z = -inf), then the block's partial list (keys entering or expiring inside the block: pairs
+// outside j <= i < e_j start their score at -inf).  The key ids of a tile are themselves copied
+// into an LDS ring NS-1 tiles before the tile's K/V copies are issued, so no register ever waits
+// on a load.
 //
 // Per tile the wave computes S^T = K Q^T (keys x queries) so that each lane holds one query column
 // per block: the softmax statistics are per lane, and the exponentiated block is already laid out
-// as the B operand of O^T += V^T P^T.
+// as the B operand of O^T += V^T P^T.  The bias z is not added after the product: the accumulator
+// starts at z / scale, so scale * acc is the biased score and one FMA gives the exp2 argument.
 #include "common.h"
 
 namespace dma {
