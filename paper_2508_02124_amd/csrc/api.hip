@@ -122,7 +122,8 @@ int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const fl
 size_t dma_decode_kept_bytes(const dma_shape* shape) {
   if (check_shape(shape) != DMA_OK) return 0;
   const size_t kcap = (size_t)(shape->k < shape->T ? shape->k : shape->T);
-  return align_up((size_t)shape->n_docs * shape->H_q * kcap * 4, 256) + align_up(decode_part_floats(*shape) * 4, 256);
+  return align_up((size_t)shape->n_docs * shape->H_q * kcap * 4, 256) + align_up(decode_part_floats(*shape) * 4, 256) +
+         align_up(decode_sel_words(*shape) * 4, 256);
 }
 
 int dma_decode(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,

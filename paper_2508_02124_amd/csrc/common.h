@@ -127,6 +127,7 @@ int launch_mask_bwd(const dma_shape& s, const void* V, const float* W, const flo
                     float* dW, float* dA, void* dV, int accumulate, hipStream_t st);
 
 size_t decode_part_floats(const dma_shape& s);
+size_t decode_sel_words(const dma_shape& s);
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
                   const int32_t* cu, void* o, float* lse, int32_t* kept, hipStream_t st);
 

@@ -15,122 +15,203 @@ __device__ __forceinline__ uint32_t desc_key_u32(float z) {
   return ~u;
 }
 
-// Selection: one workgroup (16 waves) per (sequence, q-head).
-//  (1) radix select, most significant byte first: the key value `thr` of the kk-th best score and
-//      how many keys equal to it are still needed (`need_eq`, the ones with the lowest indices);
-//  (2) ordered compaction of the kept indices into `kept` (ascending).
-__global__ __launch_bounds__(1024) void decode_select_kernel(const float* __restrict__ z, const int32_t* __restrict__ cu,
-                                                             int32_t* kept, int T, int H_q, int k) {
-  const int b = blockIdx.x, h = blockIdx.y;
-  const int a = cu[b], n = cu[b + 1] - a;
+// ---- selection of the kept set, spread over nsl slices of every (sequence, q-head) so that it
+// uses the whole chip: four histogram launches (radix select of the kk-th best score, most
+// significant byte first, per-pass histograms accumulated in global memory), one counting launch
+// and one ordered-compaction launch.  Every workgroup re-derives the digits already fixed from the
+// finished histograms (256 counters per pass), so no launch has to hand state to the next one.
+struct DecSel {
+  const float* z;
+  const int32_t* cu;
+  int32_t* kept;
+  uint32_t* hist;  // [4][n_docs * H_q][256], zeroed before the first pass
+  uint32_t* cnt;   // [n_docs * H_q][nsl][4 waves][2]: keys better than / equal to the threshold
+  int T, H_q, k, nsl;
+};
+
+// Wave 0: the digit of `h256` at which the running count reaches `remaining`; updates prefix / remaining.
+__device__ __forceinline__ void dec_pick(const uint32_t* h256, int l, uint32_t& prefix, uint32_t& remaining) {
+  uint32_t c4[4], sum = 0;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    c4[i] = h256[4 * l + i];
+    sum += c4[i];
+  }
+  uint32_t inc = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t t = __shfl_up(inc, off);
+    if (l >= off) inc += t;
+  }
+  uint32_t run = inc - sum, dig = 0, rem = 0;
+  bool mine = false;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    if (!mine && run < remaining && remaining <= run + c4[i]) {
+      mine = true;
+      dig = 4 * l + i;
+      rem = remaining - run;
+    }
+    run += c4[i];
+  }
+  const unsigned long long m = __ballot(mine);
+  const int src = __ffsll((long long)m) - 1;  // exactly one lane finds it (remaining >= 1 and <= total)
+  prefix = (prefix << 8) | (uint32_t)__shfl((int)dig, src);
+  remaining = (uint32_t)__shfl((int)rem, src);
+}
+
+struct DecSlice {
+  int a, n, kk, j0, j1;  // document start / length, kept count, this wave's key range [j0, j1)
+};
+__device__ __forceinline__ DecSlice dec_slice(const DecSel& p, int b, int sl, int w) {
+  DecSlice s;
+  s.a = p.cu[b];
+  s.n = p.cu[b + 1] - s.a;
+  s.kk = p.k < s.n ? p.k : s.n;
+  const int slen = ((s.n + p.nsl - 1) / p.nsl + 255) / 256 * 256;
+  const int wlen = slen / 4;
+  s.j0 = min(s.n, sl * slen + w * wlen);
+  s.j1 = min(s.n, sl * slen + (w + 1) * wlen);
+  return s;
+}
+
+// Threshold state after the passes above `pass` (pass = -1: after all four).
+__device__ __forceinline__ void dec_state(const DecSel& p, int bh, int nbh, int pass, int kk, int l, uint32_t* sh2) {
+  if (threadIdx.x < 64) {
+    uint32_t prefix = 0, remaining = (uint32_t)kk;
+    for (int q = 3; q > pass; q--) dec_pick(p.hist + ((size_t)q * nbh + bh) * 256, l, prefix, remaining);
+    if (l == 0) {
+      sh2[0] = prefix;
+      sh2[1] = remaining;
+    }
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void decode_hist_kernel(DecSel p, int pass) {
+  const int bh = blockIdx.x, b = bh / p.H_q, h = bh % p.H_q, sl = blockIdx.y, nbh = gridDim.x;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-  const int kcap = k < T ? k : T;
-  int32_t* list = kept + ((size_t)b * H_q + h) * kcap;
-  if (n <= 0) return;
-  const int kk = k < n ? k : n;
-  const float* zh = z + (size_t)h * T + a;
+  const DecSlice s = dec_slice(p, b, sl, w);
+  if (s.n <= 0 || s.kk == s.n) return;  // (workgroup-uniform)
   // every digit has 32 sub-counters (one per lane pair), so that the lanes of a wave that hit the
   // same digit (scores share their leading bits) do not serialise on one LDS address
   __shared__ uint32_t hist[256 * 32];
-  __shared__ uint32_t sel[2];     // selected digit, remaining count
-  __shared__ uint32_t wcnt[2][16];
-  uint32_t prefix = 0, remaining = (uint32_t)kk;
-  if (kk < n) {
-    for (int pass = 3; pass >= 0; pass--) {
-      for (int i = tid; i < 256 * 32; i += 1024) hist[i] = 0;
-      __syncthreads();
-      const int sh = 8 * pass;
-      for (int j0 = tid; j0 < n; j0 += 8 * 1024) {  // eight loads in flight per lane
-        float zv[8];
+  __shared__ uint32_t st[2];
+  for (int i = tid; i < 256 * 32; i += 256) hist[i] = 0;
+  dec_state(p, bh, nbh, pass, s.kk, l, st);
+  const uint32_t prefix = st[0];
+  const float* zh = p.z + (size_t)h * p.T + s.a;
+  const int sh = 8 * pass;
+  for (int j0 = s.j0; j0 < s.j1; j0 += 8 * 64) {  // eight loads in flight per lane
+    float zv[8];
 #pragma unroll
-        for (int u = 0; u < 8; u++) zv[u] = j0 + u * 1024 < n ? zh[j0 + u * 1024] : 0.f;
+    for (int u = 0; u < 8; u++) zv[u] = j0 + u * 64 + l < s.j1 ? zh[j0 + u * 64 + l] : 0.f;
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
-          const uint32_t key = desc_key_u32(zv[u]);
-          if (j0 + u * 1024 < n && (pass == 3 || (key >> (sh + 8)) == prefix)) atomicAdd(&hist[((key >> sh) & 255u) * 32 + (l & 31)], 1u);
-        }
-      }
-      __syncthreads();
-      if (w == 0) {  // the digit at which the running count reaches `remaining`
-        uint32_t c4[4], s = 0;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          c4[i] = 0;
-          for (int sc = 0; sc < 32; sc++) c4[i] += hist[(4 * l + i) * 32 + ((sc + l) & 31)];
-          s += c4[i];
-        }
-        uint32_t inc = s;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const uint32_t t = __shfl_up(inc, off);
-          if (l >= off) inc += t;
-        }
-        uint32_t run = inc - s;  // keys with a smaller digit than 4l
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          if (run < remaining && remaining <= run + c4[i]) {
-            sel[0] = 4 * l + i;
-            sel[1] = remaining - run;
-          }
-          run += c4[i];
-        }
-      }
-      __syncthreads();
-      prefix = (prefix << 8) | sel[0];
-      remaining = sel[1];
-      __syncthreads();
+    for (int u = 0; u < 8; u++) {
+      const uint32_t key = desc_key_u32(zv[u]);
+      if (j0 + u * 64 + l < s.j1 && (pass == 3 || (key >> (sh + 8)) == prefix))
+        atomicAdd(&hist[((key >> sh) & 255u) * 32 + (l & 31)], 1u);
     }
   }
-  const uint32_t thr = prefix, need_eq = remaining;
-  // (2) ordered compaction: keys better than thr, and the first need_eq keys equal to thr
-  if (kk == n) {
-    for (int j = tid; j < n; j += 1024) list[j] = a + j;
-  } else {
-    // every wave owns a contiguous range of keys: count, prefix over the waves, then write in order
-    const unsigned long long lt = (1ull << l) - 1ull;
-    const int seg = ((n + 15) / 16 + 63) / 64 * 64;
-    const int j_begin = w * seg, j_end = min(n, j_begin + seg);
-    uint32_t cb = 0, ce = 0;
-    for (int j0 = j_begin; j0 < j_end; j0 += 8 * 64) {
-      float zv[8];
-#pragma unroll
-      for (int u = 0; u < 8; u++) zv[u] = j0 + u * 64 + l < j_end ? zh[j0 + u * 64 + l] : 0.f;
-#pragma unroll
-      for (int u = 0; u < 8; u++) {
-        const bool in = j0 + u * 64 + l < j_end;
-        const uint32_t key = desc_key_u32(zv[u]);
-        cb += (uint32_t)__popcll(__ballot(in && key < thr));
-        ce += (uint32_t)__popcll(__ballot(in && key == thr));
-      }
-    }
+  __syncthreads();
+  {
+    uint32_t c = 0;
+    for (int sc = 0; sc < 32; sc++) c += hist[tid * 32 + ((sc + tid) & 31)];
+    if (c) atomicAdd(p.hist + ((size_t)pass * nbh + bh) * 256 + tid, c);
+  }
+}
+
+__global__ __launch_bounds__(256) void decode_count_kernel(DecSel p) {
+  const int bh = blockIdx.x, b = bh / p.H_q, h = bh % p.H_q, sl = blockIdx.y, nbh = gridDim.x;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const DecSlice s = dec_slice(p, b, sl, w);
+  uint32_t* out = p.cnt + (((size_t)bh * p.nsl + sl) * 4 + w) * 2;
+  if (s.n <= 0 || s.kk == s.n) {  // everything is kept
     if (l == 0) {
-      wcnt[0][w] = cb;
-      wcnt[1][w] = ce;
+      out[0] = (uint32_t)(s.j1 - s.j0);
+      out[1] = 0;
     }
-    __syncthreads();
-    uint32_t rb = 0, re = 0;  // better / equal keys before this wave's range, then before the chunk
-    for (int i = 0; i < w; i++) {
-      rb += wcnt[0][i];
-      re += wcnt[1][i];
-    }
-    for (int j0 = j_begin; j0 < j_end; j0 += 8 * 64) {
-      float zv[8];
+    return;
+  }
+  __shared__ uint32_t st[2];
+  dec_state(p, bh, nbh, -1, s.kk, l, st);
+  const uint32_t thr = st[0];
+  const float* zh = p.z + (size_t)h * p.T + s.a;
+  uint32_t cb = 0, ce = 0;
+  for (int j0 = s.j0; j0 < s.j1; j0 += 8 * 64) {
+    float zv[8];
 #pragma unroll
-      for (int u = 0; u < 8; u++) zv[u] = j0 + u * 64 + l < j_end ? zh[j0 + u * 64 + l] : 0.f;
+    for (int u = 0; u < 8; u++) zv[u] = j0 + u * 64 + l < s.j1 ? zh[j0 + u * 64 + l] : 0.f;
 #pragma unroll
-      for (int u = 0; u < 8; u++) {
-        const int j = j0 + u * 64 + l;
-        const uint32_t key = desc_key_u32(zv[u]);
-        const bool better = j < j_end && key < thr, equal = j < j_end && key == thr;
-        const unsigned long long bm = __ballot(better), em = __ballot(equal);
-        const uint32_t eq_before = re + (uint32_t)__popcll(em & lt);  // equal keys with a lower index
-        const uint32_t pos = rb + (uint32_t)__popcll(bm & lt) + min(eq_before, need_eq);
-        if (better || (equal && eq_before < need_eq)) list[pos] = a + j;
-        rb += (uint32_t)__popcll(bm);
-        re += (uint32_t)__popcll(em);
-      }
+    for (int u = 0; u < 8; u++) {
+      const bool in = j0 + u * 64 + l < s.j1;
+      const uint32_t key = desc_key_u32(zv[u]);
+      cb += (uint32_t)__popcll(__ballot(in && key < thr));
+      ce += (uint32_t)__popcll(__ballot(in && key == thr));
     }
   }
+  if (l == 0) {
+    out[0] = cb;
+    out[1] = ce;
+  }
+}
+
+// Ordered compaction: keys better than the threshold, and the first need_eq keys equal to it, in
+// ascending index order.
+__global__ __launch_bounds__(256) void decode_write_kernel(DecSel p) {
+  const int bh = blockIdx.x, b = bh / p.H_q, h = bh % p.H_q, sl = blockIdx.y, nbh = gridDim.x;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const DecSlice s = dec_slice(p, b, sl, w);
+  if (s.n <= 0) return;
+  const int kcap = p.k < p.T ? p.k : p.T;
+  int32_t* list = p.kept + (size_t)bh * kcap;
+  __shared__ uint32_t st[2];
+  uint32_t thr = 0xffffffffu, need_eq = 0;  // kk == n: every real key is "better"
+  if (s.kk < s.n) {
+    dec_state(p, bh, nbh, -1, s.kk, l, st);
+    thr = st[0];
+    need_eq = st[1];
+  }
+  // better / equal keys before this wave's range: the counts of all earlier (slice, wave) pairs
+  uint32_t rb = 0, re = 0;
+  {
+    const uint32_t* c = p.cnt + (size_t)bh * p.nsl * 8;
+    const int npairs = sl * 4 + w;
+    for (int i = l; i < npairs; i += 64) {
+      rb += c[2 * i];
+      re += c[2 * i + 1];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      rb += __shfl_xor(rb, off);
+      re += __shfl_xor(re, off);
+    }
+  }
+  const unsigned long long lt = (1ull << l) - 1ull;
+  const float* zh = p.z + (size_t)h * p.T + s.a;
+  for (int j0 = s.j0; j0 < s.j1; j0 += 8 * 64) {
+    float zv[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) zv[u] = j0 + u * 64 + l < s.j1 ? zh[j0 + u * 64 + l] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+      const int j = j0 + u * 64 + l;
+      const uint32_t key = desc_key_u32(zv[u]);
+      const bool in = j < s.j1;
+      const bool better = in && (s.kk == s.n || key < thr), equal = in && s.kk < s.n && key == thr;
+      const unsigned long long bm = __ballot(better), em = __ballot(equal);
+      const uint32_t eq_before = re + (uint32_t)__popcll(em & lt);  // equal keys with a lower index
+      const uint32_t pos = rb + (uint32_t)__popcll(bm & lt) + min(eq_before, need_eq);
+      if (better || (equal && eq_before < need_eq)) list[pos] = s.a + j;
+      rb += (uint32_t)__popcll(bm);
+      re += (uint32_t)__popcll(em);
+    }
+  }
+}
+
+__global__ void decode_zero_kernel(uint32_t* p, size_t n) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
 }
 
 // Keys per workgroup of the attention pass.
@@ -258,10 +339,27 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(const float* __restrict
   if (c == 0) lse[(size_t)h * n_docs + b] = (M + __builtin_amdgcn_logf(den)) * LN2;
 }
 
-// scratch after the kept lists: per (sequence, head) and chunk, D + 2 floats
+// slices per (sequence, head) of the selection: enough workgroups for the chip, slices of >= 1024 keys
+int decode_nsl(const dma_shape& s) {
+  const long nbh = (long)s.n_docs * s.H_q;
+  const int longest = s.max_seqlen > 0 && s.max_seqlen < s.T ? s.max_seqlen : s.T;
+  long nsl = (1024 + nbh - 1) / nbh;
+  const long cap = (longest + 1023) / 1024;
+  if (nsl > cap) nsl = cap;
+  if (nsl > 64) nsl = 64;
+  if (nsl < 1) nsl = 1;
+  return (int)nsl;
+}
+
+// scratch after the kept lists: per (sequence, head) and chunk, D + 2 floats of partial output;
+// then the selection's histograms and slice counts (as 32-bit words)
 size_t decode_part_floats(const dma_shape& s) {
   const size_t kcap = (size_t)(s.k < s.T ? s.k : s.T);
   return (size_t)s.n_docs * s.H_q * ((kcap + DEC_CHUNK - 1) / DEC_CHUNK) * (s.d + 2);
+}
+size_t decode_sel_words(const dma_shape& s) {
+  const size_t nbh = (size_t)s.n_docs * s.H_q;
+  return 4 * nbh * 256 + nbh * (size_t)decode_nsl(s) * 8;
 }
 
 template <typename TV, int D>
@@ -281,7 +379,20 @@ int launch_decode(const dma_shape& s, float scale, const void* q, const void* K,
   const int nsplit = (int)((kcap + DEC_CHUNK - 1) / DEC_CHUNK);
   float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(kept) +
                                          align_up((size_t)s.n_docs * s.H_q * kcap * 4, 256));
-  decode_select_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(z, cu, kept, s.T, s.H_q, s.k);
+  const int nbh = s.n_docs * s.H_q;
+  DecSel ds;
+  ds.z = z; ds.cu = cu; ds.kept = kept;
+  ds.hist = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(part) + align_up(decode_part_floats(s) * 4, 256));
+  ds.cnt = ds.hist + 4 * (size_t)nbh * 256;
+  ds.T = s.T; ds.H_q = s.H_q; ds.k = s.k; ds.nsl = decode_nsl(s);
+  {
+    const size_t nz = 4 * (size_t)nbh * 256;
+    decode_zero_kernel<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(ds.hist, nz);
+  }
+  const dim3 sgrid(nbh, ds.nsl);
+  for (int pass = 3; pass >= 0; pass--) decode_hist_kernel<<<sgrid, 256, 0, st>>>(ds, pass);
+  decode_count_kernel<<<sgrid, 256, 0, st>>>(ds);
+  decode_write_kernel<<<sgrid, 256, 0, st>>>(ds);
   if (s.dtype == DMA_BF16) {
     if (s.d == 128) launch_decode_t<__bf16, 128>(s, c2, q, K, V, z, cu, o, lse, kept, part, nsplit, st);
     else launch_decode_t<__bf16, 64>(s, c2, q, K, V, z, cu, o, lse, kept, part, nsplit, st);
