@@ -373,6 +373,12 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     lane_r[j] = rbase + l / CPR;
     lane_c[j] = (uint32_t)(((l % CPR) ^ TL::swz(lane_r[j])) * 16);
   }
+  uint32_t lane_off[WLW];  // byte offset of the lane's chunk from the step's first row, for a full step
+#pragma unroll
+  for (int j = 0; j < WLW; j++) {
+    lane_off[j] = (uint32_t)lane_r[j] * row_stride + lane_c[j];
+    settle(lane_off[j]);
+  }
   Cursor pc = {-1, 0, 0, 0};
   auto issue = [&](int v) {
     const int qs = v % NSUB;
@@ -384,10 +390,10 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     const size_t boff = ((size_t)rb * p.H_q + h) * D;
 #pragma unroll
     for (int j = 0; j < WLW; j++) {
-      const int r = min(lane_r[j], max(nvalid - 1, 0));
+      uint32_t off = lane_off[j];
+      if (nvalid < SUB) off = (uint32_t)min(lane_r[j], max(nvalid - 1, 0)) * row_stride + lane_c[j];  // (wave-uniform branch)
       const int rbase = ((lane_do[j] ? w + 8 * j - NWL / 2 : w + 8 * j)) * RPL;
-      dma16s((lane_do[j] ? p.dO : p.Q) + boff, (uint32_t)r * row_stride + lane_c[j],
-             (lane_do[j] ? ringdO : ringQ) + st * STILE + rbase * D);
+      dma16s((lane_do[j] ? p.dO : p.Q) + boff, off, (lane_do[j] ? ringdO : ringQ) + st * STILE + rbase * D);
     }
     if (w == 0) {
       const bool ok = n < nvalid;
@@ -575,9 +581,13 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 
     // role 0: S = Q K^T ; role 1: dP = dO V^T   (this lane's key column against the step's 32 rows)
     const uint16_t* As = role == 0 ? Qs : dOs;
-    const float s0 = role == 0 ? zq : 0.f;  // S starts at z / scale, so that scale * S is the biased score
+    if (role == 0) {  // S starts at z / scale, so that scale * S is the biased score
 #pragma unroll
-    for (int vv = 0; vv < 16; vv++) sacc[vv] = s0;
+      for (int vv = 0; vv < 16; vv++) sacc[vv] = zq;
+    } else {
+#pragma unroll
+      for (int vv = 0; vv < 16; vv++) sacc[vv] = 0.f;  // (a constant accumulator operand, no moves)
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       sacc = mfma32(fo.row_frag(As, 0, ks), breg[ks], sacc);
