@@ -274,14 +274,16 @@ def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
 
 
 def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=None,
-                 mask_method="sequential", row_chunk=1024, return_dz_abs=False):
+                 mask_method="sequential", row_chunk=1024, return_dz_abs=False, abs_out=None):
     """Eq. 7-10 / Alg. 2 result: dQ [T, H_q, d], dK, dV [T, H_kv, d], dz [H_q, T].
 
     dK and dV are summed over the q-heads listed in `heads` that share a
     kv-head (all heads by default).  dV is the attention-path gradient only
     (the path V -> z is not part of this function).  With return_dz_abs a fifth array
     sum_i |dS_ij| [H_q, T] is returned: the magnitude of the summands of dz, against which a
-    reduced-precision dz is judged.
+    reduced-precision dz is judged.  A dict passed as abs_out receives the same
+    magnitudes for dK and dV, "dK": scale * sum_i |dS_ij| |q_ic| and "dV": sum_i P_ij |do_ic|, both
+    [T, H_kv, d] (no part of the result: the yardstick for a reduced-precision sum of many terms).
     """
     Q, K, V, z, dO = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO)
     T, H_q, d = Q.shape
@@ -295,6 +297,8 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     dK = np.zeros((T, H_kv, d))
     dV = np.zeros((T, H_kv, d))
     cu = [int(c) for c in cu_seqlens]
+    dK_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
+    dV_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
     for h in heads:
         g = h // G
         for a, b in zip(cu[:-1], cu[1:]):
@@ -318,8 +322,14 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
                 dK[a:b, g] += scale * (dS.T @ q[r0:r1])             # Eq. 10
                 dzd += dS.sum(axis=0)                               # Eq. 9, summed over rows
                 dza += np.abs(dS).sum(axis=0)
+                if dK_abs is not None:
+                    dK_abs[a:b, g] += scale * (np.abs(dS).T @ np.abs(q[r0:r1]))
+                    dV_abs[a:b, g] += P.T @ np.abs(do[r0:r1])
             dz[h, a:b] = dzd
             dz_abs[h, a:b] = dza
+    if abs_out is not None:
+        abs_out["dK"] = dK_abs
+        abs_out["dV"] = dV_abs
     if return_dz_abs:
         return dQ, dK, dV, dz, dz_abs
     return dQ, dK, dV, dz

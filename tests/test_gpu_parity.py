@@ -13,7 +13,7 @@ import torch
 import oracle as orc
 from paper_2508_02124_amd import binding as B
 from paper_2508_02124_amd import workloads as wlmod
-from gpu_harness import BQ, DeviceCase, check_close, tol
+from gpu_harness import BQ, DZ_SREL, DeviceCase, check_close, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -24,6 +24,13 @@ SMALL = {
     "k_ge_len": lambda: wlmod.small_workload("k_ge_len", 13, 4, 4, 64, 512, (150, 150)),
     "empty_doc": lambda: wlmod.small_workload("empty_doc", 14, 2, 2, 64, 32, (100, 0, 60)),
     "multi_tile_d128": lambda: wlmod.small_workload("multi_tile_d128", 15, 4, 2, 128, 160, (700, 260)),
+    # degenerate shapes: one-token and few-token documents, k = 1, a single token in total, k = 2 across
+    # several blocks (almost every key is evicted at once), 8 q-heads per kv-head, 3 q-heads (not a multiple of 8)
+    "tiny_docs": lambda: wlmod.small_workload("tiny_docs", 16, 2, 2, 64, 2, (1, 2, 1, 3, 64, 65, 1)),
+    "k1_d128": lambda: wlmod.small_workload("k1_d128", 17, 2, 1, 128, 1, (300,)),
+    "single_token": lambda: wlmod.small_workload("single_token", 18, 2, 2, 64, 4, (1,)),
+    "k2_many_blocks": lambda: wlmod.small_workload("k2_many_blocks", 19, 3, 3, 64, 2, (900,)),
+    "gqa8_d64": lambda: wlmod.small_workload("gqa8_d64", 20, 8, 1, 64, 70, (520,)),
 }
 
 
@@ -149,10 +156,20 @@ def test_backward_small(gpu, name, dtype):
     case.fwd()
     case.bwd()
     zg = case.host("z").astype(np.float64)
-    dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, inp.wl.k)
+    mass = {}
+    dQ, dK, dV, dz, dza = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, inp.wl.k,
+                                           return_dz_abs=True, abs_out=mass)
     t = tol(dtype == "bf16")
-    for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
-        print(f"  {nm}", check_close(nm, case.host(nm), ref, **t), flush=True)
+    print("  dQ", check_close("dQ", case.host("dQ"), dQ, **t), flush=True)
+    # bf16: P and dS enter the dV, dK and dz products rounded to bf16, and dS also carries the rounding
+    # of the stored O (see DZ_SREL).  With a keep window of a few keys the kept probabilities are of
+    # order one and a resident key collects hundreds of such terms, so these sums over rows are also
+    # judged against the oracle's sum of |terms|; at the usual windows that allowance is below the
+    # plain tolerance.  fp32: plain tolerance.
+    srel = DZ_SREL if dtype == "bf16" else 0.0
+    for nm, ref in (("dK", dK), ("dV", dV)):
+        print(f"  {nm}", check_close(nm, case.host(nm), ref, summand_abs=mass[nm], srel=srel, **t), flush=True)
+    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dza, srel=srel, **t), flush=True)
     # keys that are never kept get exactly zero gradient into z
     eg = case.host("expiry")
     never = eg == np.arange(inp.T)[None, :]
