@@ -21,4 +21,6 @@ from .dma_oracle import (  # noqa: F401
     dma_keys,
     mask_backward,
     dma_decode,
+    z_scores_xhead,
+    xhead_backward,
 )

@@ -26,7 +26,10 @@ row's causal prefix (Listing 1); rows with fewer than k candidates keep all of
 them; Alg. 2's "rowsum(dS)" into dM is a sum over the query rows of a column
 (Eq. 9 summed over time steps); no gradient flows through the selection
 (Section 6, "Fully Differentiable Design").  Each q-head h uses its own vector
-w_h on the values of its kv-head g(h) = h // (H_q / H_kv).
+w_h on the values of its kv-head g(h) = h // (H_q / H_kv); z_scores_xhead is the
+paper's full form, in which the score of head h contracts the token's values of
+ALL heads (Delta in R^{n_h x d_h x n_h}, Eq. 3; Listing 1 flattens the heads'
+values before the projection).
 
 Layouts: Q, O, dO, dQ [T, H_q, d]; K, V, dK, dV [T, H_kv, d]; z, dz, LSE
 [H_q, T]; cu_seqlens [n_docs + 1] with cu[0] = 0, cu[-1] = T.
@@ -37,8 +40,10 @@ k = 1, all-equal z (tie rule), row sums, exact zeros, finite differences for
 all four gradients, algebraic identities, scalar triple-loop brute force, and
 the gather-loop formulation of Listing 1; mask_backward: central finite
 differences of Eq. 3 and torch autograd of the forward formula; dma_decode:
-the last rows of the dense forward oracle and of topk_indices.  No function
-here is unpinned.
+the last rows of the dense forward oracle and of topk_indices; z_scores_xhead /
+xhead_backward: a block-structured Delta reproduces the per-head functions,
+torch's linear + softplus + exp and its autograd, central finite differences.
+No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -52,6 +57,7 @@ __all__ = [
     "expiry_from_kept", "expiry_sequential", "topk_indices", "dma_forward",
     "dma_backward", "dma_forward_gather_loop", "dma_scalar_bruteforce",
     "n_active_pairs", "dma_rows", "dma_keys", "mask_backward", "dma_decode",
+    "z_scores_xhead", "xhead_backward",
 ]
 
 
@@ -112,6 +118,49 @@ def mask_backward(V, W, A, dz, H_q):
         dW[h] = dx @ V[:, g, :]
         dVz[:, g, :] += np.outer(dx, W[h])
     return dW, dA, dVz
+
+
+def z_scores_xhead(V, Delta, A):
+    """Eq. 3 with the full sampling tensor: the score of head h contracts the token's value
+    vectors of all kv-heads, z[h, j] = exp(A_h * softplus(sum_{g, c} v_{g, j, c} Delta[h, g, c])).
+
+    V [T, H_kv, d], Delta [H_q, H_kv * d] (row h = the flattened [H_kv, d] weights of head h, the
+    layout of a linear layer's weight), A [H_q]  ->  z [H_q, T] (float64).
+    """
+    V = np.asarray(V, dtype=np.float64)
+    Delta = np.asarray(Delta, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    T = V.shape[0]
+    x = V.reshape(T, -1) @ Delta.T                  # [T, H_q]
+    return np.exp(A[None, :] * softplus(x)).T
+
+
+def xhead_backward(V, Delta, A, dz):
+    """Chain rule of z_scores_xhead, given dz [H_q, T]:
+
+        dx[h, j]        = dz[h, j] z[h, j] A_h sigmoid(x[h, j])
+        dA[h]           = sum_j dz[h, j] z[h, j] softplus(x[h, j])
+        dDelta[h, g, c] = sum_j dx[h, j] v_{g, j, c}
+        dVz[j, g, c]    = sum_h dx[h, j] Delta[h, g, c]
+
+    Returns dDelta [H_q, H_kv * d], dA [H_q], dVz [T, H_kv, d] (float64).
+    """
+    V = np.asarray(V, dtype=np.float64)
+    Delta = np.asarray(Delta, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    dz = np.asarray(dz, dtype=np.float64)
+    T, H_kv, d = V.shape
+    Vf = V.reshape(T, -1)
+    x = Vf @ Delta.T                                # [T, H_q]
+    sp = softplus(x)
+    z = np.exp(A[None, :] * sp)
+    sig = 1.0 / (1.0 + np.exp(-x))
+    dzt = dz.T                                      # [T, H_q]
+    dx = dzt * z * A[None, :] * sig
+    dA = np.sum(dzt * z * sp, axis=0)
+    dDelta = dx.T @ Vf
+    dVz = (dx @ Delta).reshape(T, H_kv, d)
+    return dDelta, dA, dVz
 
 
 # --------------------------------------------------------------------------- kept sets

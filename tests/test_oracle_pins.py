@@ -388,6 +388,74 @@ def test_mask_backward_special_cases():
     assert np.allclose(dA, (dz * sp).sum(1))
 
 
+# ----------------------------------------------------------------------------- cross-head scores (Eq. 3 with the full Delta)
+def _xhead_case(seed=4, T=19, H_q=6, H_kv=3, d=5):
+    r = np.random.default_rng(seed)
+    V = r.standard_normal((T, H_kv, d))
+    Delta = r.standard_normal((H_q, H_kv * d)) / math.sqrt(H_kv * d)
+    A = -r.uniform(0.5, 2.0, H_q)
+    dz = r.standard_normal((H_q, T))
+    return V, Delta, A, dz
+
+
+def test_xhead_scores_match_torch_linear():
+    """Listing 1's form, with library routines: a linear layer on the token's flattened values, then
+    softplus, gate and exp.  Catches a transposed Delta and a wrong flattening order of (head, channel)."""
+    V, Delta, A, _ = _xhead_case()
+    z = orc.z_scores_xhead(V, Delta, A)
+    x = torch.nn.functional.linear(torch.tensor(V).reshape(V.shape[0], -1), torch.tensor(Delta))
+    zt = torch.exp(torch.tensor(A) * torch.nn.functional.softplus(x)).T
+    assert z.shape == (Delta.shape[0], V.shape[0])
+    assert np.allclose(z, zt.numpy(), rtol=1e-12, atol=0)
+
+
+def test_xhead_with_block_structure_is_the_per_head_form():
+    """Delta[h] zero outside the block of kv-head g(h) reduces both functions to z_scores /
+    mask_backward with w_h = that block."""
+    V, W, A, dz, H_q = _mask_case(seed=9, T=31, H_q=6, H_kv=3, d=4)
+    H_kv, d = V.shape[1], V.shape[2]
+    G = H_q // H_kv
+    Delta = np.zeros((H_q, H_kv * d))
+    for h in range(H_q):
+        Delta[h, (h // G) * d:(h // G + 1) * d] = W[h]
+    assert np.allclose(orc.z_scores_xhead(V, Delta, A), orc.z_scores(V, W, A, H_q), rtol=1e-13, atol=0)
+    dD, dA, dVz = orc.xhead_backward(V, Delta, A, dz)
+    dW, dA2, dVz2 = orc.mask_backward(V, W, A, dz, H_q)
+    for h in range(H_q):
+        assert np.allclose(dD[h, (h // G) * d:(h // G + 1) * d], dW[h], rtol=1e-12, atol=1e-14)
+    assert np.allclose(dA, dA2, rtol=1e-12, atol=1e-14)
+    assert np.allclose(dVz, dVz2, rtol=1e-12, atol=1e-14)
+
+
+def test_xhead_backward_matches_finite_differences_and_autograd():
+    """Catches: dDelta missing the off-group blocks, dVz summed over one group only, a dropped
+    factor, dA using x instead of softplus(x)."""
+    V, Delta, A, dz = _xhead_case(seed=6)
+    dD, dA, dVz = orc.xhead_backward(V, Delta, A, dz)
+
+    def loss(V_, D_, A_):
+        return float(np.sum(dz * orc.z_scores_xhead(V_, D_, A_)))
+
+    eps = 1e-6
+    r = np.random.default_rng(12)
+    for _ in range(12):
+        h, c = int(r.integers(Delta.shape[0])), int(r.integers(Delta.shape[1]))
+        Dp, Dm = Delta.copy(), Delta.copy(); Dp[h, c] += eps; Dm[h, c] -= eps
+        assert abs((loss(V, Dp, A) - loss(V, Dm, A)) / (2 * eps) - dD[h, c]) <= 1e-6 * (1 + abs(dD[h, c]))
+        t, g, cc = int(r.integers(V.shape[0])), int(r.integers(V.shape[1])), int(r.integers(V.shape[2]))
+        Vp, Vm = V.copy(), V.copy(); Vp[t, g, cc] += eps; Vm[t, g, cc] -= eps
+        assert abs((loss(Vp, Delta, A) - loss(Vm, Delta, A)) / (2 * eps) - dVz[t, g, cc]) <= 1e-6 * (1 + abs(dVz[t, g, cc]))
+    for h in range(len(A)):
+        Ap, Am = A.copy(), A.copy(); Ap[h] += eps; Am[h] -= eps
+        assert abs((loss(V, Delta, Ap) - loss(V, Delta, Am)) / (2 * eps) - dA[h]) <= 1e-6 * (1 + abs(dA[h]))
+    Vt, Dt, At = (torch.tensor(a, requires_grad=True) for a in (V, Delta, A))
+    z = torch.exp(At * torch.nn.functional.softplus(torch.nn.functional.linear(Vt.reshape(V.shape[0], -1), Dt))).T
+    (z * torch.tensor(dz)).sum().backward()
+    assert np.allclose(Dt.grad.numpy(), dD, rtol=1e-10, atol=1e-12)
+    assert np.allclose(At.grad.numpy(), dA, rtol=1e-10, atol=1e-12)
+    assert np.allclose(Vt.grad.numpy(), dVz, rtol=1e-10, atol=1e-12)
+
+
 # ----------------------------------------------------------------------------- decode (last row of every document)
 @pytest.mark.parametrize("ties", [False, True])
 def test_decode_equals_last_rows_of_the_dense_forward(ties):
