@@ -230,6 +230,26 @@ def main():
         mb_bytes = 3 * inp.T * wl.H_kv * wl.d * 2 + 4 * wl.H_q * inp.T   # V read, dV read + write, dz read
         out["mask_bwd"] = {"ms": mb_ms, "algorithmic_bytes": mb_bytes, "GB/s": mb_bytes / (mb_ms * 1e-3) / 1e9,
                            "hbm_peak_GB/s": 8000.0}
+        # not part of the step: the scores from the full cross-head Delta (Eq. 3) and their chain rule
+        if wl.H_q <= 32:
+            Dl = torch.randn((wl.H_q, wl.H_kv * wl.d), device=dev) / float(np.sqrt(wl.H_kv * wl.d))
+            dDl = torch.empty_like(Dl)
+            zx = torch.empty_like(case.z)
+            times = {}
+            for nm, fn in (("fwd", lambda: B.dma_scores_xhead(case.shape, case.V, Dl, case.A, zx)),
+                           ("bwd", lambda: B.dma_scores_xhead_bwd(case.shape, case.V, Dl, case.A, case.dz, dDl, dA,
+                                                                  case.dV, True))):
+                fn()
+                for i in range(5):
+                    ev[i].record()
+                    fn()
+                ev[5].record()
+                torch.cuda.synchronize()
+                times[nm] = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
+            vb = inp.T * wl.H_kv * wl.d * 2
+            out["scores_xhead"] = {"fwd_ms": times["fwd"], "fwd_algorithmic_bytes": vb + 4 * wl.H_q * inp.T,
+                                   "bwd_ms": times["bwd"], "bwd_algorithmic_bytes": 3 * vb + 4 * wl.H_q * inp.T,
+                                   "gflop_fwd": 2.0 * inp.T * wl.H_kv * wl.d * wl.H_q / 1e9}
     if wl.name == HEADLINE and not args.k:
         # not part of the step: decode of one new row against a 65536-token cache (HBM-bound)
         Ld, kd = 65536, 2048

@@ -127,6 +127,25 @@ int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const fl
                  float* dW, float* dA, void* dV, int accumulate, void* stream);
 
 /*
+ * Content scores with the paper's full sampling tensor (Eq. 3 states Delta in R^{n_h x d_h x n_h};
+ * Listing 1 flattens the values of all heads of a token before the projection): the score of q-head
+ * h contracts the token's value vectors of ALL kv-heads,
+ *     z[h, j] = exp(A_h * softplus(sum_{g, c} V[j, g, c] * Delta[h, g, c])).
+ *   Delta in  [H_q, H_kv * d] float, row h = the [H_kv, d] weights of head h (the layout of a linear
+ *             layer's weight from the flattened values to the heads)
+ *   z     out [H_q, T]; pass it to dma_mask_gen with W == NULL (caller-supplied scores).
+ * dma_scores_xhead_bwd is its chain rule, the counterpart of dma_mask_bwd:
+ *   dz in [H_q, T];  dDelta out [H_q, H_kv * d] f32 = sum_j dx[h, j] V[j, g, c];  dA out [H_q] f32;
+ *   dV [T, H_kv, d], dtype of V: sum_h dx[h, j] Delta[h, g, c], written (accumulate == 0) or added.
+ * dDelta and dA are accumulated with floating-point atomics.  H_q <= 32 (DMA_EUNSUPPORTED beyond);
+ * shape->k, n_docs and softmax_scale are not used.  No workspace.
+ */
+int dma_scores_xhead(const dma_shape* shape, const void* V, const float* Delta, const float* A, float* z,
+                     void* stream);
+int dma_scores_xhead_bwd(const dma_shape* shape, const void* V, const float* Delta, const float* A, const float* dz,
+                         float* dDelta, float* dA, void* dV, int accumulate, void* stream);
+
+/*
  * Decode: the newest row of every sequence against its KV cache (Eq. 4-6 for one query row; the
  * regime of the paper's largest speed-ups, Section 5).  Sequence b occupies rows
  * [cu_seqlens[b], cu_seqlens[b+1]) of K, V and z, its last row being the new token; that row's

@@ -57,6 +57,10 @@ def lib():
         L.dma_bwd.restype = i32
         L.dma_mask_bwd.argtypes = [shp] + [vp] * 7 + [i32, vp]
         L.dma_mask_bwd.restype = i32
+        L.dma_scores_xhead.argtypes = [shp] + [vp] * 5
+        L.dma_scores_xhead.restype = i32
+        L.dma_scores_xhead_bwd.argtypes = [shp] + [vp] * 7 + [i32, vp]
+        L.dma_scores_xhead_bwd.restype = i32
         L.dma_decode_kept_bytes.argtypes = [shp]
         L.dma_decode_kept_bytes.restype = sz
         L.dma_decode.argtypes = [shp] + [vp] * 8 + [sz, vp]
@@ -144,6 +148,17 @@ def dma_decode(shape, q, K, V, z, cu_seqlens, o, lse, kept, kept_bytes, stream=N
 def dma_mask_bwd(shape, V, W, A, dz, dW, dA, dV, accumulate, stream=None):
     _check(lib().dma_mask_bwd(ctypes.byref(shape), _ptr(V), _ptr(W), _ptr(A), _ptr(dz), _ptr(dW), _ptr(dA), _ptr(dV),
                               int(bool(accumulate)), _stream(stream)), "dma_mask_bwd")
+
+
+def dma_scores_xhead(shape, V, Delta, A, z, stream=None):
+    _check(lib().dma_scores_xhead(ctypes.byref(shape), _ptr(V), _ptr(Delta), _ptr(A), _ptr(z), _stream(stream)),
+           "dma_scores_xhead")
+
+
+def dma_scores_xhead_bwd(shape, V, Delta, A, dz, dDelta, dA, dV, accumulate, stream=None):
+    _check(lib().dma_scores_xhead_bwd(ctypes.byref(shape), _ptr(V), _ptr(Delta), _ptr(A), _ptr(dz), _ptr(dDelta),
+                                      _ptr(dA), _ptr(dV), int(bool(accumulate)), _stream(stream)),
+           "dma_scores_xhead_bwd")
 
 
 def dma_bwd(shape, Q, K, V, O, dO, LSE, z, expiry, mask, cu_seqlens, dQ, dK, dV, dz, ws, ws_bytes, stream=None):

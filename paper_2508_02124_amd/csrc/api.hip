@@ -119,6 +119,24 @@ int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const fl
   return launch_mask_bwd(*shape, V, W, A, dz, dW, dA, dV, accumulate != 0, (hipStream_t)stream);
 }
 
+int dma_scores_xhead(const dma_shape* shape, const void* V, const float* Delta, const float* A, float* z,
+                     void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!V || !Delta || !A || !z) return DMA_EINVAL;
+  if (!aligned16(V) || !aligned16(Delta) || !aligned16(z)) return DMA_EINVAL;
+  return launch_xhead_scores(*shape, V, Delta, A, z, (hipStream_t)stream);
+}
+
+int dma_scores_xhead_bwd(const dma_shape* shape, const void* V, const float* Delta, const float* A, const float* dz,
+                         float* dDelta, float* dA, void* dV, int accumulate, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!V || !Delta || !A || !dz || !dDelta || !dA || !dV) return DMA_EINVAL;
+  if (!aligned16(V) || !aligned16(Delta) || !aligned16(dz) || !aligned16(dDelta) || !aligned16(dV)) return DMA_EINVAL;
+  return launch_xhead_bwd(*shape, V, Delta, A, dz, dDelta, dA, dV, accumulate != 0, (hipStream_t)stream);
+}
+
 size_t dma_decode_kept_bytes(const dma_shape* shape) {
   if (check_shape(shape) != DMA_OK) return 0;
   const size_t kcap = (size_t)(shape->k < shape->T ? shape->k : shape->T);

@@ -126,6 +126,10 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
 int launch_mask_bwd(const dma_shape& s, const void* V, const float* W, const float* A, const float* dz,
                     float* dW, float* dA, void* dV, int accumulate, hipStream_t st);
 
+int launch_xhead_scores(const dma_shape& s, const void* V, const float* Delta, const float* A, float* z, hipStream_t st);
+int launch_xhead_bwd(const dma_shape& s, const void* V, const float* Delta, const float* A, const float* dz,
+                     float* dDelta, float* dA, void* dV, int accumulate, hipStream_t st);
+
 size_t decode_part_floats(const dma_shape& s);
 size_t decode_sel_words(const dma_shape& s);
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,

@@ -28,6 +28,7 @@ def declared_symbols():
 def test_header_symbols_exported(lib):
     names = declared_symbols()
     assert {"dma_mask_gen", "dma_fwd", "dma_bwd", "dma_mask_bwd", "dma_decode", "dma_decode_kept_bytes",
+            "dma_scores_xhead", "dma_scores_xhead_bwd",
             "dma_mask_bytes", "dma_workspace_bytes",
             "dma_strerror", "dma_version"} <= set(names)
     for n in names:
@@ -76,6 +77,19 @@ def test_error_codes_before_any_launch(lib):
     assert e.value.status == B.DMA_EINVAL
     with pytest.raises(B.DmaError) as e:
         B.dma_mask_bwd(ok, p, p, p, p + 8, p, p, p, 1, stream=0)         # dz misaligned
+    assert e.value.status == B.DMA_EINVAL
+    with pytest.raises(B.DmaError) as e:
+        B.dma_scores_xhead(ok, p, None, p, p, stream=0)                  # Delta missing
+    assert e.value.status == B.DMA_EINVAL
+    many = B.make_shape(T=256, n_docs=1, H_q=64, H_kv=2, d=64, k=64)
+    with pytest.raises(B.DmaError) as e:
+        B.dma_scores_xhead(many, p, p, p, p, stream=0)                   # more than 32 heads
+    assert e.value.status == B.DMA_EUNSUPPORTED
+    with pytest.raises(B.DmaError) as e:
+        B.dma_scores_xhead_bwd(many, p, p, p, p, p, p, p, 0, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
+    with pytest.raises(B.DmaError) as e:
+        B.dma_scores_xhead_bwd(ok, p, p, p, p, p + 4, p, p, 0, stream=0)  # dDelta misaligned
     assert e.value.status == B.DMA_EINVAL
     with pytest.raises(B.DmaError) as e:
         B.dma_decode(ok, p, p, p, p, p, p, p, p, 0, stream=0)            # kept buffer too small

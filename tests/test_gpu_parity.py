@@ -238,6 +238,85 @@ def test_mask_backward(gpu, name, dtype):
     print("  dW again", check_close("dW", dWd.cpu().numpy(), dW, **t32), flush=True)
 
 
+# ----------------------------------------------------------------------------- cross-head scores (Eq. 3, full Delta)
+XHEAD_CASES = {
+    # name: (T, H_q, H_kv, d)
+    "ragged_d64": (517, 6, 3, 64),
+    "bench_heads_d128": (300, 32, 8, 128),
+    "one_tile_d128": (64, 2, 1, 128),
+    "odd_heads_d64": (1000, 5, 1, 64),
+    "many_tiles_d128": (40000, 12, 4, 128),      # several tiles per workgroup in the backward
+}
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("name", list(XHEAD_CASES))
+def test_xhead_scores_and_backward(gpu, name, dtype):
+    print(f"[case] xhead {name} {dtype}", flush=True)
+    import torch
+    T, H_q, H_kv, d = XHEAD_CASES[name]
+    r = np.random.default_rng(200 + list(XHEAD_CASES).index(name))
+    V = r.standard_normal((T, H_kv, d)).astype(np.float32)
+    dV0 = r.standard_normal((T, H_kv, d)).astype(np.float32)
+    if dtype == "bf16":
+        V = wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(V))
+        dV0 = wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(dV0))
+    Delta = (r.standard_normal((H_q, H_kv * d)) / np.sqrt(H_kv * d)).astype(np.float32)
+    A = (-r.uniform(0.5, 2.0, H_q)).astype(np.float32)
+    dz = r.standard_normal((H_q, T)).astype(np.float32)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    shape = B.make_shape(T=T, n_docs=1, H_q=H_q, H_kv=H_kv, d=d, k=1,
+                         dtype=B.DMA_BF16 if dtype == "bf16" else B.DMA_F32)
+    dev = lambda x, dt=None: torch.from_numpy(np.ascontiguousarray(x)).to(gpu).to(dt or torch.float32)
+    Vd, Dd, Ad, dzd = dev(V, tdt), dev(Delta), dev(A), dev(dz)
+    zd = torch.full((H_q, T), float("nan"), device=gpu)
+    B.dma_scores_xhead(shape, Vd, Dd, Ad, zd)
+    zr = orc.z_scores_xhead(V, Delta, A)
+    zg = zd.cpu().numpy().astype(np.float64)
+    assert np.isfinite(zg).all()
+    rel = np.abs(zg - zr) / zr
+    print("  z max rel", rel.max(), flush=True)
+    assert rel.max() <= 1e-5
+    dDd = torch.full((H_q, H_kv * d), 7.0, device=gpu)       # outputs are overwritten, whatever they held
+    dAd = torch.full((H_q,), -3.0, device=gpu)
+    dVd = torch.full((T, H_kv, d), 5.0, device=gpu, dtype=tdt)
+    B.dma_scores_xhead_bwd(shape, Vd, Dd, Ad, dzd, dDd, dAd, dVd, False)
+    dD, dA, dVz = orc.xhead_backward(V, Delta, A, dz)
+    t = tol(dtype == "bf16")
+    t32 = dict(atol=1e-4, rtol=1e-4, frob=1e-5)               # fp32 sums over T rows, fp32 exp / log
+    if T > 10000:
+        t32 = dict(atol=1e-3, rtol=1e-4, frob=1e-5)           # sums of 40000 terms of order one
+    print("  dDelta", check_close("dDelta", dDd.cpu().numpy(), dD, **t32), flush=True)
+    print("  dA", check_close("dA", dAd.cpu().numpy(), dA, **t32), flush=True)
+    tv = t if dtype == "bf16" else dict(atol=1e-4, rtol=1e-4, frob=1e-5)
+    print("  dVz", check_close("dVz", dVd.float().cpu().numpy(), dVz, **tv), flush=True)
+    dVd2 = dev(dV0, tdt)
+    B.dma_scores_xhead_bwd(shape, Vd, Dd, Ad, dzd, dDd, dAd, dVd2, True)
+    print("  dV+=", check_close("dV+dVz", dVd2.float().cpu().numpy(), dV0 + dVz, **tv), flush=True)
+    print("  dDelta again", check_close("dDelta", dDd.cpu().numpy(), dD, **t32), flush=True)
+
+
+@pytest.mark.gpu
+def test_xhead_block_structure_equals_per_head_path(gpu):
+    """A Delta that is zero outside the block of each head's own kv-head gives the scores of the
+    per-head entry point (dma_mask_gen with W), to fp32 rounding."""
+    print("[case] xhead vs per-head", flush=True)
+    import torch
+    wl = wlmod.small_workload("xh", 23, 8, 2, 128, 50, (700,))
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen()
+    G = wl.H_q // wl.H_kv
+    Delta = np.zeros((wl.H_q, wl.H_kv * wl.d), dtype=np.float32)
+    for h in range(wl.H_q):
+        Delta[h, (h // G) * wl.d:(h // G + 1) * wl.d] = inp.W[h]
+    z2 = torch.empty_like(case.z)
+    B.dma_scores_xhead(case.shape, case.V, torch.from_numpy(Delta).to(gpu), case.A, z2)
+    a, b = case.host("z").astype(np.float64), z2.cpu().numpy().astype(np.float64)
+    assert (np.abs(a - b) / a).max() <= 2e-6
+
+
 # ----------------------------------------------------------------------------- decode (newest row of every sequence)
 DECODE_CASES = {
     # name: (doc lengths, H_q, H_kv, d, k, tie levels or 0)
