@@ -40,7 +40,7 @@ extern "C" {
 typedef enum {
   DMA_OK = 0,
   DMA_EINVAL = -1,       /* null pointer, misaligned pointer, T<=0, k<=0, n_docs<=0, H_q % H_kv != 0 */
-  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, causal == 0 */
+  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, more than 32 heads for the cross-head scores */
   DMA_EWORKSPACE = -3,   /* ws_bytes smaller than dma_workspace_bytes() */
   DMA_EHIP = -4          /* a launch failed (hipGetLastError) */
 } dma_status;
@@ -56,7 +56,8 @@ typedef struct {
   int32_t d;            /* head dimension: 64 or 128                                  */
   int32_t k;            /* keep-window (the paper's w): kept keys per query row;
                            k larger than a document keeps all of its causal keys      */
-  int32_t causal;       /* 1: candidates of row i are the keys j <= i of its document */
+  int32_t causal;       /* 1: candidates of row i are the keys j <= i of its document;
+                           0: all keys of its document (every row keeps the same keys)  */
   int32_t dtype;        /* dma_dtype of Q/K/V/O and their gradients                   */
   float softmax_scale;  /* 0 => d^-1/2                                                */
 } dma_shape;
@@ -77,7 +78,9 @@ size_t dma_workspace_bytes(const dma_shape* shape);
  *                   that does NOT keep key j; e == j: never kept; e == end of the
  *                   document: kept to the end.  Row i keeps key j  <=>  j <= i < e[h, j].
  *                   The kept set of a row is its min(k, i - doc_start + 1) best causal
- *                   keys by (z descending, index ascending).
+ *                   keys by (z descending, index ascending).  With causal == 0 every row of a
+ *                   document keeps the document's min(k, n) best keys: e[h, j] = end of the
+ *                   document for those keys (kept by all rows) and e[h, j] = j for the others.
  *   topk_idx   out, nullable: [H_q, T, k] int32, the kept keys of each row as global
  *                   indices in ascending order, padded with -1 (debug; O(T k) memory).
  *   mask       out  dma_mask_bytes(shape) bytes; consumed by dma_fwd / dma_bwd.  It also holds

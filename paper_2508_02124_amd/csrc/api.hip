@@ -26,7 +26,6 @@ int check_shape(const dma_shape* s) {
   if (s->softmax_scale < 0.f || s->softmax_scale != s->softmax_scale) return DMA_EINVAL;
   if (s->d != 64 && s->d != 128) return DMA_EUNSUPPORTED;
   if (s->dtype != DMA_BF16 && s->dtype != DMA_F32) return DMA_EUNSUPPORTED;
-  if (!s->causal) return DMA_EUNSUPPORTED;
   if (s->H_q > 65535 || s->H_kv > 65535) return DMA_EUNSUPPORTED;
   return DMA_OK;
 }
@@ -162,7 +161,7 @@ const char* dma_strerror(int status) {
   switch (status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
-    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32, causal = 1)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32)";
     case DMA_EWORKSPACE: return "workspace missing or smaller than dma_workspace_bytes()";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";

@@ -22,13 +22,17 @@ template <int D, int MODE>
 __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                      const float* __restrict__ V, const float* __restrict__ z,
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
-                                                     int n_docs, int T, int H_q, int H_kv, float scale,
+                                                     int n_docs, int causal, int T, int H_q, int H_kv, float scale,
                                                      float* __restrict__ O, float* __restrict__ LSE,
                                                      const float* __restrict__ dO, float* __restrict__ Dout,
                                                      float* __restrict__ dQ) {
   const int t = blockIdx.x, h = blockIdx.y, l = threadIdx.x;
   const int g = h / (H_q / H_kv);
-  const int a = cu[find_doc(cu, n_docs, t)];
+  const int doc = find_doc(cu, n_docs, t);
+  const int a = cu[doc];
+  // candidates: keys a .. jl; key j is kept by this row if its expiry lies beyond `thr`.  Causal:
+  // jl = t and thr = t; otherwise every row of the document keeps the same keys (expiry > own index).
+  const int jl = causal ? t : cu[doc + 1] - 1;
   __shared__ float qs[D], dos[D];
   const float* qrow = Q + ((size_t)t * H_q + h) * D;
   for (int c = l; c < D; c += 64) qs[c] = qrow[c];
@@ -48,9 +52,9 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
   __syncthreads();
   float m = -INFINITY;
   if (MODE == 0) {
-    for (int j0 = a; j0 <= t; j0 += 64) {
+    for (int j0 = a; j0 <= jl; j0 += 64) {
       const int j = j0 + l;
-      if (j <= t && expiry[(size_t)h * T + j] > t) {
+      if (j <= jl && expiry[(size_t)h * T + j] > (causal ? t : j)) {
         const float* kr = K + ((size_t)j * H_kv + g) * D;
         float s = 0.f;
         for (int c = 0; c < D; c++) s = fmaf(qs[c], kr[c], s);
@@ -63,9 +67,9 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
 #pragma unroll
   for (int c = 0; c < D; c++) acc[c] = 0.f;
   float lsum = 0.f;
-  for (int j0 = a; j0 <= t; j0 += 64) {
+  for (int j0 = a; j0 <= jl; j0 += 64) {
     const int j = j0 + l;
-    if (j <= t && expiry[(size_t)h * T + j] > t) {
+    if (j <= jl && expiry[(size_t)h * T + j] > (causal ? t : j)) {
       const float* kr = K + ((size_t)j * H_kv + g) * D;
       const float* vr = V + ((size_t)j * H_kv + g) * D;
       float s = 0.f;
@@ -104,7 +108,8 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
 template <int D>
 __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                      const float* __restrict__ V, const float* __restrict__ z,
-                                                     const int32_t* __restrict__ expiry, int T, int H_q, int H_kv,
+                                                     const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
+                                                     int n_docs, int causal, int T, int H_q, int H_kv,
                                                      float scale, const float* __restrict__ LSE,
                                                      const float* __restrict__ dO, const float* __restrict__ Dws,
                                                      float* __restrict__ dK, float* __restrict__ dV,
@@ -125,7 +130,13 @@ __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q
     const int e = expiry[(size_t)h * T + t];
     const float zt = z[(size_t)h * T + t];
     float dzacc = 0.f;
-    for (int i = t; i < e; i++) {
+    int i0 = t, i1 = e;  // rows that keep this key: causal t .. e - 1; otherwise the whole document or none
+    if (!causal) {
+      const int doc = find_doc(cu, n_docs, t);
+      i0 = e > t ? cu[doc] : t;
+      i1 = e > t ? cu[doc + 1] : t;
+    }
+    for (int i = i0; i < i1; i++) {
       const float* qr = Q + ((size_t)i * H_q + h) * D;
       const float* dor = dO + ((size_t)i * H_q + h) * D;
       float qv[CPL], dov[CPL], s = 0.f, dp = 0.f;
@@ -161,10 +172,10 @@ int launch_fwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   const dma_shape& s = p.s;
   dim3 grid(s.T, s.H_q);
   if (s.d == 128)
-    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
                                                 nullptr, nullptr, nullptr);
   else
-    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
                                                nullptr, nullptr, nullptr);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
@@ -176,13 +187,13 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   float* Dws = (float*)ws;
   dim3 grid(s.T, s.H_q), gridk(s.T, s.H_kv);
   if (s.d == 128) {
-    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale,
+    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
                                                 const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
   } else {
-    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.T, s.H_q, s.H_kv, p.scale,
+    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
                                                const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
   }
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }

@@ -21,7 +21,10 @@
 namespace dma {
 
 // ------------------------------------------------------------------ block table
-__global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int nblk_cap, int4* blk,
+// blk[i] = {document, first row, end row, w}: the attention kernels take min(k, first row - w) as the
+// number of resident slot columns of the block.  Causal: w = first row of the document (the keys
+// before the block); otherwise every block of a document has min(k, n) columns.
+__global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int nblk_cap, int k, int causal, int4* blk,
                                int32_t* docblk, int32_t* hdr) {
   __shared__ int s_total;
   if (threadIdx.x == 0) {
@@ -39,7 +42,8 @@ __global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int n
   for (int d = threadIdx.x; d < n_docs; d += blockDim.x) {
     int a = cu[d], b = cu[d + 1];
     int b0 = docblk[d];
-    for (int r = a, i = 0; r < b; r += BQ, i++) blk[b0 + i] = make_int4(d, r, min(r + BQ, b), a);
+    for (int r = a, i = 0; r < b; r += BQ, i++)
+      blk[b0 + i] = make_int4(d, r, min(r + BQ, b), causal ? a : r - min(k, b - a));
   }
   for (int i = s_total + threadIdx.x; i < nblk_cap; i += blockDim.x) blk[i] = make_int4(-1, 0, 0, 0);
 }
@@ -609,8 +613,28 @@ __global__ __launch_bounds__(BQ) void partial_list_kernel(const int4* __restrict
   if (tid == 0) pcnt[(size_t)h * nblk_cap + bi] = etot + xtot;
 }
 
+// Without the causal restriction every row of a document keeps the same min(k, n) best keys.  One
+// thread per (head, rank position r of the sorted order): the key at rank r < k is kept (expiry =
+// end of the document) and fills slot column r of every block of the document; the others are
+// never kept (expiry = own index).  Documents of at most k keys were not sorted: key j is rank j.
+__global__ __launch_bounds__(256) void noncausal_plan_kernel(const int32_t* __restrict__ cu, int n_docs,
+                                                             const uint32_t* __restrict__ si0,
+                                                             const int32_t* __restrict__ docblk, int32_t* expiry,
+                                                             int32_t* slot_tab, int T, int k, int nblk_cap, int kpad) {
+  const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+  if (t >= T) return;
+  const int d = find_doc(cu, n_docs, t);
+  const int a = cu[d], b = cu[d + 1], n = b - a;
+  const int r = t - a;
+  const int j = n <= k ? r : (int)si0[(size_t)h * T + t];
+  const bool kept = r < k;
+  expiry[(size_t)h * T + a + j] = kept ? b : a + j;
+  if (!kept) return;
+  for (int bl = docblk[d]; bl < docblk[d + 1]; bl++) slot_tab[((size_t)h * nblk_cap + bl) * kpad + r] = a + j;
+}
+
 // Debug output: kept keys of every row, ascending, -1 padded.  One wave per (row, head).
-__global__ __launch_bounds__(64) void topk_idx_kernel(const int32_t* __restrict__ cu, int n_docs,
+__global__ __launch_bounds__(64) void topk_idx_kernel(const int32_t* __restrict__ cu, int n_docs, int causal,
                                                       const int32_t* __restrict__ expiry, int32_t* out, int T, int k) {
   const int t = blockIdx.x, h = blockIdx.y, l = threadIdx.x;
   const int d = find_doc(cu, n_docs, t);
@@ -618,9 +642,10 @@ __global__ __launch_bounds__(64) void topk_idx_kernel(const int32_t* __restrict_
   int32_t* o = out + ((size_t)h * T + t) * k;
   const unsigned long long lt = (1ull << l) - 1ull;
   int count = 0;
-  for (int j0 = a; j0 <= t; j0 += 64) {
+  const int jl = causal ? t : cu[d + 1] - 1;
+  for (int j0 = a; j0 <= jl; j0 += 64) {
     const int j = j0 + l;
-    const bool keep = (j <= t) && expiry[(size_t)h * T + j] > t;
+    const bool keep = (j <= jl) && expiry[(size_t)h * T + j] > (causal ? t : j);
     const unsigned long long m = __ballot(keep);
     const int pos = count + __popcll(m & lt);
     if (keep && pos < k) o[pos] = j;
@@ -645,7 +670,7 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   int32_t* slotid = (int32_t*)(base + L.off_slotid);
 
   prof_begin(DMA_STAGE_Z, st);
-  blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, blk, docblk, hdr);
+  blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, s.k, s.causal, blk, docblk, hdr);
   if (W) {
     const int G = s.H_q / s.H_kv;
     dim3 grid((s.T + 63) / 64, s.H_kv);
@@ -677,22 +702,32 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   prof_begin(DMA_STAGE_SORT, st);
   sort_wavelet_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(sa);
   prof_end(DMA_STAGE_SORT, st);
-  prof_begin(DMA_STAGE_EXPIRY, st);
-  expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
-  prof_end(DMA_STAGE_EXPIRY, st);
-  prof_begin(DMA_STAGE_PLAN, st);
-  slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
-  {
-    const size_t n = (size_t)s.H_q * L.nblk_cap * L.kpad;
+  const auto fill = [&](int32_t* dst, size_t n, int32_t v) {
     size_t grid = (n + 2047) / 2048;
     if (grid > (1u << 20)) grid = 1u << 20;
     if (grid < 1) grid = 1;
-    fill_i32_kernel<<<(unsigned)grid, 256, 0, st>>>(slot_tab, n, -1);
+    fill_i32_kernel<<<(unsigned)grid, 256, 0, st>>>(dst, n, v);
+  };
+  if (!s.causal) {
+    prof_begin(DMA_STAGE_EXPIRY, st);
+    prof_end(DMA_STAGE_EXPIRY, st);
+    prof_begin(DMA_STAGE_PLAN, st);
+    fill(slot_tab, (size_t)s.H_q * L.nblk_cap * L.kpad, -1);
+    fill(pcnt, (size_t)s.H_q * L.nblk_cap, 0);
+    noncausal_plan_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, sa.si0, docblk, expiry, slot_tab,
+                                                                        s.T, s.k, L.nblk_cap, L.kpad);
+  } else {
+    prof_begin(DMA_STAGE_EXPIRY, st);
+    expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    prof_end(DMA_STAGE_EXPIRY, st);
+    prof_begin(DMA_STAGE_PLAN, st);
+    slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
+    fill(slot_tab, (size_t)s.H_q * L.nblk_cap * L.kpad, -1);
+    slot_table_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, expiry, slotid, docblk, slot_tab,
+                                                                    s.T, L.nblk_cap, L.kpad);
+    partial_list_kernel<<<dim3(L.nblk_cap, s.H_q), BQ, 0, st>>>(blk, expiry, parent, pcnt, plist, s.T, L.nblk_cap);
   }
-  slot_table_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, expiry, slotid, docblk, slot_tab,
-                                                                  s.T, L.nblk_cap, L.kpad);
-  partial_list_kernel<<<dim3(L.nblk_cap, s.H_q), BQ, 0, st>>>(blk, expiry, parent, pcnt, plist, s.T, L.nblk_cap);
-  if (topk_idx) topk_idx_kernel<<<dim3(s.T, s.H_q), 64, 0, st>>>(cu, s.n_docs, expiry, topk_idx, s.T, s.k);
+  if (topk_idx) topk_idx_kernel<<<dim3(s.T, s.H_q), 64, 0, st>>>(cu, s.n_docs, s.causal, expiry, topk_idx, s.T, s.k);
   prof_end(DMA_STAGE_PLAN, st);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }

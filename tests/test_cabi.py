@@ -62,10 +62,7 @@ def test_error_codes_before_any_launch(lib):
     with pytest.raises(B.DmaError) as e:
         B.dma_fwd(B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=80, k=64), p, p, p, p, p, p, p, p, p, None, 0, stream=0)
     assert e.value.status == B.DMA_EUNSUPPORTED
-    with pytest.raises(B.DmaError) as e:
-        B.dma_fwd(B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=64, k=64, causal=False),
-                  p, p, p, p, p, p, p, p, p, None, 0, stream=0)
-    assert e.value.status == B.DMA_EUNSUPPORTED
+    assert B.dma_mask_bytes(B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=64, k=64, causal=False)) > 0
     with pytest.raises(B.DmaError) as e:
         B.dma_bwd(ok, p, p, p, p, p, p, p, p, p, p, p, p, p, p, p, 16, stream=0)   # workspace too small
     assert e.value.status == B.DMA_EWORKSPACE

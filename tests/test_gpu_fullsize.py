@@ -193,3 +193,31 @@ def test_decode_long_cache(gpu):
     # the same row through the prefill path
     case.fwd()
     print("  o vs dma_fwd last row", check_close("o", o.float().cpu().numpy()[0], case.host("O")[-1], **T_BF16), flush=True)
+
+
+def test_noncausal_cfg2_shape_dense(gpu):
+    """The GQA training shape without the causal restriction (every row of a document keeps the
+    document's k best keys): dense oracle on all heads."""
+    print("[case] cfg2 shape, causal = 0", flush=True)
+    from dataclasses import replace
+    wl = replace(wlmod.CONFIGS["cfg2"], name="cfg2_noncausal", seed=2002, causal=False)
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen(); case.fwd(); case.bwd()
+    zg, eg = case.host("z").astype(np.float64), case.host("expiry")
+    for h in range(wl.H_q):
+        for a, b in zip(inp.cu_seqlens[:-1], inp.cu_seqlens[1:]):
+            order = np.argsort(-zg[h, a:b], kind="stable")[:wl.k]
+            ref = np.arange(a, b)
+            ref[order] = b
+            assert (eg[h, a:b] == ref).all(), f"expiry head {h} doc [{a},{b})"
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k, causal=False)
+    print("  O", check_close("O", case.host("O"), O, **T_BF16), flush=True)
+    print("  LSE", check_close("LSE", case.host("LSE"), LSE, **T_BF16), flush=True)
+    mass = {}
+    dQ, dK, dV, dz, dza = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, causal=False,
+                                           return_dz_abs=True, abs_out=mass)
+    print("  dQ", check_close("dQ", case.host("dQ"), dQ, **T_BF16), flush=True)
+    for nm, ref in (("dK", dK), ("dV", dV)):
+        print(f"  {nm}", check_close(nm, case.host(nm), ref, summand_abs=mass[nm], srel=DZ_SREL, **T_BF16), flush=True)
+    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dza, srel=DZ_SREL, **T_BF16), flush=True)

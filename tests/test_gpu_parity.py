@@ -238,6 +238,93 @@ def test_mask_backward(gpu, name, dtype):
     print("  dW again", check_close("dW", dWd.cpu().numpy(), dW, **t32), flush=True)
 
 
+# ----------------------------------------------------------------------------- without the causal restriction
+NONCAUSAL = {
+    "nc_ragged_varlen_d64": lambda: wlmod.small_workload("nc_ragged_varlen_d64", 41, 4, 2, 64, 48, (200, 77, 300, 1, 129), causal=False),
+    "nc_multi_tile_d128": lambda: wlmod.small_workload("nc_multi_tile_d128", 42, 4, 2, 128, 160, (700, 260), causal=False),
+    "nc_k_ge_len": lambda: wlmod.small_workload("nc_k_ge_len", 43, 4, 4, 64, 512, (150, 0, 150), causal=False),
+    "nc_k1_d128": lambda: wlmod.small_workload("nc_k1_d128", 44, 2, 1, 128, 1, (300,), causal=False),
+    "nc_k_not_tile_multiple": lambda: wlmod.small_workload("nc_k_not_tile_multiple", 45, 3, 3, 64, 130, (1000,), causal=False),
+}
+
+
+def check_noncausal_mask(case, label):
+    """expiry = end of the document for the document's min(k, n) best keys, own index otherwise;
+    topk_idx: that set on every row; plan: every block of the document lists exactly that set, no
+    partial keys."""
+    inp, wl = case.inp, case.wl
+    cu = inp.cu_seqlens
+    zg = case.host("z").astype(np.float64)
+    eg = case.host("expiry")
+    tk = case.host("topk")
+    pv = case.plan_views()
+    bi = 0
+    for d, (a, b) in enumerate(zip(cu[:-1], cu[1:])):
+        n = int(b - a)
+        if n == 0:
+            continue
+        nb = (n + BQ - 1) // BQ
+        for h in range(wl.H_q):
+            kept = orc.kept_mask_definition(zg[h, a:b], wl.k, causal=False)
+            assert (kept == kept[0]).all()
+            ref_e = np.where(kept[0], b, np.arange(a, b))
+            assert (eg[h, a:b] == ref_e).all(), f"{label}: expiry head {h} doc {d}"
+            ref_tk = orc.topk_indices(zg[h, a:b], wl.k, causal=False)
+            assert (tk[h, a:b] == np.where(ref_tk >= 0, ref_tk + a, -1)).all(), f"{label}: topk_idx head {h} doc {d}"
+            want = (np.flatnonzero(kept[0]) + a).tolist()
+            for blk in range(bi, bi + nb):
+                row = pv["slot"][h, blk]
+                assert sorted(row[row >= 0].tolist()) == want, f"{label}: slot table block {blk} head {h}"
+                assert (row[min(wl.k, n):] == -1).all()
+                assert pv["pcnt"][h, blk] == 0
+        bi += nb
+    assert pv["nblk"] == bi
+
+
+@pytest.mark.parametrize("name", list(NONCAUSAL))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_noncausal_small(gpu, name, dtype):
+    print(f"[case] non-causal {name} {dtype}", flush=True)
+    wl = NONCAUSAL[name]()
+    inp = wlmod.make_inputs(wl, dtype=dtype)
+    case = DeviceCase(inp, gpu, topk=True)
+    case.mask_gen()
+    check_noncausal_mask(case, f"{name}/{dtype}")
+    case.fwd()
+    case.bwd()
+    zg = case.host("z").astype(np.float64)
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k, causal=False)
+    mass = {}
+    dQ, dK, dV, dz, dza = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, causal=False,
+                                           return_dz_abs=True, abs_out=mass)
+    t = tol(dtype == "bf16")
+    print("  O", check_close("O", case.host("O"), O, **t), flush=True)
+    print("  LSE", check_close("LSE", case.host("LSE"), LSE, **t), flush=True)
+    print("  dQ", check_close("dQ", case.host("dQ"), dQ, **t), flush=True)
+    # a kept key is summed over every row of its document: same allowance as in test_backward_small
+    srel = DZ_SREL if dtype == "bf16" else 0.0
+    for nm, ref in (("dK", dK), ("dV", dV)):
+        print(f"  {nm}", check_close(nm, case.host(nm), ref, summand_abs=mass[nm], srel=srel, **t), flush=True)
+    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dza, srel=srel, **t), flush=True)
+    eg = case.host("expiry")
+    never = eg == np.arange(inp.T)[None, :]
+    assert (case.host("dz")[never] == 0.0).all()
+
+
+def test_noncausal_ties_supplied_scores(gpu):
+    print("[case] non-causal ties", flush=True)
+    wl = wlmod.small_workload("nc_ties", 46, 4, 2, 64, 70, (500, 140), causal=False)
+    inp = wlmod.make_inputs(wl)
+    z = tie_scores(wl.H_q, inp.T, 9, 4)
+    case = DeviceCase(inp, gpu, z_override=z, topk=True)
+    case.mask_gen()
+    check_noncausal_mask(case, "nc_ties")
+    case.fwd()
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, z.astype(np.float64), inp.cu_seqlens, wl.k, causal=False)
+    check_close("O", case.host("O"), O, **tol(True))
+    check_close("LSE", case.host("LSE"), LSE, **tol(True))
+
+
 # ----------------------------------------------------------------------------- cross-head scores (Eq. 3, full Delta)
 XHEAD_CASES = {
     # name: (T, H_q, H_kv, d)

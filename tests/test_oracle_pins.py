@@ -328,6 +328,48 @@ def test_sampled_rows_and_keys_match_dense_oracle():
             assert val == pytest.approx(dz[h, j], abs=1e-12)
 
 
+# ----------------------------------------------------------------------------- without the causal restriction
+@pytest.mark.parametrize("ties", [False, True])
+def test_noncausal_is_plain_attention_over_the_gathered_top_k(ties):
+    """Without the causal restriction every row of a document keeps the same min(k, n) best keys
+    (Eq. 4 over all keys), so the path is dense attention over those gathered keys with their scores
+    as a bias.  torch computes that and differentiates it.  Catches: a causal mask left in, a kept set
+    that varies with the row, a wrong tie rule, gradients leaking to unselected keys."""
+    Q, K, V, dO, z = rand_case(n=50, H_q=4, H_kv=2, d=8, seed=31, ties=ties)
+    cu = np.array([0, 20, 50])
+    k, scale = 7, 1.0 / math.sqrt(8)
+    O, LSE = orc.dma_forward(Q, K, V, z, cu, k, causal=False)
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, cu, k, causal=False)
+    Qt, Kt, Vt, zt = (torch.tensor(a, requires_grad=True) for a in (Q, K, V, z))
+    outs = []
+    for a, b in zip(cu[:-1], cu[1:]):
+        per_head = []
+        for h in range(4):
+            g = h // 2
+            sel = np.sort(np.argsort(-z[h, a:b], kind="stable")[:k]) + a
+            S = scale * Qt[a:b, h] @ Kt[sel, g].T + zt[h, sel][None, :]
+            per_head.append(torch.softmax(S, dim=-1) @ Vt[sel, g])
+            assert np.allclose(LSE[h, a:b], torch.logsumexp(S, dim=-1).detach().numpy(), rtol=1e-12)
+        outs.append(torch.stack(per_head, dim=1))
+    Ot = torch.cat(outs, dim=0)
+    assert np.allclose(O, Ot.detach().numpy(), rtol=1e-11, atol=1e-13)
+    (Ot * torch.tensor(dO)).sum().backward()
+    assert np.allclose(dQ, Qt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dK, Kt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dV, Vt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dz, zt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    tk = orc.topk_indices(z[1, 20:50], k, causal=False)
+    assert (tk == tk[0]).all() and (tk[0] == np.sort(np.argsort(-z[1, 20:50], kind="stable")[:k])).all()
+
+
+def test_noncausal_full_window_is_bidirectional_sdpa():
+    Q, K, V, dO, z = rand_case(n=33, H_q=2, H_kv=2, d=8, seed=32)
+    O, _ = orc.dma_forward(Q, K, V, np.zeros_like(z), np.array([0, 33]), 64, causal=False)
+    q, kk, v = (torch.tensor(a).permute(1, 0, 2)[None] for a in (Q, K, V))
+    ref = torch.nn.functional.scaled_dot_product_attention(q, kk, v, is_causal=False)[0].permute(1, 0, 2).numpy()
+    assert np.allclose(O, ref, rtol=1e-10, atol=1e-12)
+
+
 # ----------------------------------------------------------------------------- mask-path backward (chain rule of Eq. 3)
 def _mask_case(seed=3, T=23, H_q=6, H_kv=2, d=5):
     r = np.random.default_rng(seed)
