@@ -221,3 +221,31 @@ def test_noncausal_cfg2_shape_dense(gpu):
     for nm, ref in (("dK", dK), ("dV", dV)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, summand_abs=mass[nm], srel=DZ_SREL, **T_BF16), flush=True)
     print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dza, srel=DZ_SREL, **T_BF16), flush=True)
+
+
+def test_decode_half_million_token_cache(gpu):
+    """The long end of the paper's decode range (Section 5): a 524288-token cache next to a short one."""
+    print("[case] decode against 524288- and 3000-token caches, k = 2048", flush=True)
+    import torch
+    from paper_2508_02124_amd import binding as B
+    lens, H_q, H_kv, d, k = (524288, 3000), 4, 1, 128, 2048
+    T = sum(lens)
+    r = np.random.default_rng(77)
+    rb = lambda shape: wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(r.standard_normal(shape, dtype=np.float32)))
+    K, V, q = rb((T, H_kv, d)), rb((T, H_kv, d)), rb((len(lens), H_q, d))
+    z = r.uniform(0.05, 1.0, size=(H_q, T)).astype(np.float32)
+    z[1] = np.round(z[1] * 64) / 64                  # one head with heavy ties across the threshold
+    cu = np.array([0, lens[0], T], dtype=np.int32)
+    shape = B.make_shape(T=T, n_docs=2, H_q=H_q, H_kv=H_kv, d=d, k=k)
+    dev = lambda x, dt: torch.from_numpy(np.ascontiguousarray(x)).to(gpu).to(dt)
+    Kd, Vd, qd = dev(K, torch.bfloat16), dev(V, torch.bfloat16), dev(q, torch.bfloat16)
+    zd, cud = dev(z, torch.float32), dev(cu, torch.int32)
+    kept = torch.empty(B.dma_decode_kept_bytes(shape) // 4, dtype=torch.int32, device=gpu)
+    o = torch.empty((2, H_q, d), dtype=torch.bfloat16, device=gpu)
+    lse = torch.empty((H_q, 2), device=gpu)
+    B.dma_decode(shape, qd, Kd, Vd, zd, cud, o, lse, kept, kept.numel() * 4)
+    ro, rl, rk = orc.dma_decode(q, K, V, z.astype(np.float64), cu, k)
+    got_k = kept.cpu().numpy()[: 2 * H_q * k].reshape(2, H_q, k)
+    assert (got_k == rk).all()
+    print("  o", check_close("o", o.float().cpu().numpy(), ro, **T_BF16), flush=True)
+    print("  lse", check_close("lse", lse.cpu().numpy(), rl, **T_BF16), flush=True)
