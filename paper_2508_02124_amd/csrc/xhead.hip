@@ -5,7 +5,8 @@
 //   dDelta[h, g, c] = sum_j dx[h, j] v_{g, j, c},   dVz[j, g, c] = sum_h dx[h, j] Delta[h, g, c].
 // Delta is [H_q, H_kv * d] row-major (the weight of a linear layer from the flattened values to the
 // heads).  A [T x H_kv d] x [H_kv d x H_q] contraction with H_q <= 32 output columns and fp32
-// weights: one pass over V, computed with fp32 vector FMAs from LDS tiles.
+// weights.  bf16 values run on the matrix cores (the *_mfma_kernel pair below: the weights split into
+// three bf16 terms, exact); fp32 values, the debug dtype, use fp32 vector FMAs from LDS tiles.
 #include "common.h"
 
 namespace dma {
@@ -119,6 +120,372 @@ __global__ __launch_bounds__(256) void xhead_scores_kernel(const TV* __restrict_
   for (int i = 0; i < HPT; i++) {
     const int h = hq * HPT + i;
     if (h < H_q) z[(size_t)h * T + t] = expf(A[h] * softplus_f(x[i]));
+  }
+}
+
+// Delta[:, g, :] -> three swizzled bf16 planes [32 heads][D] (hi, mid, lo: truncated 8-bit pieces of the
+// fp32 mantissa, hi + mid + lo == the value exactly); heads past H_q are zero rows.  In two halves, so
+// that a kernel can have the loads of the next kv-head in flight while it works on the current one:
+// request() reads the thread's 8-channel chunks into registers, commit() splits and stores them.
+template <int D, int NTHREADS>
+struct DeltaChunks {
+  static constexpr int CPR = D / 8, N = 32 * CPR / NTHREADS;
+  static_assert(N * NTHREADS == 32 * CPR, "chunks must divide evenly over the threads");
+  float w[N][8];
+  __device__ __forceinline__ void request(const float* __restrict__ Delta, int g, int H_q, int H_kv) {
+#pragma unroll
+    for (int j = 0; j < N; j++) {
+      const int ch = threadIdx.x + j * NTHREADS, h = ch / CPR, c = ch % CPR;
+      if (h < H_q) {
+        const float* src = Delta + ((size_t)h * H_kv + g) * D + 8 * c;
+        const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
+        w[j][0] = a.x; w[j][1] = a.y; w[j][2] = a.z; w[j][3] = a.w;
+        w[j][4] = b.x; w[j][5] = b.y; w[j][6] = b.z; w[j][7] = b.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) w[j][e] = 0.f;
+      }
+    }
+  }
+  __device__ __forceinline__ void commit(uint16_t* planes) const {
+    constexpr int PLANE = 32 * D;
+#pragma unroll
+    for (int j = 0; j < N; j++) {
+      const int ch = threadIdx.x + j * NTHREADS, h = ch / CPR, c = ch % CPR;
+      uint32_t pk[3][4];
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        float r = w[j][e];
+#pragma unroll
+        for (int q = 0; q < 3; q++) {
+          const uint32_t top = __float_as_uint(r) & 0xffff0000u;  // the leading 8 mantissa bits, truncated
+          r -= __uint_as_float(top);                              // exact
+          if (e & 1) pk[q][e >> 1] |= top;
+          else pk[q][e >> 1] = top >> 16;
+        }
+      }
+      const int off = TileLayout<D>::off(h, c);
+#pragma unroll
+      for (int q = 0; q < 3; q++)
+        *reinterpret_cast<uint4*>(&planes[q * PLANE + off]) = make_uint4(pk[q][0], pk[q][1], pk[q][2], pk[q][3]);
+    }
+  }
+};
+
+// ---- bf16 values: the contraction on the matrix cores.  V is exact in bf16; the fp32 weights are
+// split into three bf16 terms by truncation (8 + 8 + 8 mantissa bits: hi + mid + lo == the fp32 value
+// exactly), so x = V (hi + mid + lo) is three bf16 MFMA chains with fp32 accumulation and matches the
+// fp32 dot product to accumulation rounding.  One wave per 32-token tile, NW tiles per workgroup;
+// per kv-head the workgroup splits Delta[:, g, :] once into three swizzled LDS planes,
+// each wave reads its V fragments straight from global memory (lane = token, 16 bytes per step).
+// Orientation D[head][token] = Delta_g[head][c] V[token][c]: lane (n, hh) ends up with the scores of
+// token n for heads 8 (v / 4) + 4 hh + v % 4, so consecutive lanes write consecutive tokens of z.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void xhead_scores_mfma_kernel(const uint16_t* __restrict__ V,
+                                                                const float* __restrict__ Delta,
+                                                                const float* __restrict__ A, float* __restrict__ z,
+                                                                int T, int H_q, int H_kv) {
+  constexpr int KS = D / 16, PLANE = 32 * D;
+  __shared__ __align__(16) uint16_t planes[3 * PLANE];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
+  const int t = blockIdx.x * (32 * NW) + w * 32 + n;
+  const int tl = t < T ? t : T - 1;  // rows past the end re-read the last row; their scores are not written
+  FragOffsets<D> fo;
+  fo.init(l);
+  f32x16 acc[3];
+#pragma unroll
+  for (int q = 0; q < 3; q++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[q][v] = 0.f;
+  // the loads of kv-head g + 1 (this lane's V fragments, the thread's Delta chunks) are in flight
+  // while kv-head g is split into the planes and multiplied
+  DeltaChunks<D, 64 * NW> dc;
+  bf16x8 vf[KS];
+  auto load_v = [&](int g, bf16x8 (&f)[KS]) {
+    const uint16_t* vrow = V + ((size_t)tl * H_kv + g) * D + 8 * hh;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) f[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(vrow + 16 * ks));
+  };
+  // one kv-head: `cd`, `cv` were requested one step earlier; `nd`, `nv` receive the next kv-head's loads
+  // (two register sets used alternately, so that nothing is moved and nothing waits for them here; the
+  // barriers order LDS traffic only -- a full __syncthreads() would also wait for the loads in flight)
+  auto step = [&](int g, DeltaChunks<D, 64 * NW>& cd, bf16x8 (&cv)[KS], DeltaChunks<D, 64 * NW>& nd, bf16x8 (&nv)[KS]) {
+    lds_barrier();  // the previous kv-head's readers of the planes are done
+    cd.commit(planes);
+    const int gn = g + 1 < H_kv ? g + 1 : g;
+    nd.request(Delta, gn, H_q, H_kv);
+    load_v(gn, nv);
+    lds_barrier();
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+#pragma unroll
+      for (int q = 0; q < 3; q++) acc[q] = mfma32(fo.row_frag(planes + q * PLANE, 0, ks), cv[ks], acc[q]);
+    }
+  };
+  DeltaChunks<D, 64 * NW> dc2;
+  bf16x8 vf2[KS];
+  dc.request(Delta, 0, H_q, H_kv);
+  load_v(0, vf);
+  for (int g = 0; g < H_kv; g += 2) {
+    step(g, dc, vf, dc2, vf2);
+    if (g + 1 < H_kv) step(g + 1, dc2, vf2, dc, vf);
+  }
+  if (t >= T) return;
+#pragma unroll
+  for (int v = 0; v < 16; v++) {
+    const int h = 8 * (v / 4) + 4 * hh + (v % 4);
+    if (h < H_q) {
+      const float x = (acc[2][v] + acc[1][v]) + acc[0][v];
+      z[(size_t)h * T + t] = expf(A[h] * softplus_f(x));
+    }
+  }
+}
+
+// Chain rule on the matrix cores (bf16 values).  One wave owns TPW 32-token tiles.
+//   phase 1: x as in the forward kernel, but in the orientation D[token][head], so that lane (n, hh)
+//     holds, for head n, the tokens 8 (v / 4) + 4 hh + v % 4: dx in that layout is the operand of the
+//     dDelta contraction as it stands (hi + lo bf16 terms); a bf16 copy goes to a wave-private
+//     [token][head] LDS tile for the dVz contraction; dA is reduced over the lane's tokens.
+//   phase 2, per kv-head (planes staged again, workgroups starting at staggered kv-heads): each tile's
+//     V rows go to a wave-private swizzled LDS tile; dDelta[head][channel] += dx^T V reads it
+//     transposed; dVz[token][channel] = dx Delta_g (hi + mid planes, read transposed) is staged as fp32,
+//     32 channels at a time, and leaves as 32-byte row pieces (added to dV in fp32 when accumulating:
+//     one rounding).  dDelta accumulates over the wave's tiles, is summed over the four waves through LDS
+//     and added to the output once per (workgroup, kv-head).
+template <int D, int TPW>
+__global__ __launch_bounds__(256) void xhead_bwd_mfma_kernel(const uint16_t* __restrict__ V,
+                                                             const float* __restrict__ Delta,
+                                                             const float* __restrict__ A, const float* __restrict__ dz,
+                                                             float* dDelta, float* dA, uint16_t* dV, int accumulate,
+                                                             int T, int H_q, int H_kv) {
+  using TL = TileLayout<D>;
+  constexpr int KS = D / 16, CB = D / 32, PLANE = 32 * D;
+  constexpr int DXS = 40;  // row stride of the [token][head] dx tile (bf16 elements)
+  constexpr int SST = 36;  // row stride of the fp32 staging tile [32 tokens][32 channels]
+  __shared__ __align__(16) uint16_t planes[3 * PLANE];
+  __shared__ __align__(16) uint16_t vtile_all[4][32 * D];
+  __shared__ __align__(16) uint16_t dxt_all[4][TPW][32 * DXS];
+  __shared__ __align__(16) float stage_all[4][32 * SST];
+  __shared__ __align__(16) float red_all[4][CB * 16 * 64];  // per wave: its dDelta[:, g, :] partial sums
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, n = l & 31, hh = l >> 5;
+  uint16_t* vt = vtile_all[w];
+  float* stg = stage_all[w];
+  const int tile0 = (blockIdx.x * 4 + w) * TPW;  // first 32-token tile of this wave
+  FragOffsets<D> fo;
+  fo.init(l);
+  auto wave_fence = [] { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };  // orders this wave's own LDS traffic
+  auto load_v = [&](int tile, int g, bf16x8 (&vf)[KS]) {
+    const int t = tile * 32 + n;
+    const uint16_t* vrow = V + ((size_t)(t < T ? t : T - 1) * H_kv + g) * D + 8 * hh;  // rows past the end: dx is 0
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) vf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(vrow + 16 * ks));
+  };
+
+  // ---- phase 1
+  bf16x8 dxh[TPW][2], dxl[TPW][2];
+  {
+    f32x16 xacc[TPW][3];
+#pragma unroll
+    for (int i = 0; i < TPW; i++)
+#pragma unroll
+      for (int q = 0; q < 3; q++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) xacc[i][q][v] = 0.f;
+    // (the loads of kv-head g + 1 are in flight while kv-head g is split and multiplied)
+    DeltaChunks<D, 256> dc;
+    bf16x8 vf[TPW][KS];
+    auto step = [&](int g, DeltaChunks<D, 256>& cd, bf16x8 (&cv)[TPW][KS], DeltaChunks<D, 256>& nd, bf16x8 (&nv)[TPW][KS]) {
+      lds_barrier();
+      cd.commit(planes);
+      const int gn = g + 1 < H_kv ? g + 1 : g;
+      nd.request(Delta, gn, H_q, H_kv);
+#pragma unroll
+      for (int i = 0; i < TPW; i++) load_v(tile0 + i, gn, nv[i]);
+      lds_barrier();
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+        for (int q = 0; q < 3; q++) {
+          const bf16x8 df = fo.row_frag(planes + q * PLANE, 0, ks);
+#pragma unroll
+          for (int i = 0; i < TPW; i++) xacc[i][q] = mfma32(cv[i][ks], df, xacc[i][q]);
+        }
+    };
+    DeltaChunks<D, 256> dc2;
+    bf16x8 vf2[TPW][KS];
+    dc.request(Delta, 0, H_q, H_kv);
+#pragma unroll
+    for (int i = 0; i < TPW; i++) load_v(tile0 + i, 0, vf[i]);
+    for (int g = 0; g < H_kv; g += 2) {
+      step(g, dc, vf, dc2, vf2);
+      if (g + 1 < H_kv) step(g + 1, dc2, vf2, dc, vf);
+    }
+    const int h = n;
+    const float a = h < H_q ? A[h] : 0.f;
+    float da = 0.f;
+#pragma unroll
+    for (int i = 0; i < TPW; i++) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int tok = 8 * (v / 4) + 4 * hh + (v % 4), t = (tile0 + i) * 32 + tok;
+        float dx = 0.f;
+        if (h < H_q && t < T) {
+          const float x = (xacc[i][2][v] + xacc[i][1][v]) + xacc[i][0][v];
+          const float sp = softplus_f(x);
+          const float zv = expf(a * sp), sig = 1.f / (1.f + expf(-x));
+          const float dzz = dz[(size_t)h * T + t] * zv;
+          dx = dzz * a * sig;
+          da += dzz * sp;
+        }
+        const __bf16 hi = (__bf16)dx;
+        dxh[i][v >> 3][v & 7] = hi;
+        dxl[i][v >> 3][v & 7] = (__bf16)(dx - (float)hi);
+        dxt_all[w][i][tok * DXS + h] = __builtin_bit_cast(uint16_t, hi);
+      }
+    }
+    da += __shfl_xor(da, 32);
+    if (hh == 0 && h < H_q) atomicAdd(dA + h, da);
+  }
+
+  // ---- phase 2 (same software pipeline: V rows, the dV rows to add to, and the Delta chunks of the next
+  // kv-head are requested before this kv-head's work)
+  const int tok2 = l >> 1, half2 = l & 1;  // this lane's row piece of the staged dVz tile
+  auto load_old = [&](int tile, int g, uint4 (&old)[CB][2]) {
+    const int t = tile * 32 + tok2;
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int q2 = 0; q2 < 2; q2++) {
+        old[cb][q2] = make_uint4(0, 0, 0, 0);
+        if (accumulate && t < T)
+          old[cb][q2] = *reinterpret_cast<const uint4*>(dV + ((size_t)t * H_kv + g) * D + 32 * cb + 16 * half2 + 8 * q2);
+      }
+  };
+  DeltaChunks<D, 256> dc;
+  bf16x8 vf[TPW][KS];
+  uint4 old[TPW][CB][2];
+  {
+    const int g0 = blockIdx.x % H_kv;
+    dc.request(Delta, g0, H_q, H_kv);
+#pragma unroll
+    for (int i = 0; i < TPW; i++) {
+      load_v(tile0 + i, g0, vf[i]);
+      load_old(tile0 + i, g0, old[i]);
+    }
+  }
+  auto step2 = [&](int gi, DeltaChunks<D, 256>& cd, bf16x8 (&cv)[TPW][KS], uint4 (&cold)[TPW][CB][2],
+                   DeltaChunks<D, 256>& nd, bf16x8 (&nv)[TPW][KS], uint4 (&nold)[TPW][CB][2]) {
+    const int g = (gi + blockIdx.x) % H_kv;
+    lds_barrier();
+    cd.commit(planes);
+    {
+      const int gn = gi + 1 < H_kv ? (gi + 1 + blockIdx.x) % H_kv : g;
+      nd.request(Delta, gn, H_q, H_kv);
+#pragma unroll
+      for (int i = 0; i < TPW; i++) {
+        load_v(tile0 + i, gn, nv[i]);
+        load_old(tile0 + i, gn, nold[i]);
+      }
+    }
+    lds_barrier();
+    f32x16 dacc[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) dacc[cb][v] = 0.f;
+#pragma unroll
+    for (int i = 0; i < TPW; i++) {
+      const int tbase = (tile0 + i) * 32;
+      if (tbase >= T) continue;  // (wave-uniform; no workgroup barrier inside this loop)
+      wave_fence();  // the previous tile's transposed reads of vt are done
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++)
+        *reinterpret_cast<uint4*>(&vt[TL::off(n, 2 * ks + hh)]) = __builtin_bit_cast(uint4, cv[i][ks]);
+      wave_fence();
+      // dDelta[head][channel] += dx^T V: k runs over tokens 16c + 4hh + e % 4 + 8 (e / 4) on both operands
+#pragma unroll
+      for (int c = 0; c < 2; c++)
+#pragma unroll
+        for (int cb = 0; cb < CB; cb++) {
+          const bf16x8 vtr = fo.tr_frag(vt, 16 * c, cb);
+          dacc[cb] = mfma32(dxh[i][c], vtr, dacc[cb]);
+          dacc[cb] = mfma32(dxl[i][c], vtr, dacc[cb]);
+        }
+      // dVz[token][channel] = dx Delta_g: k runs over heads 16c + 4hh + e % 4 + 8 (e / 4)
+      f32x16 vacc[CB];
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) vacc[cb][v] = 0.f;
+#pragma unroll
+      for (int c = 0; c < 2; c++) {
+        const uint16_t* row = dxt_all[w][i] + n * DXS + 16 * c + 4 * hh;
+        const s16x4 lo4 = *reinterpret_cast<const s16x4*>(row), hi4 = *reinterpret_cast<const s16x4*>(row + 8);
+        const bf16x8 af = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+        for (int cb = 0; cb < CB; cb++) {
+          vacc[cb] = mfma32(af, fo.tr_frag(planes, 16 * c, cb), vacc[cb]);
+          vacc[cb] = mfma32(af, fo.tr_frag(planes + PLANE, 16 * c, cb), vacc[cb]);
+        }
+      }
+      // out through the fp32 staging tile, 32 channels at a time: lane = (token l / 2, half l % 2) writes 16 channels
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++) {
+        wave_fence();  // the previous pass's reads of the staging tile are done
+#pragma unroll
+        for (int v = 0; v < 16; v++) stg[(8 * (v / 4) + 4 * hh + (v % 4)) * SST + n] = vacc[cb][v];
+        wave_fence();
+        const int t = tbase + tok2;
+        float o[16];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          const f32x4 x4 = *reinterpret_cast<const f32x4*>(&stg[tok2 * SST + 16 * half2 + 4 * q4]);
+          o[4 * q4] = x4[0]; o[4 * q4 + 1] = x4[1]; o[4 * q4 + 2] = x4[2]; o[4 * q4 + 3] = x4[3];
+        }
+        if (t < T) {
+          uint16_t* dst = dV + ((size_t)t * H_kv + g) * D + 32 * cb + 16 * half2;
+#pragma unroll
+          for (int q2 = 0; q2 < 2; q2++) {
+            const uint32_t u[4] = {cold[i][cb][q2].x, cold[i][cb][q2].y, cold[i][cb][q2].z, cold[i][cb][q2].w};
+            bf16x8 ob;  // (the rows to add to were requested as zeros when not accumulating)
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              ob[2 * e] = (__bf16)(o[8 * q2 + 2 * e] + __uint_as_float(u[e] << 16));
+              ob[2 * e + 1] = (__bf16)(o[8 * q2 + 2 * e + 1] + __uint_as_float(u[e] & 0xffff0000u));
+            }
+            *reinterpret_cast<uint4*>(dst + 8 * q2) = __builtin_bit_cast(uint4, ob);
+          }
+        }
+      }
+    }
+    // lane (n, hh) holds dDelta[head 8 (v / 4) + 4 hh + v % 4][g][32 cb + n] of its own tiles.  The four waves'
+    // copies are summed through LDS and each wave adds a quarter of the values to the output (the
+    // atomics are the scarce resource here: one set per workgroup and kv-head instead of four);
+    // consecutive lanes, consecutive channels.
+    {
+      constexpr int NV = CB * 16, SH = NV / 4;
+      float* mine = red_all[w];
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) mine[(cb * 16 + v) * 64 + l] = dacc[cb][v];
+      lds_barrier();
+#pragma unroll
+      for (int j = 0; j < SH; j++) {
+        const int idx = w * SH + j, cb = idx / 16, v = idx % 16;
+        const float sum = (red_all[0][idx * 64 + l] + red_all[1][idx * 64 + l]) +
+                          (red_all[2][idx * 64 + l] + red_all[3][idx * 64 + l]);
+        const int h = 8 * (v / 4) + 4 * hh + (v % 4);
+        if (h < H_q) atomicAdd(dDelta + ((size_t)h * H_kv + g) * D + 32 * cb + n, sum);
+      }
+    }
+  };
+  DeltaChunks<D, 256> dc2;
+  bf16x8 vf2[TPW][KS];
+  uint4 old2[TPW][CB][2];
+  for (int gi = 0; gi < H_kv; gi += 2) {
+    step2(gi, dc, vf, old, dc2, vf2, old2);
+    if (gi + 1 < H_kv) step2(gi + 1, dc2, vf2, old2, dc, vf, old);
   }
 }
 
@@ -283,11 +650,15 @@ static int scores_dispatch(int hpt, dim3 grid, size_t sh, hipStream_t st, const 
 int launch_xhead_scores(const dma_shape& s, const void* V, const float* Delta, const float* A, float* z, hipStream_t st) {
   const int hpt = pick_hpt(s.H_q);
   if (!hpt) return DMA_EUNSUPPORTED;
+  if (s.dtype == DMA_BF16) {
+    constexpr int NW = 4;  // waves (32-token tiles) per workgroup
+    const dim3 grid((s.T + 32 * NW - 1) / (32 * NW));
+    if (s.d == 128) xhead_scores_mfma_kernel<128, NW><<<grid, 64 * NW, 0, st>>>((const uint16_t*)V, Delta, A, z, s.T, s.H_q, s.H_kv);
+    else xhead_scores_mfma_kernel<64, NW><<<grid, 64 * NW, 0, st>>>((const uint16_t*)V, Delta, A, z, s.T, s.H_q, s.H_kv);
+    return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+  }
   const dim3 grid((s.T + XT - 1) / XT);
   const size_t sh = (size_t)XT * (s.d + 4) * sizeof(float);
-  if (s.dtype == DMA_BF16)
-    return s.d == 128 ? scores_dispatch<uint16_t, 128>(hpt, grid, sh, st, V, Delta, A, z, s)
-                      : scores_dispatch<uint16_t, 64>(hpt, grid, sh, st, V, Delta, A, z, s);
   return s.d == 128 ? scores_dispatch<float, 128>(hpt, grid, sh, st, V, Delta, A, z, s)
                     : scores_dispatch<float, 64>(hpt, grid, sh, st, V, Delta, A, z, s);
 }
@@ -309,6 +680,16 @@ int launch_xhead_bwd(const dma_shape& s, const void* V, const float* Delta, cons
   if (!hpt) return DMA_EUNSUPPORTED;
   const size_t nd = (size_t)s.H_q * s.H_kv * s.d;
   xhead_zero_kernel<<<(unsigned)((nd + 255) / 256), 256, 0, st>>>(dDelta, nd, dA, (size_t)s.H_q);
+  if (s.dtype == DMA_BF16) {
+    constexpr int TPW = 1;  // 32-token tiles per wave (two halve the atomics but measured slower)
+    const int nwaves = ((s.T + 31) / 32 + TPW - 1) / TPW;
+    const dim3 grid((nwaves + 3) / 4);
+    if (s.d == 128)
+      xhead_bwd_mfma_kernel<128, TPW><<<grid, 256, 0, st>>>((const uint16_t*)V, Delta, A, dz, dDelta, dA, (uint16_t*)dV, accumulate, s.T, s.H_q, s.H_kv);
+    else
+      xhead_bwd_mfma_kernel<64, TPW><<<grid, 256, 0, st>>>((const uint16_t*)V, Delta, A, dz, dDelta, dA, (uint16_t*)dV, accumulate, s.T, s.H_q, s.H_kv);
+    return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+  }
   const int ntiles = (s.T + XT - 1) / XT;
   // tiles per workgroup: about two workgroups per CU (fewer contended atomics on dDelta), within 64 KB of LDS
   const size_t fixed = ((size_t)XT * (s.d + 4) + (size_t)4 * hpt * s.d) * sizeof(float);
