@@ -7,8 +7,10 @@ those of Section 4: Eq. 3-6 forward, Eq. 7-10 backward, and the chain rule of Eq
 carries the bias gradient on to the score parameters (Section 6).
 
 Layout: packed tokens, Q [T, H_q, d], K, V [T, H_kv, d] (bf16 or fp32, contiguous), W [H_q, d]
-and A [H_q] fp32, cu_seqlens [n_docs + 1] int32 on the same device.  The selection of the kept
-keys is piecewise constant, so no gradient flows through it (Section 6).
+and A [H_q] fp32, cu_seqlens [n_docs + 1] int32 on the same device.  A W of shape
+[H_q, H_kv * d] selects the paper's full cross-head sampling tensor (Eq. 3: the score of a head
+contracts the token's values of all heads; dma_scores_xhead and its chain rule).  The selection of
+the kept keys is piecewise constant, so no gradient flows through it (Section 6).
 """
 from __future__ import annotations
 
@@ -35,8 +37,9 @@ def _check_inputs(Q, K, V, W, A, cu_seqlens):
         raise ValueError("expected Q [T, H_q, d] and K, V [T, H_kv, d]")
     if K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise TypeError("Q, K, V must share one dtype")
-    if W.shape != (Q.shape[1], Q.shape[2]) or A.shape != (Q.shape[1],):
-        raise ValueError("expected W [H_q, d] and A [H_q]")
+    H_q, d = Q.shape[1], Q.shape[2]
+    if W.shape not in ((H_q, d), (H_q, K.shape[1] * d)) or A.shape != (H_q,):
+        raise ValueError("expected W [H_q, d] (per head) or [H_q, H_kv * d] (cross-head) and A [H_q]")
     if W.dtype != torch.float32 or A.dtype != torch.float32 or cu_seqlens.dtype != torch.int32:
         raise TypeError("W, A must be float32 and cu_seqlens int32")
 
@@ -59,10 +62,15 @@ class DynamicMaskAttentionFunction(torch.autograd.Function):
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         O = torch.empty_like(Q)
         LSE = torch.empty((H_q, T), dtype=torch.float32, device=dev)
-        B.dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, None, mask)
+        xhead = K.shape[1] > 1 and W.shape[1] == K.shape[1] * d
+        if xhead:
+            B.dma_scores_xhead(shape, V, W, A, z)
+            B.dma_mask_gen(shape, V, None, None, cu_seqlens, z, expiry, None, mask)
+        else:
+            B.dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, None, mask)
         B.dma_fwd(shape, Q, K, V, z, expiry, mask, cu_seqlens, O, LSE, ws, ws_bytes)
         ctx.save_for_backward(Q, K, V, W, A, cu_seqlens, z, expiry, mask, O, LSE)
-        ctx.shape, ctx.ws, ctx.ws_bytes = shape, ws, ws_bytes
+        ctx.shape, ctx.ws, ctx.ws_bytes, ctx.xhead = shape, ws, ws_bytes, xhead
         return O
 
     @staticmethod
@@ -75,7 +83,7 @@ class DynamicMaskAttentionFunction(torch.autograd.Function):
         dW, dA = torch.empty_like(W), torch.empty_like(A)
         B.dma_bwd(shape, Q, K, V, O, dO, LSE, z, expiry, mask, cu_seqlens, dQ, dK, dV, dz, ctx.ws, ctx.ws_bytes)
         # dz -> dW, dA, and the part of dV that flows through the content scores, added in place
-        B.dma_mask_bwd(shape, V, W, A, dz, dW, dA, dV, True)
+        (B.dma_scores_xhead_bwd if ctx.xhead else B.dma_mask_bwd)(shape, V, W, A, dz, dW, dA, dV, True)
         return dQ, dK, dV, dW, dA, None, None, None, None
 
 
@@ -86,23 +94,26 @@ def dynamic_mask_attention(Q, K, V, W, A, cu_seqlens, k, max_seqlen=0, softmax_s
 
 class DynamicMaskAttention(torch.nn.Module):
     """The attention core of a DMA layer (the part between the QKV projections and the output
-    projection).  Parameters: the per-head score projection `W` [H_q, d] (the paper's Delta,
-    taken per head) and gate `A` [H_q].  Their initialisation is a choice of this module, not the
-    paper's: W ~ N(0, 1/d), A = -1, which keeps the initial scores in (0, 1) and close together.
+    projection).  Parameters: the score projection `W` [H_q, d] (the paper's Delta taken per head;
+    [H_q, H_kv * d], the full tensor, with cross_head=True) and the gate `A` [H_q].  Their
+    initialisation is a choice of this module, not the paper's: W ~ N(0, 1 / fan-in), A = -1, which
+    keeps the initial scores in (0, 1) and close together.
 
     forward(q, k, v): [B, L, H, d] batches (each sequence its own document), or packed [T, H, d]
     tensors with cu_seqlens.
     """
 
-    def __init__(self, num_heads, num_kv_heads, head_dim, keep_window, softmax_scale=None, device=None):
+    def __init__(self, num_heads, num_kv_heads, head_dim, keep_window, softmax_scale=None, device=None,
+                 cross_head=False):
         super().__init__()
         if num_heads % num_kv_heads:
             raise ValueError("num_heads must be a multiple of num_kv_heads")
         self.num_heads, self.num_kv_heads, self.head_dim = num_heads, num_kv_heads, head_dim
         self.keep_window = int(keep_window)
         self.softmax_scale = 0.0 if softmax_scale is None else float(softmax_scale)
-        self.W = torch.nn.Parameter(torch.randn(num_heads, head_dim, dtype=torch.float32, device=device)
-                                    / math.sqrt(head_dim))
+        fan_in = head_dim * (num_kv_heads if cross_head else 1)   # cross_head: the full Delta of Eq. 3
+        self.W = torch.nn.Parameter(torch.randn(num_heads, fan_in, dtype=torch.float32, device=device)
+                                    / math.sqrt(fan_in))
         self.A = torch.nn.Parameter(torch.full((num_heads,), -1.0, dtype=torch.float32, device=device))
 
     def forward(self, q, k, v, cu_seqlens=None, max_seqlen=0):
