@@ -275,6 +275,20 @@ def main():
         d_bytes = 4 * wl.H_q * Ld + wl.H_q * kd * (2 * wl.d * 2 + 4)     # z once; K, V rows and z of the kept keys
         out["decode"] = {"workload": f"1 x {Ld}-token cache, H_q={wl.H_q} H_kv={wl.H_kv} d={wl.d} k={kd}", "ms": d_ms,
                          "algorithmic_bytes": d_bytes, "GB/s": d_bytes / (d_ms * 1e-3) / 1e9, "hbm_peak_GB/s": 8000.0}
+        # the same cache in a decode loop: kept sets carried over and updated with the newest key only
+        lens = torch.tensor([Ld - 8], dtype=torch.int32, device=dev)
+        B.dma_decode_step(dshape, qc, Kc, Vc, zc, cuc, lens, True, oc, lc, kc, kb)
+        st_ms = []
+        for i in range(6):
+            lens.add_(1)
+            ev[0].record()
+            B.dma_decode_step(dshape, qc, Kc, Vc, zc, cuc, lens, False, oc, lc, kc, kb)
+            ev[1].record()
+            torch.cuda.synchronize()
+            st_ms.append(ev[0].elapsed_time(ev[1]))
+        s_ms = float(np.median(st_ms[1:]))
+        s_bytes = wl.H_q * kd * (2 * wl.d * 2 + 4 + 4 + 4)       # K, V rows, z (twice) and index of the kept keys
+        out["decode_step"] = {"ms": s_ms, "algorithmic_bytes": s_bytes, "GB/s": s_bytes / (s_ms * 1e-3) / 1e9}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, wl, flops / wl.H_q)
     print(json.dumps(out))

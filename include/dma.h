@@ -170,6 +170,25 @@ int dma_decode(const dma_shape* shape, const void* q, const void* K, const void*
                const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, size_t kept_bytes, void* stream);
 
 /*
+ * Decode in a loop, with the kept sets carried from step to step (Eq. 4 as a one-in / one-out update:
+ * the newest key joins the kept set, or replaces its worst member if it beats it).  For callers
+ * that keep every sequence in a region of fixed capacity: sequence b owns rows
+ * [cu_seqlens[b], cu_seqlens[b+1]) of K, V and z and currently fills the first seq_lens[b] of them
+ * (clamped to the capacity), the last of these being the new token.
+ *   seq_lens in  [n_docs] int32 (device)
+ *   refresh  != 0: select the kept sets from all scores, as dma_decode does (the first step, or after
+ *            anything but "every non-empty sequence grew by exactly one token" happened);
+ *            == 0: `kept` still holds what the previous call left for lengths seq_lens[b] - 1; it is
+ *            updated in place in O(k) per (sequence, head) instead of O(n).
+ *   q, o, lse, kept, kept_bytes: as for dma_decode; the entries of `kept` are global row indices.
+ * The scores of earlier tokens must not change between calls (they depend on each token's own value
+ * vector only).  Every other argument and error as for dma_decode.
+ */
+int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
+                    const int32_t* cu_seqlens, const int32_t* seq_lens, int refresh, void* o, float* lse,
+                    int32_t* kept, size_t kept_bytes, void* stream);
+
+/*
  * Per-stage timing aid.  dma_mask_gen, dma_fwd and dma_bwd each launch several kernels, so a
  * caller cannot bracket one of them with events from outside.  `events` is a HOST array of
  * 2 * DMA_N_STAGES hipEvent_t handles (as void*) owned by the caller, or NULL to switch the aid

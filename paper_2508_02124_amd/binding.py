@@ -65,6 +65,8 @@ def lib():
         L.dma_decode_kept_bytes.restype = sz
         L.dma_decode.argtypes = [shp] + [vp] * 8 + [sz, vp]
         L.dma_decode.restype = i32
+        L.dma_decode_step.argtypes = [shp] + [vp] * 6 + [i32] + [vp] * 3 + [sz, vp]
+        L.dma_decode_step.restype = i32
         L.dma_profile_events.argtypes = [vp]
         L.dma_profile_events.restype = None
         L.dma_strerror.argtypes = [i32]
@@ -143,6 +145,12 @@ def dma_decode_kept_bytes(shape):
 def dma_decode(shape, q, K, V, z, cu_seqlens, o, lse, kept, kept_bytes, stream=None):
     _check(lib().dma_decode(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(z), _ptr(cu_seqlens), _ptr(o),
                             _ptr(lse), _ptr(kept), int(kept_bytes), _stream(stream)), "dma_decode")
+
+
+def dma_decode_step(shape, q, K, V, z, cu_seqlens, seq_lens, refresh, o, lse, kept, kept_bytes, stream=None):
+    _check(lib().dma_decode_step(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(z), _ptr(cu_seqlens),
+                                 _ptr(seq_lens), int(bool(refresh)), _ptr(o), _ptr(lse), _ptr(kept), int(kept_bytes),
+                                 _stream(stream)), "dma_decode_step")
 
 
 def dma_mask_bwd(shape, V, W, A, dz, dW, dA, dV, accumulate, stream=None):

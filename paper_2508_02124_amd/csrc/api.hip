@@ -152,7 +152,21 @@ int dma_decode(const dma_shape* shape, const void* q, const void* K, const void*
     return DMA_EINVAL;
   if (!kept || kept_bytes < dma_decode_kept_bytes(shape)) return DMA_EWORKSPACE;
   const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->d);
-  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, o, lse, kept, (hipStream_t)stream);
+  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, nullptr, 0, o, lse, kept, (hipStream_t)stream);
+}
+
+int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
+                    const int32_t* cu_seqlens, const int32_t* seq_lens, int refresh, void* o, float* lse,
+                    int32_t* kept, size_t kept_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!q || !K || !V || !z || !cu_seqlens || !seq_lens || !o || !lse) return DMA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(z) || !aligned16(o) || !aligned16(kept))
+    return DMA_EINVAL;
+  if (!kept || kept_bytes < dma_decode_kept_bytes(shape)) return DMA_EWORKSPACE;
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->d);
+  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, seq_lens, refresh == 0, o, lse, kept,
+                       (hipStream_t)stream);
 }
 
 void dma_profile_events(void** events) { dma::g_stage_events = events; }

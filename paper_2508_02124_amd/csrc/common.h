@@ -133,7 +133,8 @@ int launch_xhead_bwd(const dma_shape& s, const void* V, const float* Delta, cons
 size_t decode_part_floats(const dma_shape& s);
 size_t decode_sel_words(const dma_shape& s);
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
-                  const int32_t* cu, void* o, float* lse, int32_t* kept, hipStream_t st);
+                  const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
+                  hipStream_t st);
 
 // stage events (see dma_profile_events): no-ops unless the caller armed them on this thread
 void prof_begin(int stage, hipStream_t st);

@@ -23,6 +23,7 @@ __device__ __forceinline__ uint32_t desc_key_u32(float z) {
 struct DecSel {
   const float* z;
   const int32_t* cu;
+  const int32_t* lens;  // nullable: current length of each sequence inside its rows [cu[b], cu[b + 1])
   int32_t* kept;
   uint32_t* hist;  // [4][n_docs * H_q][256], zeroed before the first pass
   uint32_t* cnt;   // [n_docs * H_q][nsl][4 waves][2]: keys better than / equal to the threshold
@@ -60,13 +61,19 @@ __device__ __forceinline__ void dec_pick(const uint32_t* h256, int l, uint32_t& 
   remaining = (uint32_t)__shfl((int)rem, src);
 }
 
+// length of sequence b: all of its rows, or lens[b] of them (clamped to the rows it owns)
+__device__ __forceinline__ int dec_len(const int32_t* __restrict__ cu, const int32_t* __restrict__ lens, int b) {
+  const int cap = cu[b + 1] - cu[b];
+  return lens ? max(0, min(lens[b], cap)) : cap;
+}
+
 struct DecSlice {
   int a, n, kk, j0, j1;  // document start / length, kept count, this wave's key range [j0, j1)
 };
 __device__ __forceinline__ DecSlice dec_slice(const DecSel& p, int b, int sl, int w) {
   DecSlice s;
   s.a = p.cu[b];
-  s.n = p.cu[b + 1] - s.a;
+  s.n = dec_len(p.cu, p.lens, b);
   s.kk = p.k < s.n ? p.k : s.n;
   const int slen = ((s.n + p.nsl - 1) / p.nsl + 255) / 256 * 256;
   const int wlen = slen / 4;
@@ -214,6 +221,71 @@ __global__ void decode_zero_kernel(uint32_t* p, size_t n) {
   if (i < n) p[i] = 0u;
 }
 
+// ---- the kept set carried from one decode step to the next (Eq. 4 as a one-in / one-out update):
+// `kept` holds the min(k, n - 1) best of the sequence's first n - 1 keys in ascending index order; the
+// new key n - 1 joins while fewer than k are kept, otherwise it replaces the worst kept key if it
+// beats it (a tie goes to the lower index, and the new key has the highest).  One workgroup per
+// (sequence, head); O(k) work instead of a selection over all n scores.
+__global__ __launch_bounds__(256) void decode_update_kernel(const float* __restrict__ z, const int32_t* __restrict__ cu,
+                                                            const int32_t* __restrict__ lens, int32_t* kept, int T,
+                                                            int H_q, int k) {
+  const int bh = blockIdx.x, b = bh / H_q, h = bh % H_q, tid = threadIdx.x, l = tid & 63, w = tid >> 6;
+  const int n = dec_len(cu, lens, b);
+  if (n <= 0) return;
+  const int kcap = k < T ? k : T, kprev = min(k, n - 1), jn = cu[b] + n - 1;
+  int32_t* list = kept + (size_t)bh * kcap;
+  if (kprev < k) {  // still filling (kprev < kcap: kprev <= n - 1 < T)
+    if (tid == 0) list[kprev] = jn;
+    return;
+  }
+  const float* zh = z + (size_t)h * T;
+  // worst kept key: largest (descending-score key, index); position kept alongside
+  unsigned long long worst = 0ull;
+  int wpos = -1;
+  for (int i = tid; i < kprev; i += 256) {
+    const int id = list[i];
+    const unsigned long long c = ((unsigned long long)desc_key_u32(zh[id]) << 32) | (uint32_t)id;
+    if (wpos < 0 || c > worst) {
+      worst = c;
+      wpos = i;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned long long oc = __shfl_xor(worst, off);
+    const int op = __shfl_xor(wpos, off);
+    if (op >= 0 && (wpos < 0 || oc > worst)) {
+      worst = oc;
+      wpos = op;
+    }
+  }
+  __shared__ unsigned long long sw[4];
+  __shared__ int sp[4];
+  if (l == 0) {
+    sw[w] = worst;
+    sp[w] = wpos;
+  }
+  __syncthreads();
+  for (int i = 0; i < 4; i++)
+    if (sp[i] >= 0 && (wpos < 0 || sw[i] > worst)) {
+      worst = sw[i];
+      wpos = sp[i];
+    }
+  const unsigned long long cn = ((unsigned long long)desc_key_u32(zh[jn]) << 32) | (uint32_t)jn;
+  if (cn > worst) return;  // the new key does not make it (workgroup-uniform)
+  // drop position wpos: entries behind it move one place down, chunk by chunk (a chunk reads before
+  // any thread writes, and a later chunk only overwrites what the earlier one has already read)
+  for (int i0 = wpos; i0 < kprev - 1; i0 += 256) {
+    const int i = i0 + tid;
+    int v = 0;
+    if (i < kprev - 1) v = list[i + 1];
+    __syncthreads();
+    if (i < kprev - 1) list[i] = v;
+    __syncthreads();
+  }
+  if (tid == 0) list[kprev - 1] = jn;
+}
+
 // Keys per workgroup of the attention pass.
 constexpr int DEC_CHUNK = 256;
 
@@ -224,10 +296,11 @@ template <typename TV, int D>
 __global__ __launch_bounds__(256) void decode_attend_kernel(const TV* __restrict__ q, const TV* __restrict__ K,
                                                             const TV* __restrict__ V, const float* __restrict__ z,
                                                             const int32_t* __restrict__ cu,
+                                                            const int32_t* __restrict__ lens,
                                                             const int32_t* __restrict__ kept, float* part, int T,
                                                             int H_q, int H_kv, int k, int nsplit, float c2) {
   const int bh = blockIdx.x, b = bh / H_q, h = bh % H_q, sp = blockIdx.y;
-  const int n = cu[b + 1] - cu[b];
+  const int n = dec_len(cu, lens, b);
   const int kcap = k < T ? k : T, kk = k < n ? k : n;
   const int32_t* list = kept + (size_t)bh * kcap;
   const int i0 = sp * DEC_CHUNK, i1 = min(i0 + DEC_CHUNK, kk);
@@ -316,9 +389,10 @@ __global__ __launch_bounds__(256) void decode_attend_kernel(const TV* __restrict
 // (4) merge the chunks of one (sequence, head): o = sum_c o_c 2^(M_c - M) / sum_c l_c 2^(M_c - M).
 template <typename TV, int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(const float* __restrict__ part, const int32_t* __restrict__ cu,
-                                                         TV* o, float* lse, int H_q, int k, int nsplit) {
+                                                         const int32_t* __restrict__ lens, TV* o, float* lse, int H_q,
+                                                         int k, int nsplit) {
   const int bh = blockIdx.x, b = bh / H_q, h = bh % H_q, n_docs = gridDim.x / H_q, c = threadIdx.x;
-  const int n = cu[b + 1] - cu[b];
+  const int n = dec_len(cu, lens, b);
   TV* orow = o + (size_t)bh * D;
   if (n <= 0) {  // empty sequence: zero output, LSE = -inf
     orow[c] = TV(0.f);
@@ -364,16 +438,19 @@ size_t decode_sel_words(const dma_shape& s) {
 
 template <typename TV, int D>
 static void launch_decode_t(const dma_shape& s, float c2, const void* q, const void* K, const void* V, const float* z,
-                            const int32_t* cu, void* o, float* lse, int32_t* kept, float* part, int nsplit,
-                            hipStream_t st) {
+                            const int32_t* cu, const int32_t* lens, void* o, float* lse, int32_t* kept, float* part,
+                            int nsplit, hipStream_t st) {
   const int nbh = s.n_docs * s.H_q;
-  decode_attend_kernel<TV, D><<<dim3(nbh, nsplit), 256, 0, st>>>((const TV*)q, (const TV*)K, (const TV*)V, z, cu, kept,
-                                                                  part, s.T, s.H_q, s.H_kv, s.k, nsplit, c2);
-  decode_merge_kernel<TV, D><<<nbh, D, 0, st>>>(part, cu, (TV*)o, lse, s.H_q, s.k, nsplit);
+  decode_attend_kernel<TV, D><<<dim3(nbh, nsplit), 256, 0, st>>>((const TV*)q, (const TV*)K, (const TV*)V, z, cu, lens,
+                                                                  kept, part, s.T, s.H_q, s.H_kv, s.k, nsplit, c2);
+  decode_merge_kernel<TV, D><<<nbh, D, 0, st>>>(part, cu, lens, (TV*)o, lse, s.H_q, s.k, nsplit);
 }
 
+// incremental == 0: the kept sets are selected from all scores; otherwise they are carried over from
+// the previous step and updated with the newest key of every sequence.
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
-                  const int32_t* cu, void* o, float* lse, int32_t* kept, hipStream_t st) {
+                  const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
+                  hipStream_t st) {
   const float c2 = scale * LOG2E;
   const size_t kcap = (size_t)(s.k < s.T ? s.k : s.T);
   const int nsplit = (int)((kcap + DEC_CHUNK - 1) / DEC_CHUNK);
@@ -381,24 +458,26 @@ int launch_decode(const dma_shape& s, float scale, const void* q, const void* K,
                                          align_up((size_t)s.n_docs * s.H_q * kcap * 4, 256));
   const int nbh = s.n_docs * s.H_q;
   DecSel ds;
-  ds.z = z; ds.cu = cu; ds.kept = kept;
+  ds.z = z; ds.cu = cu; ds.lens = lens; ds.kept = kept;
   ds.hist = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(part) + align_up(decode_part_floats(s) * 4, 256));
   ds.cnt = ds.hist + 4 * (size_t)nbh * 256;
   ds.T = s.T; ds.H_q = s.H_q; ds.k = s.k; ds.nsl = decode_nsl(s);
-  {
+  if (incremental) {
+    decode_update_kernel<<<nbh, 256, 0, st>>>(z, cu, lens, kept, s.T, s.H_q, s.k);
+  } else {
     const size_t nz = 4 * (size_t)nbh * 256;
     decode_zero_kernel<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(ds.hist, nz);
+    const dim3 sgrid(nbh, ds.nsl);
+    for (int pass = 3; pass >= 0; pass--) decode_hist_kernel<<<sgrid, 256, 0, st>>>(ds, pass);
+    decode_count_kernel<<<sgrid, 256, 0, st>>>(ds);
+    decode_write_kernel<<<sgrid, 256, 0, st>>>(ds);
   }
-  const dim3 sgrid(nbh, ds.nsl);
-  for (int pass = 3; pass >= 0; pass--) decode_hist_kernel<<<sgrid, 256, 0, st>>>(ds, pass);
-  decode_count_kernel<<<sgrid, 256, 0, st>>>(ds);
-  decode_write_kernel<<<sgrid, 256, 0, st>>>(ds);
   if (s.dtype == DMA_BF16) {
-    if (s.d == 128) launch_decode_t<__bf16, 128>(s, c2, q, K, V, z, cu, o, lse, kept, part, nsplit, st);
-    else launch_decode_t<__bf16, 64>(s, c2, q, K, V, z, cu, o, lse, kept, part, nsplit, st);
+    if (s.d == 128) launch_decode_t<__bf16, 128>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
+    else launch_decode_t<__bf16, 64>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
   } else {
-    if (s.d == 128) launch_decode_t<float, 128>(s, c2, q, K, V, z, cu, o, lse, kept, part, nsplit, st);
-    else launch_decode_t<float, 64>(s, c2, q, K, V, z, cu, o, lse, kept, part, nsplit, st);
+    if (s.d == 128) launch_decode_t<float, 128>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
+    else launch_decode_t<float, 64>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
   }
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }

@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_exported(lib):
     names = declared_symbols()
     assert {"dma_mask_gen", "dma_fwd", "dma_bwd", "dma_mask_bwd", "dma_decode", "dma_decode_kept_bytes",
-            "dma_scores_xhead", "dma_scores_xhead_bwd",
+            "dma_scores_xhead", "dma_scores_xhead_bwd", "dma_decode_step",
             "dma_mask_bytes", "dma_workspace_bytes",
             "dma_strerror", "dma_version"} <= set(names)
     for n in names:
@@ -94,6 +94,12 @@ def test_error_codes_before_any_launch(lib):
     with pytest.raises(B.DmaError) as e:
         B.dma_decode(ok, p, p, p, p, None, p, p, p, 1 << 30, stream=0)   # cu_seqlens missing
     assert e.value.status == B.DMA_EINVAL
+    with pytest.raises(B.DmaError) as e:
+        B.dma_decode_step(ok, p, p, p, p, p, None, 1, p, p, p, 1 << 30, stream=0)   # seq_lens missing
+    assert e.value.status == B.DMA_EINVAL
+    with pytest.raises(B.DmaError) as e:
+        B.dma_decode_step(ok, p, p, p, p, p, p, 0, p, p, p, 8, stream=0)            # kept buffer too small
+    assert e.value.status == B.DMA_EWORKSPACE
     assert B.dma_decode_kept_bytes(ok) >= 2 * 64 * 4
     assert "workspace" in B.strerror(B.DMA_EWORKSPACE)
     assert B.strerror(0) == "ok"

@@ -458,3 +458,54 @@ def test_decode(gpu, name, dtype):
         B.dma_decode(shape, dev(q, tdt), dev(K, tdt), dev(V, tdt), dev(z), torch.from_numpy(cu).to(gpu), o, lse,
                      kept_buf, nb - 256 if nb > 256 else 0)
     assert e.value.status == B.DMA_EWORKSPACE
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_step_loop(gpu, dtype):
+    """A decode loop over sequences in fixed-capacity regions: the first call selects the kept sets,
+    every later call updates them with the newest key only.  After every step the kept sets must be
+    exactly the oracle's top-k of the current prefix (one sequence crosses from "fewer than k keys" to
+    "full", one starts empty, one head has heavy ties), and o / lse must match."""
+    print(f"[case] decode step loop {dtype}", flush=True)
+    caps, lens0, steps = (400, 64, 900), (120, 0, 700), 45
+    H_q, H_kv, d, k = 4, 2, 64, 130
+    T = sum(caps)
+    starts = np.concatenate([[0], np.cumsum(caps)]).astype(np.int32)
+    r = np.random.default_rng(61)
+    rnd = lambda shape: r.standard_normal(shape).astype(np.float32)
+    K, V = rnd((T, H_kv, d)), rnd((T, H_kv, d))
+    if dtype == "bf16":
+        K, V = (wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(x)) for x in (K, V))
+    z = r.uniform(0.05, 1.0, size=(H_q, T)).astype(np.float32)
+    z[2] = np.round(z[2] * 8) / 8                         # heavy ties
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dev = lambda x, dt: torch.from_numpy(np.ascontiguousarray(x)).to(gpu).to(dt)
+    Kd, Vd, zd, cud = dev(K, tdt), dev(V, tdt), dev(z, torch.float32), dev(starts, torch.int32)
+    shape = B.make_shape(T=T, n_docs=len(caps), H_q=H_q, H_kv=H_kv, d=d, k=k,
+                         dtype=B.DMA_BF16 if dtype == "bf16" else B.DMA_F32)
+    kb = B.dma_decode_kept_bytes(shape)
+    kept = torch.full((kb // 4,), -5, dtype=torch.int32, device=gpu)
+    o = torch.empty((len(caps), H_q, d), dtype=tdt, device=gpu)
+    lse = torch.empty((H_q, len(caps)), device=gpu)
+    t = tol(dtype == "bf16")
+    for step in range(steps):
+        lens = np.array([l0 + step for l0 in lens0], dtype=np.int32)
+        q = rnd((len(caps), H_q, d))
+        if dtype == "bf16":
+            q = wlmod.bf16_bits_to_f32(wlmod.f32_to_bf16_bits(q))
+        B.dma_decode_step(shape, dev(q, tdt), Kd, Vd, zd, cud, dev(lens, torch.int32), step == 0, o, lse, kept, kb)
+        # the oracle sees the current contents packed
+        rows = np.concatenate([np.arange(starts[b], starts[b] + lens[b]) for b in range(len(caps))]).astype(np.int64)
+        cu_p = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        ro, rl, rk = orc.dma_decode(q, K[rows], V[rows], z[:, rows].astype(np.float64), cu_p, k)
+        got_k = kept.cpu().numpy()[: len(caps) * H_q * k].reshape(len(caps), H_q, k)
+        for b in range(len(caps)):
+            kk = min(k, int(lens[b]))
+            want = rk[b] - cu_p[b] + starts[b]            # [H_q, kk], packed row -> row of the capacity layout
+            assert want.shape == (H_q, kk) and (got_k[b, :, :kk] == want).all(), f"step {step} sequence {b}: kept set"
+        check_close(f"o step {step}", o.float().cpu().numpy(), ro, **t)
+        gl = lse.cpu().numpy()
+        empty = lens == 0                                  # an empty sequence: o = 0, lse = -inf on both sides
+        assert (gl[:, empty] == -np.inf).all() and (rl[:, empty] == -np.inf).all()
+        check_close(f"lse step {step}", gl[:, ~empty], rl[:, ~empty], **t)
+    print("  all steps match", flush=True)
