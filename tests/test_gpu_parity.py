@@ -13,7 +13,7 @@ import torch
 import oracle as orc
 from paper_2508_02124_amd import binding as B
 from paper_2508_02124_amd import workloads as wlmod
-from gpu_harness import BQ, DZ_SREL, DeviceCase, check_close, tol
+from gpu_harness import BQ, DZ_SREL, DeviceCase, check_close, dz_allowance, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -31,6 +31,9 @@ SMALL = {
     "single_token": lambda: wlmod.small_workload("single_token", 18, 2, 2, 64, 4, (1,)),
     "k2_many_blocks": lambda: wlmod.small_workload("k2_many_blocks", 19, 3, 3, 64, 2, (900,)),
     "gqa8_d64": lambda: wlmod.small_workload("gqa8_d64", 20, 8, 1, 64, 70, (520,)),
+    # 600 short documents (1..12 tokens, a few empty): block table, per-document sorts and plans at scale
+    "many_tiny_docs": lambda: wlmod.small_workload(
+        "many_tiny_docs", 24, 2, 1, 64, 5, tuple(int(x) for x in np.random.default_rng(24).integers(0, 13, 600))),
 }
 
 
@@ -169,7 +172,7 @@ def test_backward_small(gpu, name, dtype):
     srel = DZ_SREL if dtype == "bf16" else 0.0
     for nm, ref in (("dK", dK), ("dV", dV)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, summand_abs=mass[nm], srel=srel, **t), flush=True)
-    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dza, srel=srel, **t), flush=True)
+    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dz_allowance(dza, mass["dzD"]), srel=srel, **t), flush=True)
     # keys that are never kept get exactly zero gradient into z
     eg = case.host("expiry")
     never = eg == np.arange(inp.T)[None, :]
@@ -305,7 +308,7 @@ def test_noncausal_small(gpu, name, dtype):
     srel = DZ_SREL if dtype == "bf16" else 0.0
     for nm, ref in (("dK", dK), ("dV", dV)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, summand_abs=mass[nm], srel=srel, **t), flush=True)
-    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dza, srel=srel, **t), flush=True)
+    print("  dz", check_close("dz", case.host("dz"), dz, summand_abs=dz_allowance(dza, mass["dzD"]), srel=srel, **t), flush=True)
     eg = case.host("expiry")
     never = eg == np.arange(inp.T)[None, :]
     assert (case.host("dz")[never] == 0.0).all()
