@@ -533,11 +533,15 @@ __global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ 
     for (int r = 0; r < rounds; r++) {
       // (a thread may read an entry another thread has already advanced this round: still an
       // ancestor on the same chain, so the jumping only converges faster)
+      int moved = 0;
       for (int j = tid; j < n; j += 1024) {
         const int q = ls[j];
-        if (q >= k) ls[j] = ls[q];
+        if (q >= k) {
+          ls[j] = ls[q];
+          moved = 1;
+        }
       }
-      __syncthreads();
+      if (!__syncthreads_or(moved)) break;  // every entry is a root: chains are short (about n / k links)
     }
     for (int j = tid; j < n; j += 1024) sid[j] = ls[j];
     return;
