@@ -249,3 +249,47 @@ def test_decode_half_million_token_cache(gpu):
     assert (got_k == rk).all()
     print("  o", check_close("o", o.float().cpu().numpy(), ro, **T_BF16), flush=True)
     print("  lse", check_close("lse", lse.cpu().numpy(), rl, **T_BF16), flush=True)
+
+
+def test_long_document_backward_sampled(gpu):
+    """One 131072-token document, forward and backward: 512 query blocks, so the key-stationary sweeps are
+    cut into several work items per slot group and the selection takes the global-memory sort path.
+    Expiry exhaustive; sampled rows (O, LSE, dQ); sampled short-lived keys (dK, dV, dz), for which the
+    oracle first computes O and LSE of exactly the rows that keep them."""
+    print("[case] 131072-token document, fwd + bwd, sampled", flush=True)
+    wl = wlmod.Workload("long131k", 1006, H_q=4, H_kv=2, d=128, k=2048, seqlens=(131072,))
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen(); case.fwd(); case.bwd()
+    zg, eg = check_expiry_all(case, "long131k")
+    rng = np.random.default_rng(6)
+    rows = sample_rows(rng, inp, [0, 3], 6)
+    check_rows(case, zg, rows, "long131k", backward=True)
+    print("  sampled rows ok", flush=True)
+    # keys of kv-head 1 (q-heads 2, 3) that are kept for 1..400 rows by both heads, spread over the document
+    G = wl.H_q // wl.H_kv
+    life = (eg[2:4] - np.arange(inp.T)[None, :])
+    cand = np.flatnonzero((life.min(0) >= 1) & (life.max(0) <= 400))
+    keys = sorted(set(int(x) for x in rng.choice(cand, 6, replace=False)) | {int(cand[-1])})
+    LSE = np.zeros((wl.H_q, inp.T))
+    O = np.zeros((inp.T, wl.H_q, wl.d))
+    need = sorted({(h, i) for j in keys for h in (2, 3) for i in range(j, int(eg[h, j]))})
+    for (h, i), rec in zip(need, orc.dma_rows(inp.Q, inp.K, inp.V, zg, None, inp.cu_seqlens, wl.k, need)):
+        LSE[h, i], O[i, h] = rec["LSE"], rec["O"]
+    recs = orc.dma_keys(inp.Q, inp.K, inp.V, zg, inp.dO, LSE, O, inp.cu_seqlens, wl.k, [(1, j) for j in keys])
+    dK, dV, dz = case.host("dK"), case.host("dV"), case.host("dz")
+    # short-lived keys late in a long document collect a few hundred terms of size 1 / k: their gradients
+    # are of order 1e-2, so the absolute part of the tolerance is tightened twentyfold to keep the check sharp
+    tight = dict(atol=1e-3, rtol=1e-2, frob=1e-2)
+    ref_dK, ref_dV = np.stack([r["dK"] for r in recs]), np.stack([r["dV"] for r in recs])
+    print("  |dK|, |dV| max of the sampled keys:", float(np.abs(ref_dK).max()), float(np.abs(ref_dV).max()), flush=True)
+    print("  dK keys", check_close("dK", np.stack([dK[j, 1] for j in keys]), ref_dK, **tight), flush=True)
+    print("  dV keys", check_close("dV", np.stack([dV[j, 1] for j in keys]), ref_dV, **tight), flush=True)
+    heads = [2, 3]
+    got_dz = np.array([[dz[h, j] for h in heads] for j in keys])
+    ref_dz = np.array([[r["dz"][h] for h in heads] for r in recs])
+    abs_dz = np.array([[r["dz_abs"][h] for h in heads] for r in recs])
+    print("  dz keys", check_close("dz", got_dz, ref_dz, summand_abs=abs_dz, srel=DZ_SREL, **tight), flush=True)
+    never = eg == np.arange(inp.T)[None, :]
+    assert (dz[never] == 0.0).all()
+    assert np.isfinite(case.host("dQ")).all() and np.isfinite(dK).all() and np.isfinite(dV).all()
