@@ -700,9 +700,6 @@ int launch_xhead_bwd(const dma_shape& s, const void* V, const float* Delta, cons
   if (tpw < 1) tpw = 1;
   const dim3 grid((ntiles + tpw - 1) / tpw);
   const size_t sh = fixed + per_tile * tpw;
-  if (s.dtype == DMA_BF16)
-    return s.d == 128 ? bwd_dispatch<uint16_t, 128>(hpt, grid, sh, st, V, Delta, A, dz, dDelta, dA, dV, accumulate, s, tpw)
-                      : bwd_dispatch<uint16_t, 64>(hpt, grid, sh, st, V, Delta, A, dz, dDelta, dA, dV, accumulate, s, tpw);
   return s.d == 128 ? bwd_dispatch<float, 128>(hpt, grid, sh, st, V, Delta, A, dz, dDelta, dA, dV, accumulate, s, tpw)
                     : bwd_dispatch<float, 64>(hpt, grid, sh, st, V, Delta, A, dz, dDelta, dA, dV, accumulate, s, tpw);
 }
