@@ -239,15 +239,36 @@ __global__ __launch_bounds__(256) void decode_update_kernel(const float* __restr
     return;
   }
   const float* zh = z + (size_t)h * T;
-  // worst kept key: largest (descending-score key, index); position kept alongside
+  // worst kept key: largest (descending-score key, index); position kept alongside.  Lists of up to
+  // 8 * 256 entries stay in registers (all loads of a thread in flight together, and the shift below
+  // needs no second pass over memory).
+  constexpr int UPD_R = 8;
+  const bool in_regs = kprev <= UPD_R * 256;
+  int ids[UPD_R];
   unsigned long long worst = 0ull;
   int wpos = -1;
-  for (int i = tid; i < kprev; i += 256) {
-    const int id = list[i];
-    const unsigned long long c = ((unsigned long long)desc_key_u32(zh[id]) << 32) | (uint32_t)id;
-    if (wpos < 0 || c > worst) {
-      worst = c;
-      wpos = i;
+  if (in_regs) {
+    float zz[UPD_R];
+#pragma unroll
+    for (int j = 0; j < UPD_R; j++) ids[j] = tid + 256 * j < kprev ? list[tid + 256 * j] : -1;
+#pragma unroll
+    for (int j = 0; j < UPD_R; j++) zz[j] = ids[j] >= 0 ? zh[ids[j]] : 0.f;
+#pragma unroll
+    for (int j = 0; j < UPD_R; j++) {
+      const unsigned long long c = ((unsigned long long)desc_key_u32(zz[j]) << 32) | (uint32_t)ids[j];
+      if (ids[j] >= 0 && (wpos < 0 || c > worst)) {
+        worst = c;
+        wpos = tid + 256 * j;
+      }
+    }
+  } else {
+    for (int i = tid; i < kprev; i += 256) {
+      const int id = list[i];
+      const unsigned long long c = ((unsigned long long)desc_key_u32(zh[id]) << 32) | (uint32_t)id;
+      if (wpos < 0 || c > worst) {
+        worst = c;
+        wpos = i;
+      }
     }
   }
 #pragma unroll
@@ -273,6 +294,15 @@ __global__ __launch_bounds__(256) void decode_update_kernel(const float* __restr
     }
   const unsigned long long cn = ((unsigned long long)desc_key_u32(zh[jn]) << 32) | (uint32_t)jn;
   if (cn > worst) return;  // the new key does not make it (workgroup-uniform)
+  if (in_regs) {  // every entry was read before the barrier above: entries behind wpos move one place down
+#pragma unroll
+    for (int j = 0; j < UPD_R; j++) {
+      const int i = tid + 256 * j;
+      if (i > wpos && i < kprev) list[i - 1] = ids[j];
+    }
+    if (tid == 0) list[kprev - 1] = jn;
+    return;
+  }
   // drop position wpos: entries behind it move one place down, chunk by chunk (a chunk reads before
   // any thread writes, and a later chunk only overwrites what the earlier one has already read)
   for (int i0 = wpos; i0 < kprev - 1; i0 += 256) {
