@@ -31,3 +31,21 @@ def test_varlen_lengths_pack_exactly():
     lens = wlmod.draw_seqlens(rng, 65536, 512, 8192)
     assert sum(lens) == 65536 and all(1 <= n <= 8192 for n in lens)
     assert all(n >= 512 for n in lens[:-1])
+
+
+def test_benchmark_shapes_follow_the_papers_speed_benchmark_table():
+    """The synthetic headline and long-context workloads use the head counts, head dimension and
+    precision of the paper's own kernel benchmark (fixture: tests/golden/speed_benchmark_config.txt);
+    its window w = 1024 is one point of the cfg4 sweep, and bench.py warms up as often as the paper."""
+    import os
+    import re
+    here = os.path.dirname(os.path.abspath(__file__))
+    cfg = dict(line.split() for line in open(os.path.join(here, "golden", "speed_benchmark_config.txt"))
+               if line.strip() and not line.startswith("#"))
+    for name in ("cfg3", "cfg4"):
+        wl = wlmod.CONFIGS[name]
+        assert (wl.H_q, wl.H_kv, wl.d) == (int(cfg["n_h"]), int(cfg["n_h_kv"]), int(cfg["d_h"]))
+    assert wlmod.CONFIGS["cfg4"].with_k(int(cfg["w"])).k == 1024
+    assert wlmod.make_inputs(wlmod.CONFIGS["cfg1"]).dtype == cfg["precision"]
+    bench_src = open(os.path.join(os.path.dirname(here), "bench.py")).read()
+    assert re.search(r'"--warmup", type=int, default=%d\b' % int(cfg["warmups"]), bench_src)
