@@ -211,6 +211,18 @@ typedef enum {
 } dma_stage;
 void dma_profile_events(void** events);
 
+/*
+ * Roofline yardsticks measured on the device at hand (not operations of the paper):
+ *   dma_probe_mfma  n_workgroups workgroups of 8 waves run `iters` rounds of 8 independent
+ *                   32x32x16 bf16 MFMA chains from registers: n_workgroups * 8 * iters * 8 * 32768 flops.
+ *                   sink: DEVICE buffer of n_workgroups * 512 floats (receives sums; contents are
+ *                   of no interest).
+ *   dma_probe_copy  plain streaming copy of `bytes` (a multiple of 16) from src to dst (DEVICE).
+ * Both enqueue one kernel on `stream` and return; the caller times them with events.
+ */
+int dma_probe_mfma(float* sink, int n_workgroups, int iters, void* stream);
+int dma_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 const char* dma_strerror(int status);
 int dma_version(void);
 

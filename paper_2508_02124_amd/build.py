@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdma_hip.so")
-SOURCES = ["api.hip", "mask_gen.hip", "fwd.hip", "bwd.hip", "mask_bwd.hip", "xhead.hip", "decode.hip", "debug_f32.hip"]
+SOURCES = ["api.hip", "mask_gen.hip", "fwd.hip", "bwd.hip", "mask_bwd.hip", "xhead.hip", "decode.hip", "debug_f32.hip", "probe.hip"]
 # The attention kernels never produce a NaN from finite inputs (inf - inf is avoided explicitly), so
 # their max / compare chains may skip NaN canonicalisation; infinities stay honoured (-inf masks).
 EXTRA_FLAGS = {"fwd.hip": ["-fno-honor-nans"], "bwd.hip": ["-fno-honor-nans"]}

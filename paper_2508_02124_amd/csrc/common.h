@@ -136,6 +136,9 @@ int launch_decode(const dma_shape& s, float scale, const void* q, const void* K,
                   const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
                   hipStream_t st);
 
+int launch_probe_mfma(float* sink, int nwg, int iters, hipStream_t st);
+int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+
 // stage events (see dma_profile_events): no-ops unless the caller armed them on this thread
 void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);

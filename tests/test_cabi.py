@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_exported(lib):
     names = declared_symbols()
     assert {"dma_mask_gen", "dma_fwd", "dma_bwd", "dma_mask_bwd", "dma_decode", "dma_decode_kept_bytes",
-            "dma_scores_xhead", "dma_scores_xhead_bwd", "dma_decode_step",
+            "dma_scores_xhead", "dma_scores_xhead_bwd", "dma_decode_step", "dma_probe_mfma", "dma_probe_copy",
             "dma_mask_bytes", "dma_workspace_bytes",
             "dma_strerror", "dma_version"} <= set(names)
     for n in names:
