@@ -185,13 +185,13 @@ const char* dma_strerror(int status) {
   switch (status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
-    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads)";
     case DMA_EWORKSPACE: return "workspace missing or smaller than dma_workspace_bytes()";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";
   }
 }
 
-int dma_version(void) { return 100; }
+int dma_version(void) { return 120; }
 
 }  // extern "C"
