@@ -156,12 +156,16 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Stage events are recorded inside the timed region, on every fourth step (each armed step
+    # records 20 events between the launches, which costs 0.05-0.15 ms of its 3.9 ms at the headline
+    # shape; the kernels' durations do not depend on it).
     nst = len(B.STAGES)
-    evsets = [HipEvents(2 * nst) for _ in range(args.steps)]
+    armed = [i for i in range(args.steps) if i % 4 == 0]
+    evsets = [HipEvents(2 * nst) for _ in armed]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        B.dma_profile_events(evsets[i].arr)
+        B.dma_profile_events(evsets[armed.index(i)].arr if i in armed else None)
         step()
     B.dma_profile_events(None)
     torch.cuda.synchronize()
