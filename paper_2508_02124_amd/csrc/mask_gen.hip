@@ -510,27 +510,25 @@ __global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ 
   int32_t* sid = slotid + hb;
   const int32_t* ex = expiry + hb;
   const int tid = threadIdx.x;
-  for (int j = tid; j < n; j += 1024) {
-    par[j] = -1;
-    sid[j] = j;
-  }
-  __syncthreads();
-  if (n <= k) return;
-  for (int j = tid; j < n; j += 1024) {
-    const int e = ex[j] - a;
-    if (e > j && e < n) {  // key j is evicted at row e by key e
-      par[e] = a + j;
-      sid[e] = j;
-    }
-  }
-  __syncthreads();
   const int rounds = dev_ceil_log2(n);
-  constexpr int LDS_N = 16384;
-  __shared__ int32_t ls[LDS_N];
-  if (n <= LDS_N) {  // pointer jumping towards the chain root (< k), in LDS
-    for (int j = tid; j < n; j += 1024) ls[j] = sid[j];
+  constexpr int LDS_N = 65536;  // local indices fit 16 bits up to this length
+  __shared__ uint16_t ls[LDS_N];
+  if (n > k && n <= LDS_N) {
+    // the chain links live in LDS from the start: only parent[] and the final slot ids touch memory
+    for (int j = tid; j < n; j += 1024) {
+      par[j] = -1;
+      ls[j] = (uint16_t)j;
+    }
     __syncthreads();
-    for (int r = 0; r < rounds; r++) {
+    for (int j = tid; j < n; j += 1024) {
+      const int e = ex[j] - a;
+      if (e > j && e < n) {  // key j is evicted at row e by key e
+        par[e] = a + j;
+        ls[e] = (uint16_t)j;
+      }
+    }
+    __syncthreads();
+    for (int r = 0; r < rounds; r++) {  // pointer jumping towards the chain root (< k)
       // (a thread may read an entry another thread has already advanced this round: still an
       // ancestor on the same chain, so the jumping only converges faster)
       int moved = 0;
@@ -546,12 +544,30 @@ __global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ 
     for (int j = tid; j < n; j += 1024) sid[j] = ls[j];
     return;
   }
+  for (int j = tid; j < n; j += 1024) {
+    par[j] = -1;
+    sid[j] = j;
+  }
+  __syncthreads();
+  if (n <= k) return;
+  for (int j = tid; j < n; j += 1024) {
+    const int e = ex[j] - a;
+    if (e > j && e < n) {  // key j is evicted at row e by key e
+      par[e] = a + j;
+      sid[e] = j;
+    }
+  }
+  __syncthreads();
   for (int r = 0; r < rounds; r++) {
+    int moved = 0;
     for (int j = tid; j < n; j += 1024) {
       const int q = sid[j];
-      if (q >= k) sid[j] = sid[q];
+      if (q >= k) {
+        sid[j] = sid[q];
+        moved = 1;
+      }
     }
-    __syncthreads();
+    if (!__syncthreads_or(moved)) break;
   }
 }
 
