@@ -12,6 +12,7 @@ constexpr int BQ = 256;        // query rows per block (one workgroup of the que
 constexpr int KT = 64;         // keys per tile of the query-stationary kernels
 constexpr int MAXPART = 2 * BQ;  // a block has at most BQ entering + BQ expiring keys
 constexpr int SG = 128;        // slot columns per workgroup of the key-stationary backward
+constexpr int SEG = 16384;     // keys per segment of the selection (what one workgroup sorts in LDS)
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -27,8 +28,9 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 struct PlanLayout {
   int nblk_cap;    // upper bound on the number of query blocks: T / BQ + n_docs
   int kpad;        // slot-table row length: min(k, T) rounded up to SG
-  int nbits_cap;   // wavelet levels needed for the longest possible document
-  int wcap;        // 64-bit words per wavelet level per head: T / 64 + 2 * n_docs
+  int nbits_cap;   // wavelet levels of a segment (at most log2 SEG)
+  int wcap;        // 64-bit words per wavelet level per head (every segment has two spare words)
+  int nseg_cap;    // upper bound on the number of segments: T / SEG + n_docs + 1
   size_t off_hdr;      // int32[16]: [0] number of blocks
   size_t off_consts;   // 512 B: [0,256) zeros (a dummy K/V row); then float -inf, int32 0, int32 -1, float +inf
   size_t off_zq;       // float[H_q][T]: z / softmax_scale, the bias as the start value of a Q K^T accumulator
@@ -43,7 +45,7 @@ struct PlanLayout {
   size_t off_si0, off_si1;   // uint32[H_q][T] x2: sort payload (local key index)
   size_t off_wbits;    // uint64[H_q][nbits_cap][wcap]: zero-bit masks of each wavelet level
   size_t off_wcnt;     // uint32[H_q][nbits_cap][wcap]: zeros before each word
-  size_t off_wzero;    // uint32[H_q][n_docs][nbits_cap]: total zeros of each level
+  size_t off_wzero;    // uint32[H_q][nseg_cap][nbits_cap]: total zeros of each level of each segment
   size_t total;
 };
 
@@ -61,8 +63,9 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   p.nblk_cap = s.T / BQ + s.n_docs;
   int kk = s.k < s.T ? s.k : s.T;
   p.kpad = (kk + SG - 1) / SG * SG;
-  p.nbits_cap = ceil_log2(s.T < 2 ? 2 : s.T);
-  p.wcap = s.T / 64 + 2 * s.n_docs;
+  p.nbits_cap = ceil_log2(s.T < 2 ? 2 : (s.T < SEG ? s.T : SEG));
+  p.nseg_cap = s.T / SEG + s.n_docs + 1;
+  p.wcap = s.T / 64 + 2 * (s.T / SEG) + 5 * s.n_docs + SEG / 64 + 8;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   p.off_hdr = take(64);
@@ -81,7 +84,7 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   p.off_si1 = take(H * T * 4);
   p.off_wbits = take(H * p.nbits_cap * (size_t)p.wcap * 8);
   p.off_wcnt = take(H * p.nbits_cap * (size_t)p.wcap * 4);
-  p.off_wzero = take(H * (size_t)s.n_docs * p.nbits_cap * 4);
+  p.off_wzero = take(H * (size_t)p.nseg_cap * p.nbits_cap * 4);
   p.total = o;
   return p;
 }

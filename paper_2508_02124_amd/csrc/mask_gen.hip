@@ -145,33 +145,56 @@ struct SortArgs {
   unsigned long long* wbits;
   uint32_t* wcnt;
   uint32_t* wzero;
-  int T, n_docs, k, nbits_cap, wcap;
+  int T, n_docs, k, nbits_cap, wcap, nseg_cap;
 };
 
-// One workgroup (16 waves) per (document, head).  Stable LSD radix sort, 8-bit digits: every wave
-// owns a contiguous run of 64-key chunks, counts its digits, and after a (digit, wave)-ordered scan
-// scatters its chunks in order, ranking equal digits inside a chunk with ballots.
+// Documents are handled in segments of SEG consecutive keys (one for most documents).  Segment p of
+// document d (first token a) has the slot number a / SEG + d + p, unique and increasing over the
+// batch, and its wavelet levels start at word seg_woff of each level's row.
+__device__ __forceinline__ int seg_slot(int a, int d, int p) { return a / SEG + d + p; }
+__device__ __forceinline__ int seg_woff(int a, int d, int p) { return a / 64 + 2 * (a / SEG) + 5 * d + p * (SEG / 64 + 2); }
+
+// One workgroup (16 waves) per (segment, head).  The segment's keys are sorted by (score descending,
+// index ascending) -- a stable LSD radix sort on 8-bit digits, entirely in registers and LDS: every
+// wave owns a contiguous run of 64-key chunks, counts its digits, and after a (digit, wave)-ordered
+// scan scatters its chunks in order, ranking equal digits inside a chunk with ballots -- and a
+// wavelet matrix is built over the rank-ordered local indices (most significant bit first: per 64
+// positions the mask of zero bits and the number of zeros before the word; the array is stably
+// partitioned, zeros first, for the next level).  A document of one segment leaves its rank order in
+// si0 for expiry_kernel; the segments of a longer document leave their sorted keys and local
+// indices in sk1 / si1 for merge_expiry_kernel.
 __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
-  const int d = blockIdx.x, h = blockIdx.y;
-  const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
-  if (n <= 0) return;
+  const int slot = blockIdx.x, h = blockIdx.y;
+  // the document whose segment range [seg_slot(a, d, 0), seg_slot(a, d, nseg)) holds this slot
+  int d = 0;
+  {
+    int lo = 0, hi = p.n_docs;  // answer in [lo, hi): largest d with seg_slot(cu[d], d, 0) <= slot
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (seg_slot(p.cu[mid], mid, 0) <= slot) lo = mid; else hi = mid;
+    }
+    d = lo;
+  }
+  const int a = p.cu[d], b = p.cu[d + 1], ndoc = b - a;
+  const int ps = slot - seg_slot(a, d, 0), nseg = (ndoc + SEG - 1) / SEG;
+  if (ndoc <= 0 || ps >= nseg) return;
+  const int n = min(SEG, ndoc - ps * SEG);  // keys of this segment
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-  const size_t hb = (size_t)h * p.T + a;
-  if (n <= p.k) {  // every causal key is kept by every later row
+  const size_t hb = (size_t)h * p.T + a + (size_t)ps * SEG;
+  if (ndoc <= p.k) {  // every causal key is kept by every later row
     for (int j = tid; j < n; j += 1024) p.expiry[hb + j] = b;
     return;
   }
-  uint32_t *k0 = p.sk0 + hb, *k1 = p.sk1 + hb, *i0 = p.si0 + hb, *i1 = p.si1 + hb;
   __shared__ uint32_t hist[4096];  // [digit][wave]
   __shared__ uint32_t wsum[16];
   const int nchunks = (n + 63) / 64, cpw = (nchunks + 15) / 16;
-  const int c_begin = w * cpw, c_end = min(nchunks, c_begin + cpw);
+  const int c_begin = w * cpw;
   const unsigned long long lt = (1ull << l) - 1ull;
-  constexpr int NB = 16;           // chunk loads kept in flight per wave
-  constexpr int LDS_N = 16384;     // longest document sorted entirely in LDS
-
-  if (n <= LDS_N) {
-    // ---- whole document in registers (16 elements per thread, chunk c of a wave = elements
+  constexpr int NB = 16;           // chunks per wave: 16 waves x 16 chunks x 64 keys = SEG
+  constexpr int LDS_N = SEG;
+  static_assert(16 * NB * 64 == SEG, "a segment is what one workgroup holds in registers");
+  {
+    // ---- whole segment in registers (16 elements per thread, chunk c of a wave = elements
     // 64c + lane) and LDS: every pass scatters from registers into LDS and reads its chunks back.
     __shared__ __align__(16) uint32_t lk[LDS_N];
     __shared__ __align__(16) uint32_t li[LDS_N];
@@ -243,16 +266,27 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
         }
       }
     }
-    // sorted: ii holds the key indices in rank order; the expiry kernel reads them from si0
+    // sorted: kk / ii hold the keys and the local indices in rank order
+    if (nseg == 1) {
 #pragma unroll
-    for (int i = 0; i < NB; i++) {
-      const int j = (c_begin + i) * 64 + l;
-      if (i < cpw && j < n) i0[j] = ii[i];
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        if (i < cpw && j < n) p.si0[hb + j] = ii[i];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        const int j = (c_begin + i) * 64 + l;
+        if (i < cpw && j < n) {
+          p.sk1[hb + j] = kk[i];
+          p.si1[hb + j] = ii[i];
+        }
+      }
     }
     // wavelet matrix over ii (see below), partitioned through LDS; the level tables are collected
     // in the (now free) key buffer and written out once at the end, so no level waits on a store
     const int nbits = dev_ceil_log2(n);
-    const int woff = a / 64 + 2 * d;
+    const int woff = seg_woff(a, d, ps);
     const int lrow = nchunks + 1;  // entries per level
     unsigned long long* lwb = reinterpret_cast<unsigned long long*>(lk);  // [nbits][lrow]
     uint32_t* lwc = lk + 2 * 14 * (LDS_N / 64 + 1);                        // [nbits][lrow]
@@ -307,194 +341,100 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
       const size_t o = ((size_t)h * p.nbits_cap + lev) * p.wcap + woff + c;
       p.wbits[o] = lwb[i];
       p.wcnt[o] = lwc[i];
-      if (c == nchunks) p.wzero[((size_t)h * p.n_docs + d) * p.nbits_cap + lev] = lwc[i];
+      if (c == nchunks) p.wzero[((size_t)h * p.nseg_cap + slot) * p.nbits_cap + lev] = lwc[i];
     }
-    return;
-  }
-
-  for (int j = tid; j < n; j += 1024) {
-    k0[j] = desc_key(p.z[hb + j]);
-    i0[j] = j;
-  }
-  __syncthreads();
-
-  uint32_t *sk = k0, *dk = k1, *si = i0, *di = i1;
-  for (int pass = 0; pass < 4; pass++) {
-    const int shift = 8 * pass;
-    for (int i = tid; i < 4096; i += 1024) hist[i] = 0;
-    __syncthreads();
-    for (int cb = c_begin; cb < c_end; cb += NB) {  // NB chunk loads in flight at a time
-      uint32_t kk[NB];
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int j = (cb + i) * 64 + l;
-        kk[i] = (cb + i < c_end && j < n) ? sk[j] : 0u;
-      }
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int j = (cb + i) * 64 + l;
-        if (cb + i < c_end && j < n) atomicAdd(&hist[((kk[i] >> shift) & 255u) * 16 + w], 1u);
-      }
-    }
-    __syncthreads();
-    {  // exclusive scan of hist[4096] in (digit, wave) order
-      const uint32_t v0 = hist[4 * tid], v1 = hist[4 * tid + 1], v2 = hist[4 * tid + 2], v3 = hist[4 * tid + 3];
-      const uint32_t s = v0 + v1 + v2 + v3;
-      uint32_t inc = s;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t t = __shfl_up(inc, off);
-        if (l >= off) inc += t;
-      }
-      if (l == 63) wsum[w] = inc;
-      __syncthreads();
-      uint32_t wbase = 0;
-      for (int i = 0; i < w; i++) wbase += wsum[i];
-      const uint32_t ex = wbase + inc - s;
-      hist[4 * tid] = ex;
-      hist[4 * tid + 1] = ex + v0;
-      hist[4 * tid + 2] = ex + v0 + v1;
-      hist[4 * tid + 3] = ex + v0 + v1 + v2;
-    }
-    __syncthreads();
-    for (int cb = c_begin; cb < c_end; cb += NB) {
-      uint32_t kk[NB], ii[NB];
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int j = (cb + i) * 64 + l;
-        const bool valid = cb + i < c_end && j < n;
-        kk[i] = valid ? sk[j] : 0u;
-        ii[i] = valid ? si[j] : 0u;
-      }
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int j = (cb + i) * 64 + l;
-        const bool valid = cb + i < c_end && j < n;
-        const uint32_t key = kk[i], idx = ii[i];
-        const uint32_t dig = (key >> shift) & 255u;
-        unsigned long long m = __ballot(valid);
-#pragma unroll
-        for (int bit = 0; bit < 8; bit++) {
-          const bool one = (dig >> bit) & 1u;
-          const unsigned long long bm = __ballot(one);
-          m &= one ? bm : ~bm;
-        }
-        const uint32_t rank = __popcll(m & lt);
-        const uint32_t base = hist[dig * 16 + w];
-        if (valid) {
-          dk[base + rank] = key;
-          di[base + rank] = idx;
-          if (rank == 0) hist[dig * 16 + w] = base + (uint32_t)__popcll(m);
-        }
-      }
-    }
-    __syncthreads();
-    uint32_t* t;
-    t = sk; sk = dk; dk = t;
-    t = si; si = di; di = t;
-  }
-  // sorted: si == i0 holds the key indices in rank order.
-
-  // Wavelet matrix over that array (values = key indices), most significant bit first.  Each level
-  // stores, per 64 positions, the mask of zero bits and the number of zeros before the word; the
-  // array is then stably partitioned (zeros first) for the next level.
-  const int nbits = dev_ceil_log2(n);
-  const int woff = a / 64 + 2 * d;
-  uint32_t* src = i0;
-  uint32_t* dst = k0;
-  for (int lev = 0; lev < nbits; lev++) {
-    const int sh = nbits - 1 - lev;
-    unsigned long long* wb = p.wbits + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
-    uint32_t* wc = p.wcnt + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
-    uint32_t zc = 0;
-    for (int cb = c_begin; cb < c_end; cb += NB) {
-      uint32_t vv[NB];
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int j = (cb + i) * 64 + l;
-        vv[i] = (cb + i < c_end && j < n) ? src[j] : 0xffffffffu;  // all-ones: never counted as a zero bit
-      }
-#pragma unroll
-      for (int i = 0; i < NB; i++) zc += (uint32_t)__popcll(__ballot(!((vv[i] >> sh) & 1u)));
-    }
-    if (l == 0) wsum[w] = zc;
-    __syncthreads();
-    uint32_t run = 0, Z = 0;
-    for (int i = 0; i < 16; i++) {
-      const uint32_t x = wsum[i];
-      if (i < w) run += x;
-      Z += x;
-    }
-    for (int cb = c_begin; cb < c_end; cb += NB) {
-      uint32_t vv[NB];
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int j = (cb + i) * 64 + l;
-        vv[i] = (cb + i < c_end && j < n) ? src[j] : 0u;
-      }
-#pragma unroll
-      for (int i = 0; i < NB; i++) {
-        const int c = cb + i, j = c * 64 + l;
-        const bool valid = c < c_end && j < n;
-        const uint32_t v = vv[i];
-        const bool zero = valid && !((v >> sh) & 1u);
-        const unsigned long long zm = __ballot(zero);
-        const uint32_t zb = run + (uint32_t)__popcll(zm & lt);  // zeros before position j
-        if (l == 0 && c < c_end) {
-          wb[c] = zm;
-          wc[c] = run;
-        }
-        if (valid) dst[zero ? zb : Z + ((uint32_t)j - zb)] = v;
-        run += (uint32_t)__popcll(zm);
-      }
-    }
-    if (tid == 0) {
-      wb[nchunks] = 0ull;
-      wc[nchunks] = Z;
-      p.wzero[((size_t)h * p.n_docs + d) * p.nbits_cap + lev] = Z;
-    }
-    __syncthreads();
-    src = dst;
-    dst = (dst == k0) ? k1 : k0;
   }
 }
 
-// One thread per (head, rank position): expiry of the key at that rank.
+// The kk-th smallest (0-based) local index among the first `hi` rank positions of a segment:
+// one range-quantile query on its wavelet matrix.
+__device__ __forceinline__ uint32_t wavelet_kth(const SortArgs& p, int h, int slot, int woff, int nbits, uint32_t hi,
+                                                uint32_t kk) {
+  uint32_t lo = 0, val = 0;
+  for (int lev = 0; lev < nbits; lev++) {
+    const unsigned long long* wb = p.wbits + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
+    const uint32_t* wc = p.wcnt + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
+    const uint32_t zlo = wc[lo >> 6] + (uint32_t)__popcll(wb[lo >> 6] & ((1ull << (lo & 63)) - 1ull));
+    const uint32_t zhi = wc[hi >> 6] + (uint32_t)__popcll(wb[hi >> 6] & ((1ull << (hi & 63)) - 1ull));
+    const uint32_t c0 = zhi - zlo;
+    if (kk < c0) {
+      lo = zlo;
+      hi = zhi;
+    } else {
+      kk -= c0;
+      const uint32_t Z = p.wzero[((size_t)h * p.nseg_cap + slot) * p.nbits_cap + lev];
+      lo = Z + (lo - zlo);
+      hi = Z + (hi - zhi);
+      val |= 1u << (nbits - 1 - lev);
+    }
+  }
+  return val;
+}
+
+// Documents of one segment.  One thread per (head, rank position): expiry of the key at that rank,
+// e_j = max(j, k-th smallest index among the keys ranked ahead of j).
 __global__ __launch_bounds__(256) void expiry_kernel(SortArgs p) {
   const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
   if (t >= p.T) return;
   const int d = find_doc(p.cu, p.n_docs, t);
   const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
-  if (n <= p.k) return;
+  if (n <= p.k || n > SEG) return;
   const int r = t - a;
   const int j = (int)p.si0[(size_t)h * p.T + t];
-  int e;
-  if (r < p.k) {
-    e = b;
-  } else {
-    const int nbits = dev_ceil_log2(n);
-    const int woff = a / 64 + 2 * d;
-    uint32_t lo = 0, hi = (uint32_t)r, kk = (uint32_t)p.k - 1u, val = 0;
-    for (int lev = 0; lev < nbits; lev++) {
-      const unsigned long long* wb = p.wbits + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
-      const uint32_t* wc = p.wcnt + ((size_t)h * p.nbits_cap + lev) * p.wcap + woff;
-      const uint32_t zlo = wc[lo >> 6] + (uint32_t)__popcll(wb[lo >> 6] & ((1ull << (lo & 63)) - 1ull));
-      const uint32_t zhi = wc[hi >> 6] + (uint32_t)__popcll(wb[hi >> 6] & ((1ull << (hi & 63)) - 1ull));
-      const uint32_t c0 = zhi - zlo;
-      if (kk < c0) {
-        lo = zlo;
-        hi = zhi;
-      } else {
-        kk -= c0;
-        const uint32_t Z = p.wzero[((size_t)h * p.n_docs + d) * p.nbits_cap + lev];
-        lo = Z + (lo - zlo);
-        hi = Z + (hi - zhi);
-        val |= 1u << (nbits - 1 - lev);
-      }
-    }
-    e = a + max(j, (int)val);
-  }
+  int e = b;
+  if (r >= p.k)
+    e = a + max(j, (int)wavelet_kth(p, h, seg_slot(a, d, 0), seg_woff(a, d, 0), dev_ceil_log2(n), (uint32_t)r,
+                                    (uint32_t)p.k - 1u));
   p.expiry[(size_t)h * p.T + a + j] = e;
+}
+
+// Longer documents.  One thread per (head, key), visited in the sorted order of its segment.  Its
+// rank in the whole document is its rank in the segment plus, for every other segment, the number
+// of keys there that come before it -- a binary search in that segment's sorted keys (ties go to
+// the lower index, i.e. to the earlier segment).  Those same counts say how many of the keys ranked
+// ahead of it lie in each segment, so the k-th smallest index among them is found by walking the
+// segments in index order and asking the wavelet matrix of the one that holds it.
+__global__ __launch_bounds__(256) void merge_expiry_kernel(SortArgs p) {
+  const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+  if (t >= p.T) return;
+  const int d = find_doc(p.cu, p.n_docs, t);
+  const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
+  if (n <= p.k || n <= SEG) return;
+  const int nseg = (n + SEG - 1) / SEG;
+  const int ps = (t - a) / SEG, r = (t - a) - ps * SEG;
+  const size_t hd = (size_t)h * p.T + a;
+  const uint32_t key = p.sk1[hd + (t - a)];
+  const int j = ps * SEG + (int)p.si1[hd + (t - a)];  // index in the document
+  // keys of segment s that precede (key, j): all equal keys of an earlier segment do, none of a later one
+  auto before = [&](int s) -> int {
+    if (s == ps) return r;
+    const uint32_t* ks = p.sk1 + hd + (size_t)s * SEG;
+    int lo = 0, hi = min(SEG, n - s * SEG);
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      const uint32_t v = ks[mid];
+      if (s < ps ? v <= key : v < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+  };
+  int R = 0;
+  for (int s = 0; s < nseg; s++) R += before(s);
+  p.si0[hd + R] = (uint32_t)j;  // rank order of the whole document
+  int e = b;
+  if (R >= p.k) {
+    uint32_t kk = (uint32_t)p.k - 1u;
+    for (int s = 0; s < nseg; s++) {
+      const uint32_t c = (uint32_t)before(s);
+      if (kk < c) {
+        const int ns = min(SEG, n - s * SEG);
+        const int val = (int)wavelet_kth(p, h, seg_slot(a, d, s), seg_woff(a, d, s), dev_ceil_log2(ns), c, kk);
+        e = a + max(j, s * SEG + val);
+        break;
+      }
+      kk -= c;
+    }
+  }
+  p.expiry[hd + j] = e;
 }
 
 // ------------------------------------------------------------------ slots
@@ -719,8 +659,9 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   sa.wcnt = (uint32_t*)(base + L.off_wcnt);
   sa.wzero = (uint32_t*)(base + L.off_wzero);
   sa.T = s.T; sa.n_docs = s.n_docs; sa.k = s.k; sa.nbits_cap = L.nbits_cap; sa.wcap = L.wcap;
+  sa.nseg_cap = L.nseg_cap;
   prof_begin(DMA_STAGE_SORT, st);
-  sort_wavelet_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(sa);
+  sort_wavelet_kernel<<<dim3(L.nseg_cap, s.H_q), 1024, 0, st>>>(sa);
   prof_end(DMA_STAGE_SORT, st);
   const auto fill = [&](int32_t* dst, size_t n, int32_t v) {
     size_t grid = (n + 2047) / 2048;
@@ -734,11 +675,15 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
     prof_begin(DMA_STAGE_PLAN, st);
     fill(slot_tab, (size_t)s.H_q * L.nblk_cap * L.kpad, -1);
     fill(pcnt, (size_t)s.H_q * L.nblk_cap, 0);
+    // (documents of several segments get their whole-document rank order from the merge kernel; the
+    // causal expiry it also writes is overwritten below)
+    if (s.T > SEG) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     noncausal_plan_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, sa.si0, docblk, expiry, slot_tab,
                                                                         s.T, s.k, L.nblk_cap, L.kpad);
   } else {
     prof_begin(DMA_STAGE_EXPIRY, st);
     expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    if (s.T > SEG) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     prof_end(DMA_STAGE_EXPIRY, st);
     prof_begin(DMA_STAGE_PLAN, st);
     slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
