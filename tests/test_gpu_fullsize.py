@@ -293,3 +293,42 @@ def test_long_document_backward_sampled(gpu):
     never = eg == np.arange(inp.T)[None, :]
     assert (dz[never] == 0.0).all()
     assert np.isfinite(case.host("dQ")).all() and np.isfinite(dK).all() and np.isfinite(dV).all()
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_documents_of_several_segments_next_to_short_ones(gpu, causal):
+    """The selection works in segments of 16384 keys: documents of 3 and 2 segments (ragged last
+    segments), a one-segment document between them, heavy ties in one head.  Expiry exhaustive against
+    the definition, forward on sampled rows (causal) or the last rows (otherwise)."""
+    print(f"[case] multi-segment documents, causal={causal}", flush=True)
+    wl = wlmod.Workload("multiseg", 1007, H_q=2, H_kv=1, d=64, k=700, seqlens=(40000, 5000, 17000), causal=causal)
+    inp = wlmod.make_inputs(wl)
+    rz = np.random.default_rng(8)
+    z = rz.uniform(0.05, 1.0, size=(wl.H_q, inp.T)).astype(np.float32)
+    z[1] = np.round(z[1] * 512) / 512                     # ties across segments
+    case = DeviceCase(inp, gpu, z_override=z)
+    case.mask_gen(); case.fwd()
+    eg = case.host("expiry")
+    zd = z.astype(np.float64)
+    for h in range(wl.H_q):
+        for a, b in zip(inp.cu_seqlens[:-1], inp.cu_seqlens[1:]):
+            if causal:
+                ref = orc.expiry_sequential(zd[h, a:b], wl.k) + a
+            else:
+                order = np.argsort(-zd[h, a:b], kind="stable")[:wl.k]
+                ref = np.arange(a, b)
+                ref[order] = b
+            assert (eg[h, a:b] == ref).all(), f"expiry head {h} doc [{a},{b})"
+    if causal:
+        rows = sample_rows(np.random.default_rng(9), inp, [0, 1], 5)
+        check_rows(case, zd, rows, "multiseg", backward=False)
+    else:
+        O, LSE = case.host("O"), case.host("LSE")
+        for a, b in zip(inp.cu_seqlens[:-1], inp.cu_seqlens[1:]):
+            for h in range(wl.H_q):                       # every row of a document keeps the same keys
+                kept = np.flatnonzero(eg[h, a:b] == b) + a
+                i = b - 1
+                s = (inp.K[kept, 0].astype(np.float64) @ inp.Q[i, h].astype(np.float64)) / np.sqrt(wl.d) + zd[h, kept]
+                pr = np.exp(s - s.max()); pr /= pr.sum()
+                check_close("O last row", O[i, h], pr @ inp.V[kept, 0].astype(np.float64), **T_BF16)
+    assert np.isfinite(case.host("O")).all()
