@@ -417,14 +417,24 @@ __global__ __launch_bounds__(256) void merge_expiry_kernel(SortArgs p) {
     }
     return lo;
   };
+  constexpr int NC = 8;  // counts kept in registers (documents of up to 8 segments search only once)
+  int cnt[NC];
   int R = 0;
-  for (int s = 0; s < nseg; s++) R += before(s);
+#pragma unroll
+  for (int s = 0; s < NC; s++) {
+    cnt[s] = s < nseg ? before(s) : 0;
+    R += cnt[s];
+  }
+  for (int s = NC; s < nseg; s++) R += before(s);
   p.si0[hd + R] = (uint32_t)j;  // rank order of the whole document
   int e = b;
   if (R >= p.k) {
     uint32_t kk = (uint32_t)p.k - 1u;
     for (int s = 0; s < nseg; s++) {
-      const uint32_t c = (uint32_t)before(s);
+      int cs = 0;
+#pragma unroll
+      for (int q = 0; q < NC; q++) cs = s == q ? cnt[q] : cs;
+      const uint32_t c = (uint32_t)(s < NC ? cs : before(s));
       if (kk < c) {
         const int ns = min(SEG, n - s * SEG);
         const int val = (int)wavelet_kth(p, h, seg_slot(a, d, s), seg_woff(a, d, s), dev_ceil_log2(ns), c, kk);
