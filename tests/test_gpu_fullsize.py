@@ -332,3 +332,16 @@ def test_documents_of_several_segments_next_to_short_ones(gpu, causal):
                 pr = np.exp(s - s.max()); pr /= pr.sum()
                 check_close("O last row", O[i, h], pr @ inp.V[kept, 0].astype(np.float64), **T_BF16)
     assert np.isfinite(case.host("O")).all()
+
+
+def test_document_of_ten_segments(gpu):
+    """More segments than the merge kernel keeps counts for in registers (8): one 150000-token document."""
+    print("[case] 150000-token document (10 segments), expiry exhaustive, sampled rows", flush=True)
+    wl = wlmod.Workload("tenseg", 1008, H_q=2, H_kv=1, d=64, k=1000, seqlens=(150000,), backward=False)
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen(); case.fwd()
+    zg, eg = check_expiry_all(case, "tenseg")
+    rows = sample_rows(np.random.default_rng(10), inp, [0, 1], 5)
+    check_rows(case, zg, rows, "tenseg", backward=False)
+    assert np.isfinite(case.host("O")).all()
