@@ -12,7 +12,8 @@ constexpr int BQ = 256;        // query rows per block (one workgroup of the que
 constexpr int KT = 64;         // keys per tile of the query-stationary kernels
 constexpr int MAXPART = 2 * BQ;  // a block has at most BQ entering + BQ expiring keys
 constexpr int SG = 128;        // slot columns per workgroup of the key-stationary backward
-constexpr int SEG = 16384;     // keys per segment of the selection (what one workgroup sorts in LDS)
+constexpr int SEG_MIN = 4096;  // keys per segment of the selection (what one workgroup sorts in LDS): 4096 when
+constexpr int SEG_MAX = 16384; // no document is longer than four such segments (more workgroups), else 16384
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -28,9 +29,10 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 struct PlanLayout {
   int nblk_cap;    // upper bound on the number of query blocks: T / BQ + n_docs
   int kpad;        // slot-table row length: min(k, T) rounded up to SG
-  int nbits_cap;   // wavelet levels of a segment (at most log2 SEG)
+  int seg;         // segment length chosen for this shape
+  int nbits_cap;   // wavelet levels of a segment (at most log2 SEG_MAX)
   int wcap;        // 64-bit words per wavelet level per head (every segment has two spare words)
-  int nseg_cap;    // upper bound on the number of segments: T / SEG + n_docs + 1
+  int nseg_cap;    // upper bound on the number of segments: T / seg + n_docs + 1
   size_t off_hdr;      // int32[16]: [0] number of blocks
   size_t off_consts;   // 512 B: [0,256) zeros (a dummy K/V row); then float -inf, int32 0, int32 -1, float +inf
   size_t off_zq;       // float[H_q][T]: z / softmax_scale, the bias as the start value of a Q K^T accumulator
@@ -63,9 +65,13 @@ static inline PlanLayout plan_layout(const dma_shape& s) {
   p.nblk_cap = s.T / BQ + s.n_docs;
   int kk = s.k < s.T ? s.k : s.T;
   p.kpad = (kk + SG - 1) / SG * SG;
-  p.nbits_cap = ceil_log2(s.T < 2 ? 2 : (s.T < SEG ? s.T : SEG));
-  p.nseg_cap = s.T / SEG + s.n_docs + 1;
-  p.wcap = s.T / 64 + 2 * (s.T / SEG) + 5 * s.n_docs + SEG / 64 + 8;
+  {
+    const int longest = s.max_seqlen > 0 && s.max_seqlen < s.T ? s.max_seqlen : s.T;
+    p.seg = longest <= 4 * SEG_MIN ? SEG_MIN : SEG_MAX;  // (any choice is correct; this one is a matter of speed)
+  }
+  p.nbits_cap = ceil_log2(s.T < 2 ? 2 : (s.T < p.seg ? s.T : p.seg));
+  p.nseg_cap = s.T / p.seg + s.n_docs + 1;
+  p.wcap = s.T / 64 + 2 * (s.T / p.seg) + 5 * s.n_docs + p.seg / 64 + 8;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
   p.off_hdr = take(64);

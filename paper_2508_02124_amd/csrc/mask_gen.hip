@@ -145,14 +145,16 @@ struct SortArgs {
   unsigned long long* wbits;
   uint32_t* wcnt;
   uint32_t* wzero;
-  int T, n_docs, k, nbits_cap, wcap, nseg_cap;
+  int T, n_docs, k, nbits_cap, wcap, nseg_cap, seg;
 };
 
-// Documents are handled in segments of SEG consecutive keys (one for most documents).  Segment p of
-// document d (first token a) has the slot number a / SEG + d + p, unique and increasing over the
-// batch, and its wavelet levels start at word seg_woff of each level's row.
-__device__ __forceinline__ int seg_slot(int a, int d, int p) { return a / SEG + d + p; }
-__device__ __forceinline__ int seg_woff(int a, int d, int p) { return a / 64 + 2 * (a / SEG) + 5 * d + p * (SEG / 64 + 2); }
+// Documents are handled in segments of `seg` consecutive keys (4096 or 16384, one launch-wide
+// choice).  Segment p of document d (first token a) has the slot number a / seg + d + p, unique and
+// increasing over the batch, and its wavelet levels start at word seg_woff of each level's row.
+__device__ __forceinline__ int seg_slot(int seg, int a, int d, int p) { return a / seg + d + p; }
+__device__ __forceinline__ int seg_woff(int seg, int a, int d, int p) {
+  return a / 64 + 2 * (a / seg) + 5 * d + p * (seg / 64 + 2);
+}
 
 // One workgroup (16 waves) per (segment, head).  The segment's keys are sorted by (score descending,
 // index ascending) -- a stable LSD radix sort on 8-bit digits, entirely in registers and LDS: every
@@ -163,7 +165,9 @@ __device__ __forceinline__ int seg_woff(int a, int d, int p) { return a / 64 + 2
 // partitioned, zeros first, for the next level).  A document of one segment leaves its rank order in
 // si0 for expiry_kernel; the segments of a longer document leave their sorted keys and local
 // indices in sk1 / si1 for merge_expiry_kernel.
+template <int NB>  // chunks of 64 keys per wave: a segment is 16 waves x NB chunks = 1024 NB keys
 __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
+  constexpr int SEG = 1024 * NB;
   const int slot = blockIdx.x, h = blockIdx.y;
   // the document whose segment range [seg_slot(a, d, 0), seg_slot(a, d, nseg)) holds this slot
   int d = 0;
@@ -171,12 +175,12 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
     int lo = 0, hi = p.n_docs;  // answer in [lo, hi): largest d with seg_slot(cu[d], d, 0) <= slot
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if (seg_slot(p.cu[mid], mid, 0) <= slot) lo = mid; else hi = mid;
+      if (seg_slot(SEG, p.cu[mid], mid, 0) <= slot) lo = mid; else hi = mid;
     }
     d = lo;
   }
   const int a = p.cu[d], b = p.cu[d + 1], ndoc = b - a;
-  const int ps = slot - seg_slot(a, d, 0), nseg = (ndoc + SEG - 1) / SEG;
+  const int ps = slot - seg_slot(SEG, a, d, 0), nseg = (ndoc + SEG - 1) / SEG;
   if (ndoc <= 0 || ps >= nseg) return;
   const int n = min(SEG, ndoc - ps * SEG);  // keys of this segment
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
@@ -190,9 +194,7 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
   const int nchunks = (n + 63) / 64, cpw = (nchunks + 15) / 16;
   const int c_begin = w * cpw;
   const unsigned long long lt = (1ull << l) - 1ull;
-  constexpr int NB = 16;           // chunks per wave: 16 waves x 16 chunks x 64 keys = SEG
   constexpr int LDS_N = SEG;
-  static_assert(16 * NB * 64 == SEG, "a segment is what one workgroup holds in registers");
   {
     // ---- whole segment in registers (16 elements per thread, chunk c of a wave = elements
     // 64c + lane) and LDS: every pass scatters from registers into LDS and reads its chunks back.
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(1024) void sort_wavelet_kernel(SortArgs p) {
     // wavelet matrix over ii (see below), partitioned through LDS; the level tables are collected
     // in the (now free) key buffer and written out once at the end, so no level waits on a store
     const int nbits = dev_ceil_log2(n);
-    const int woff = seg_woff(a, d, ps);
+    const int woff = seg_woff(SEG, a, d, ps);
     const int lrow = nchunks + 1;  // entries per level
     unsigned long long* lwb = reinterpret_cast<unsigned long long*>(lk);  // [nbits][lrow]
     uint32_t* lwc = lk + 2 * 14 * (LDS_N / 64 + 1);                        // [nbits][lrow]
@@ -378,12 +380,12 @@ __global__ __launch_bounds__(256) void expiry_kernel(SortArgs p) {
   if (t >= p.T) return;
   const int d = find_doc(p.cu, p.n_docs, t);
   const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
-  if (n <= p.k || n > SEG) return;
+  if (n <= p.k || n > p.seg) return;
   const int r = t - a;
   const int j = (int)p.si0[(size_t)h * p.T + t];
   int e = b;
   if (r >= p.k)
-    e = a + max(j, (int)wavelet_kth(p, h, seg_slot(a, d, 0), seg_woff(a, d, 0), dev_ceil_log2(n), (uint32_t)r,
+    e = a + max(j, (int)wavelet_kth(p, h, seg_slot(p.seg, a, d, 0), seg_woff(p.seg, a, d, 0), dev_ceil_log2(n), (uint32_t)r,
                                     (uint32_t)p.k - 1u));
   p.expiry[(size_t)h * p.T + a + j] = e;
 }
@@ -399,6 +401,7 @@ __global__ __launch_bounds__(256) void merge_expiry_kernel(SortArgs p) {
   if (t >= p.T) return;
   const int d = find_doc(p.cu, p.n_docs, t);
   const int a = p.cu[d], b = p.cu[d + 1], n = b - a;
+  const int SEG = p.seg;
   if (n <= p.k || n <= SEG) return;
   const int nseg = (n + SEG - 1) / SEG;
   const int ps = (t - a) / SEG, r = (t - a) - ps * SEG;
@@ -437,7 +440,7 @@ __global__ __launch_bounds__(256) void merge_expiry_kernel(SortArgs p) {
       const uint32_t c = (uint32_t)(s < NC ? cs : before(s));
       if (kk < c) {
         const int ns = min(SEG, n - s * SEG);
-        const int val = (int)wavelet_kth(p, h, seg_slot(a, d, s), seg_woff(a, d, s), dev_ceil_log2(ns), c, kk);
+        const int val = (int)wavelet_kth(p, h, seg_slot(SEG, a, d, s), seg_woff(SEG, a, d, s), dev_ceil_log2(ns), c, kk);
         e = a + max(j, s * SEG + val);
         break;
       }
@@ -669,9 +672,10 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   sa.wcnt = (uint32_t*)(base + L.off_wcnt);
   sa.wzero = (uint32_t*)(base + L.off_wzero);
   sa.T = s.T; sa.n_docs = s.n_docs; sa.k = s.k; sa.nbits_cap = L.nbits_cap; sa.wcap = L.wcap;
-  sa.nseg_cap = L.nseg_cap;
+  sa.nseg_cap = L.nseg_cap; sa.seg = L.seg;
   prof_begin(DMA_STAGE_SORT, st);
-  sort_wavelet_kernel<<<dim3(L.nseg_cap, s.H_q), 1024, 0, st>>>(sa);
+  if (L.seg == SEG_MIN) sort_wavelet_kernel<SEG_MIN / 1024><<<dim3(L.nseg_cap, s.H_q), 1024, 0, st>>>(sa);
+  else sort_wavelet_kernel<SEG_MAX / 1024><<<dim3(L.nseg_cap, s.H_q), 1024, 0, st>>>(sa);
   prof_end(DMA_STAGE_SORT, st);
   const auto fill = [&](int32_t* dst, size_t n, int32_t v) {
     size_t grid = (n + 2047) / 2048;
@@ -687,13 +691,13 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
     fill(pcnt, (size_t)s.H_q * L.nblk_cap, 0);
     // (documents of several segments get their whole-document rank order from the merge kernel; the
     // causal expiry it also writes is overwritten below)
-    if (s.T > SEG) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    if (s.T > L.seg) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     noncausal_plan_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, sa.si0, docblk, expiry, slot_tab,
                                                                         s.T, s.k, L.nblk_cap, L.kpad);
   } else {
     prof_begin(DMA_STAGE_EXPIRY, st);
     expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
-    if (s.T > SEG) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    if (s.T > L.seg) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     prof_end(DMA_STAGE_EXPIRY, st);
     prof_begin(DMA_STAGE_PLAN, st);
     slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
