@@ -293,12 +293,14 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   __shared__ __align__(16) float stage_all[8 * 32 * LDS_ST];  // per wave: [32 columns][32 channels] fp32, flush staging
   __shared__ __align__(16) f32x4 pbuf[2][4][4][64];  // P hand-off (fp32): [step parity][column block][row group][lane]
 
-  // item = chunk * ngrp + group: the groups of one (head, chunk) run side by side and share Q / dO
   const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
   const int nchunk = (p.nblk_cap + (PARTIAL ? p.seg_part : p.seg) - 1) / (PARTIAL ? p.seg_part : p.seg);
   int h, item;
   if (!xcd_map(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
-  const int chunk = item / ngrp, grp = item - chunk * ngrp;
+  // Clean mode: the groups of a chunk are neighbours.  Partial mode: group-major, because the high
+  // groups of most chunks are empty and workgroups go to the shader engines in turn: with the
+  // groups as the fast index all the work would land on the engines that get groups 0 and 1.
+  const int chunk = PARTIAL ? item % nchunk : item / ngrp, grp = PARTIAL ? item / nchunk : item - chunk * ngrp;
   const int g = h / (p.H_q / p.H_kv);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int kb4 = w & 3, role = w >> 2;
