@@ -157,7 +157,7 @@ def main():
         del src, dst
 
     # Stage events are recorded inside the timed region, on every fourth step (each armed step
-    # records 20 events between the launches, which costs 0.05-0.15 ms of its 3.9 ms at the headline
+    # records 20 events between the launches, which costs 0.05-0.15 ms of its 3.5 ms at the headline
     # shape; the kernels' durations do not depend on it).
     nst = len(B.STAGES)
     armed = [i for i in range(args.steps) if i % 4 == 0]
@@ -240,7 +240,7 @@ def main():
         best = min(best, ev2[0].elapsed_time(ev2[1]))
     copy_measured = 2.0 * cbytes / (best * 1e-3) / 1e9
     del csrc, cdst, sink
-    device = {"name": prop.name, "compute_units": int(prop.multi_processor_count),
+    device = {"name": prop.name or getattr(prop, "gcnArchName", ""), "compute_units": int(prop.multi_processor_count),
               "mfma_bf16_measured_tflops": mfma_measured, "stream_copy_measured_GB/s": copy_measured}
     out = {
         "metric": "dma_mask_fwd_bwd_effective_tflops" if wl.backward else "dma_mask_fwd_effective_tflops",
