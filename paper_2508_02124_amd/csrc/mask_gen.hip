@@ -487,7 +487,7 @@ __global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ 
       int moved = 0;
       for (int j = tid; j < n; j += 1024) {
         const int q = ls[j];
-        if (q >= k) {
+        if (q >= k && q != j) {  // (q == j: a key that never enters; nothing points at it)
           ls[j] = ls[q];
           moved = 1;
         }
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(1024) void slot_kernel(const int32_t* __restrict__ 
     int moved = 0;
     for (int j = tid; j < n; j += 1024) {
       const int q = sid[j];
-      if (q >= k) {
+      if (q >= k && q != j) {
         sid[j] = sid[q];
         moved = 1;
       }
