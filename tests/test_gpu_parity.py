@@ -195,11 +195,13 @@ def test_backward_heavy_ties(gpu):
 
 # ----------------------------------------------------------------------------- gradient of the content scores
 MASK_BWD_CASES = {
-    # name: (T, H_q, H_kv, d)  -- several 64-token tiles with a ragged tail, G = 1, 2, 4, 8
+    # name: (T, H_q, H_kv, d)  -- several 64-token tiles with a ragged tail, G = 1, 2, 4, 8, 16
     "tail_d64": (333, 4, 2, 64),
     "g1_d128": (200, 3, 3, 128),
     "g8_d128": (1000, 8, 1, 128),
     "tiny": (5, 2, 1, 64),
+    "g16_d64": (300, 16, 1, 64),          # more than 8 q-heads per kv-head: the LDS-based kernel
+    "many_tiles_d128": (70000, 4, 1, 128),  # several tiles per workgroup
 }
 
 
