@@ -548,50 +548,59 @@ __global__ __launch_bounds__(256) void slot_table_kernel(const int32_t* __restri
   }
 }
 
-// The same table, row by row, for windows of up to SLOT_TILE columns.  One workgroup per (chunk of
-// consecutive blocks, head) keeps in LDS, per slot, the latest key of the slot's chain among the keys
+// The same table, row by row, in tiles of SLOT_TILE columns.  One workgroup per (chunk of
+// consecutive blocks, head, column tile) keeps in LDS, per slot, the latest key of the slot's chain among the keys
 // before the current block, with its expiry; a block's row is then one coalesced pass (the key if
 // it outlives the block, else -1; nothing is left for a fill launch), after which the block's own
 // keys are taken in.  The state at the chunk's first block comes from one scan of the document's
-// earlier keys (exactly one key per chain is still kept at a given row).  The scattered 4-byte
+// earlier keys (exactly one key per chain is still kept at a given row; every column tile repeats
+// the scan, so this kernel serves windows of up to SLOT_TILES_MAX tiles).  The scattered 4-byte
 // stores of the kernel above cost a 64-byte write each; these rows are written whole.
 constexpr int SLOT_TILE = 4096;
+constexpr int SLOT_TILES_MAX = 4;
 __global__ __launch_bounds__(512) void slot_rows_kernel(const int4* __restrict__ blk, const int32_t* __restrict__ expiry,
                                                         const int32_t* __restrict__ slotid, int32_t* slot_tab, int T,
                                                         int nblk_cap, int kpad, int blocks_per_chunk) {
   __shared__ unsigned long long cur[SLOT_TILE];  // (key + 1) << 32 | expiry; 0 = no key yet
   const int h = blockIdx.y, tid = threadIdx.x;
+  const int c0 = blockIdx.z * SLOT_TILE, nc = min(SLOT_TILE, kpad - c0);  // this workgroup's columns
   const int b_begin = blockIdx.x * blocks_per_chunk, b_end = min(b_begin + blocks_per_chunk, nblk_cap);
   const int32_t* ex = expiry + (size_t)h * T;
   const int32_t* sid = slotid + (size_t)h * T;
   int doc = -1;
   for (int b = b_begin; b < b_end; b++) {
     const int4 info = blk[b];  // (the same for every thread: the branches below are uniform)
-    int32_t* row = slot_tab + ((size_t)h * nblk_cap + b) * kpad;
+    int32_t* row = slot_tab + ((size_t)h * nblk_cap + b) * kpad + c0;
     if (info.x < 0) {
-      for (int c = tid; c < kpad; c += 512) row[c] = -1;
+      for (int c = tid; c < nc; c += 512) row[c] = -1;
       continue;
     }
     const int lo = info.y, hi = info.z - 1, a = info.w;  // causal plan: w = first row of the document
     if (info.x != doc) {
       doc = info.x;
       __syncthreads();
-      for (int c = tid; c < kpad; c += 512) cur[c] = 0ull;
+      for (int c = tid; c < nc; c += 512) cur[c] = 0ull;
       __syncthreads();
       for (int j = a + tid; j < lo; j += 512) {
         const int e = ex[j];
-        if (e > j && e >= lo) cur[sid[j]] = ((unsigned long long)(unsigned)(j + 1) << 32) | (unsigned)e;
+        if (e > j && e >= lo) {
+          const int c = sid[j] - c0;
+          if (c >= 0 && c < nc) cur[c] = ((unsigned long long)(unsigned)(j + 1) << 32) | (unsigned)e;
+        }
       }
       __syncthreads();
     }
-    for (int c = tid; c < kpad; c += 512) {
+    for (int c = tid; c < nc; c += 512) {
       const unsigned long long v = cur[c];
       row[c] = (v != 0ull && (int)(unsigned)v > hi) ? (int)(v >> 32) - 1 : -1;
     }
     __syncthreads();
     for (int j = lo + tid; j <= hi; j += 512) {
       const int e = ex[j];
-      if (e > j) atomicMax(&cur[sid[j]], ((unsigned long long)(unsigned)(j + 1) << 32) | (unsigned)e);
+      if (e > j) {
+        const int c = sid[j] - c0;
+        if (c >= 0 && c < nc) atomicMax(&cur[c], ((unsigned long long)(unsigned)(j + 1) << 32) | (unsigned)e);
+      }
     }
     __syncthreads();
   }
@@ -750,9 +759,9 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
     prof_end(DMA_STAGE_EXPIRY, st);
     prof_begin(DMA_STAGE_PLAN, st);
     slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);
-    if (L.kpad <= SLOT_TILE) {
+    if (L.kpad <= SLOT_TILES_MAX * SLOT_TILE) {
       const int per = L.nblk_cap / 16 > 4 ? L.nblk_cap / 16 : 4;  // about 16 chunks per head
-      slot_rows_kernel<<<dim3((L.nblk_cap + per - 1) / per, s.H_q), 512, 0, st>>>(blk, expiry, slotid, slot_tab, s.T,
+      slot_rows_kernel<<<dim3((L.nblk_cap + per - 1) / per, s.H_q, (L.kpad + SLOT_TILE - 1) / SLOT_TILE), 512, 0, st>>>(blk, expiry, slotid, slot_tab, s.T,
                                                                                L.nblk_cap, L.kpad, per);
     } else {
       fill(slot_tab, (size_t)s.H_q * L.nblk_cap * L.kpad, -1);

@@ -97,6 +97,16 @@ def check_mask(case: DeviceCase, label):
     return n_sel_diff
 
 
+def test_plan_window_wider_than_one_column_tile(gpu):
+    """k = 5000: the slot table is written in two column tiles (4096 + 1024 columns)."""
+    print("[case] plan wide window", flush=True)
+    wl = wlmod.small_workload("wide_window", 24, 2, 1, 64, 5000, (7000, 300, 5300))
+    inp = wlmod.make_inputs(wl)
+    case = DeviceCase(inp, gpu)
+    case.mask_gen()
+    print("  selection differences vs fp64 scores:", check_mask(case, "wide_window"), flush=True)
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_mask_gen_and_forward_small(gpu, name, dtype):
