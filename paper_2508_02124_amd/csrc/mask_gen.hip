@@ -56,46 +56,65 @@ __global__ void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 
 // ------------------------------------------------------------------ content scores (Eq. 3)
 // One workgroup per (64 tokens, kv-head): each value row is read once and scored for all q-heads
-// of its group.  z = exp(A * softplus(w . v)) in fp32.
-template <typename TV, int D>
+// of its group.  z = exp(A * softplus(w . v)) in fp32; z / softmax_scale is written next to it
+// (the attention kernels start their Q K^T accumulators at it).  A row is held by D / 8 lanes; the
+// loads of the tile's rows are all in flight before the first dot product, and a group of up to
+// GMAX q-heads keeps this lane's 8 weights of every head in registers.
+template <typename TV, int D, int GMAX>
 __global__ __launch_bounds__(256) void z_kernel(const TV* __restrict__ V, const float* __restrict__ W,
                                                 const float* __restrict__ A, float* __restrict__ z,
-                                                int T, int H_q, int H_kv) {
+                                                float* __restrict__ zq, float inv_scale, int T, int H_q, int H_kv) {
   extern __shared__ float zs[];  // [G][64]
   constexpr int LPR = D / 8;     // lanes per value row (8 elements per lane)
   constexpr int RPP = 256 / LPR; // rows per pass
+  constexpr int NP = 64 / RPP;
   const int g = blockIdx.y, G = H_q / H_kv, t0 = blockIdx.x * 64;
   const int tid = threadIdx.x, sub = tid % LPR, rl = tid / LPR;
-  for (int pass = 0; pass < 64 / RPP; pass++) {
-    const int r = pass * RPP + rl, t = t0 + r;
-    float v[8];
+  float v[NP][8];
 #pragma unroll
-    for (int e = 0; e < 8; e++) v[e] = 0.f;
+  for (int pass = 0; pass < NP; pass++) {
+    const int t = t0 + pass * RPP + rl;
+#pragma unroll
+    for (int e = 0; e < 8; e++) v[pass][e] = 0.f;
     if (t < T) {
       const TV* src = V + ((size_t)t * H_kv + g) * D + 8 * sub;
       if constexpr (sizeof(TV) == 2) {
-        uint4 raw = *reinterpret_cast<const uint4*>(src);
-        uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+        const uint4 raw = *reinterpret_cast<const uint4*>(src);
+        const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-          v[2 * e] = __uint_as_float(u[e] << 16);
-          v[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+          v[pass][2 * e] = __uint_as_float(u[e] << 16);
+          v[pass][2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
         }
       } else {
-        float4 x0 = *reinterpret_cast<const float4*>(src);
-        float4 x1 = *reinterpret_cast<const float4*>(src + 4);
-        v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
-        v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+        const float4 x0 = *reinterpret_cast<const float4*>(src);
+        const float4 x1 = *reinterpret_cast<const float4*>(src + 4);
+        v[pass][0] = x0.x; v[pass][1] = x0.y; v[pass][2] = x0.z; v[pass][3] = x0.w;
+        v[pass][4] = x1.x; v[pass][5] = x1.y; v[pass][6] = x1.z; v[pass][7] = x1.w;
       }
     }
-    for (int hh = 0; hh < G; hh++) {
-      const float* w = W + (size_t)(g * G + hh) * D + 8 * sub;
-      float acc = 0.f;
+  }
+  for (int h0 = 0; h0 < G; h0 += GMAX) {  // (one trip unless the group has more than GMAX q-heads)
+    float wreg[GMAX][8];
 #pragma unroll
-      for (int e = 0; e < 8; e++) acc = fmaf(v[e], w[e], acc);
+    for (int hh = 0; hh < GMAX; hh++) {
+      const float4* w4 = reinterpret_cast<const float4*>(W + (size_t)(g * G + min(h0 + hh, G - 1)) * D + 8 * sub);
+      const float4 a = w4[0], b = w4[1];
+      wreg[hh][0] = a.x; wreg[hh][1] = a.y; wreg[hh][2] = a.z; wreg[hh][3] = a.w;
+      wreg[hh][4] = b.x; wreg[hh][5] = b.y; wreg[hh][6] = b.z; wreg[hh][7] = b.w;
+    }
 #pragma unroll
-      for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-      if (sub == 0) zs[hh * 64 + r] = acc;
+    for (int pass = 0; pass < NP; pass++) {
+      const int r = pass * RPP + rl;
+#pragma unroll
+      for (int hh = 0; hh < GMAX; hh++) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc = fmaf(v[pass][e], wreg[hh][e], acc);
+#pragma unroll
+        for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+        if (sub == 0 && h0 + hh < G) zs[(h0 + hh) * 64 + r] = acc;
+      }
     }
   }
   __syncthreads();
@@ -104,7 +123,10 @@ __global__ __launch_bounds__(256) void z_kernel(const TV* __restrict__ V, const 
     if (t < T) {
       const float x = zs[idx];
       const float sp = fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
-      z[(size_t)(g * G + hh) * T + t] = expf(A[g * G + hh] * sp);
+      const float zv = expf(A[g * G + hh] * sp);
+      const size_t o = (size_t)(g * G + hh) * T + t;
+      z[o] = zv;
+      zq[o] = zv * inv_scale;
     }
   }
 }
@@ -702,24 +724,30 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
 
   prof_begin(DMA_STAGE_Z, st);
   blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, s.k, s.causal, blk, docblk, hdr);
+  float* zq = (float*)(base + L.off_zq);
+  const float inv_scale = 1.0f / p.scale;
   if (W) {
     const int G = s.H_q / s.H_kv;
     dim3 grid((s.T + 63) / 64, s.H_kv);
     const size_t sh = (size_t)G * 64 * sizeof(float);
+#define DMA_Z(TV, DD, GM) \
+  z_kernel<TV, DD, GM><<<grid, 256, sh, st>>>((const TV*)V, W, A, z, zq, inv_scale, s.T, s.H_q, s.H_kv)
     if (s.dtype == DMA_BF16) {
-      if (s.d == 128) z_kernel<uint16_t, 128><<<grid, 256, sh, st>>>((const uint16_t*)V, W, A, z, s.T, s.H_q, s.H_kv);
-      else z_kernel<uint16_t, 64><<<grid, 256, sh, st>>>((const uint16_t*)V, W, A, z, s.T, s.H_q, s.H_kv);
+      if (s.d == 128) { if (G <= 4) DMA_Z(uint16_t, 128, 4); else DMA_Z(uint16_t, 128, 8); }
+      else { if (G <= 4) DMA_Z(uint16_t, 64, 4); else DMA_Z(uint16_t, 64, 8); }
     } else {
-      if (s.d == 128) z_kernel<float, 128><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
-      else z_kernel<float, 64><<<grid, 256, sh, st>>>((const float*)V, W, A, z, s.T, s.H_q, s.H_kv);
+      if (s.d == 128) { if (G <= 4) DMA_Z(float, 128, 4); else DMA_Z(float, 128, 8); }
+      else { if (G <= 4) DMA_Z(float, 64, 4); else DMA_Z(float, 64, 8); }
     }
+#undef DMA_Z
   }
   {
-    const size_t n = (size_t)s.H_q * s.T;
+    // caller-supplied scores: z / softmax_scale here; always: the plan's constant block
+    const size_t n = W ? 0 : (size_t)s.H_q * s.T;
     size_t grid = (n + 1023) / 1024;
     if (grid > (1u << 20)) grid = 1u << 20;
-    zq_consts_kernel<<<(unsigned)grid, 256, 0, st>>>(z, (float*)(base + L.off_zq), 1.0f / p.scale, n,
-                                                     (uint32_t*)(base + L.off_consts));
+    if (grid < 1) grid = 1;
+    zq_consts_kernel<<<(unsigned)grid, 256, 0, st>>>(z, zq, inv_scale, n, (uint32_t*)(base + L.off_consts));
   }
   prof_end(DMA_STAGE_Z, st);
   SortArgs sa;
