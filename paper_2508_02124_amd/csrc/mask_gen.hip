@@ -39,11 +39,14 @@ __global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int n
     s_total = acc;
   }
   __syncthreads();
-  for (int d = threadIdx.x; d < n_docs; d += blockDim.x) {
-    int a = cu[d], b = cu[d + 1];
-    int b0 = docblk[d];
-    for (int r = a, i = 0; r < b; r += BQ, i++)
-      blk[b0 + i] = make_int4(d, r, min(r + BQ, b), causal ? a : r - min(k, b - a));
+  for (int i = threadIdx.x; i < s_total; i += blockDim.x) {  // one block per thread
+    int lo = 0, hi = n_docs;  // its document: the last d with docblk[d] <= i (empty documents own no block)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (docblk[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int a = cu[lo], b = cu[lo + 1], r = a + (i - docblk[lo]) * BQ;
+    blk[i] = make_int4(lo, r, min(r + BQ, b), causal ? a : r - min(k, b - a));
   }
   for (int i = s_total + threadIdx.x; i < nblk_cap; i += blockDim.x) blk[i] = make_int4(-1, 0, 0, 0);
 }
