@@ -785,7 +785,8 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
                                                                         s.T, s.k, L.nblk_cap, L.kpad);
   } else {
     prof_begin(DMA_STAGE_EXPIRY, st);
-    expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    // (documents of one segment / of several segments; a single document is one or the other)
+    if (s.n_docs > 1 || s.T <= L.seg) expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     if (s.T > L.seg) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     prof_end(DMA_STAGE_EXPIRY, st);
     prof_begin(DMA_STAGE_PLAN, st);
