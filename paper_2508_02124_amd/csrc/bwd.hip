@@ -39,6 +39,8 @@ struct BwdArgs {
   int seg;       // query blocks swept by one clean-mode work item of dkv_kernel
   int seg_part;  // ... by one partial-mode work item
   float scale, c2;
+  size_t zero_n4;  // float4 elements from dK32 to the end of dV32 (cleared by dq_kernel)
+  size_t dz_n;     // elements of dz (cleared by dq_kernel)
 };
 
 // ------------------------------------------------------------------ dQ (and D, LSE * log2 e)
@@ -53,6 +55,15 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   __shared__ __align__(16) float z_ring[NS][KT];
   __shared__ __align__(16) int e_ring[NS][KT];
 
+  // This launch also clears what the key-stationary launches behind it accumulate into with atomics
+  // (the fp32 dK / dV buffers and dz): every workgroup, also one without a block, takes its share of
+  // the stores; this kernel is bound by the matrix cores, so they cost no time here.
+  {
+    const size_t nth = (size_t)gridDim.x * 512, gid = (size_t)blockIdx.x * 512 + threadIdx.x;
+    float4* acc4 = reinterpret_cast<float4*>(p.dK32);
+    for (size_t i = gid; i < p.zero_n4; i += nth) acc4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (size_t i = gid; i < p.dz_n; i += nth) p.dz[i] = 0.f;
+  }
   int h, item;
   if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
   const int bi = p.nblk_cap - 1 - item;  // long blocks first
@@ -629,12 +640,6 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   flush(true);
 }
 
-__global__ void fill_f32_kernel(float* p, size_t n, float v) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  const size_t st = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += st) p[i] = v;
-}
-
 // dK, dV: fp32 accumulators -> bf16 outputs
 __global__ void cvt_bf16_kernel(const float* __restrict__ a, const float* __restrict__ b, uint16_t* __restrict__ oa,
                                 uint16_t* __restrict__ ob, size_t n4) {
@@ -689,9 +694,9 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   }
 
   const size_t nkv = (size_t)s.T * s.H_kv * s.d;
-  prof_begin(DMA_STAGE_BWD_ZERO, st);
-  fill_f32_kernel<<<grid_for(2 * nkv, 2048), 256, 0, st>>>(a.dK32, (wl.off_dV - wl.off_dK) / 4 + nkv, 0.f);
-  fill_f32_kernel<<<grid_for((size_t)s.H_q * s.T, 2048), 256, 0, st>>>(dz, (size_t)s.H_q * s.T, 0.f);
+  a.zero_n4 = ((wl.off_dV - wl.off_dK) / 4 + nkv + 3) / 4;  // (the layout pads both buffers to 256 bytes)
+  a.dz_n = (size_t)s.H_q * s.T;
+  prof_begin(DMA_STAGE_BWD_ZERO, st);  // (no launch of its own any more: dq_kernel clears the accumulators)
   prof_end(DMA_STAGE_BWD_ZERO, st);
   const unsigned gq = xcd_grid(s.H_q, L.nblk_cap);
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
