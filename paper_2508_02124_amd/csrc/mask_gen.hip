@@ -20,13 +20,26 @@
 
 namespace dma {
 
+// The plan's constant block: a zero K/V row for empty slots, then the -inf / 0 / -1 / +inf scalars
+// the asynchronous copies point at for empty ids (words 64, 65, 66, 67).
+__device__ __forceinline__ void plan_consts(uint32_t* consts, size_t i) {
+  if (i < 128) {
+    uint32_t v = 0u;
+    if (i == 64) v = 0xff800000u;       // float -inf
+    if (i == 66) v = 0xffffffffu;       // int -1
+    if (i == 67) v = 0x7f800000u;       // float +inf
+    consts[i] = v;
+  }
+}
+
 // ------------------------------------------------------------------ block table
 // blk[i] = {document, first row, end row, w}: the attention kernels take min(k, first row - w) as the
 // number of resident slot columns of the block.  Causal: w = first row of the document (the keys
 // before the block); otherwise every block of a document has min(k, n) columns.
 __global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int nblk_cap, int k, int causal, int4* blk,
-                               int32_t* docblk, int32_t* hdr) {
+                               int32_t* docblk, int32_t* hdr, uint32_t* consts) {
   __shared__ int s_total;
+  plan_consts(consts, threadIdx.x);
   if (threadIdx.x == 0) {
     int acc = 0;
     for (int d = 0; d < n_docs; d++) {
@@ -134,20 +147,12 @@ __global__ __launch_bounds__(256) void z_kernel(const TV* __restrict__ V, const 
   }
 }
 
-// zq = z / softmax_scale (the attention kernels start their Q K^T accumulators at it, so that
-// scale * accumulator is the biased score), plus the plan's constant block: a zero K/V row for
-// empty slots, -inf / 0 / -1 scalars the asynchronous copies point at for empty ids.
-__global__ __launch_bounds__(256) void zq_consts_kernel(const float* __restrict__ z, float* __restrict__ zq,
-                                                        float inv_scale, size_t n, uint32_t* consts) {
+// zq = z / softmax_scale for scores supplied by the caller (the attention kernels start their
+// Q K^T accumulators at it, so that scale * accumulator is the biased score).
+__global__ __launch_bounds__(256) void zq_kernel(const float* __restrict__ z, float* __restrict__ zq,
+                                                 float inv_scale, size_t n) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   const size_t st = (size_t)gridDim.x * blockDim.x;
-  if (i < 128) {
-    uint32_t v = 0u;
-    if (i == 64) v = 0xff800000u;       // float -inf
-    if (i == 66) v = 0xffffffffu;       // int -1
-    if (i == 67) v = 0x7f800000u;       // float +inf
-    consts[i] = v;
-  }
   for (; i < n; i += st) zq[i] = z[i] * inv_scale;
 }
 
@@ -726,7 +731,8 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
   int32_t* slotid = (int32_t*)(base + L.off_slotid);
 
   prof_begin(DMA_STAGE_Z, st);
-  blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, s.k, s.causal, blk, docblk, hdr);
+  blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, s.k, s.causal, blk, docblk, hdr,
+                                   (uint32_t*)(base + L.off_consts));
   float* zq = (float*)(base + L.off_zq);
   const float inv_scale = 1.0f / p.scale;
   if (W) {
@@ -744,13 +750,11 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
     }
 #undef DMA_Z
   }
-  {
-    // caller-supplied scores: z / softmax_scale here; always: the plan's constant block
-    const size_t n = W ? 0 : (size_t)s.H_q * s.T;
+  if (!W) {  // caller-supplied scores: only z / softmax_scale is left to do
+    const size_t n = (size_t)s.H_q * s.T;
     size_t grid = (n + 1023) / 1024;
     if (grid > (1u << 20)) grid = 1u << 20;
-    if (grid < 1) grid = 1;
-    zq_consts_kernel<<<(unsigned)grid, 256, 0, st>>>(z, zq, inv_scale, n, (uint32_t*)(base + L.off_consts));
+    zq_kernel<<<(unsigned)grid, 256, 0, st>>>(z, zq, inv_scale, n);
   }
   prof_end(DMA_STAGE_Z, st);
   SortArgs sa;
