@@ -35,8 +35,11 @@ struct FwdArgs {
 
 constexpr float MSLACK = 8.f;  // log2 slack of the lazily updated softmax reference maximum
 
+// (second launch bound = waves per SIMD: at D = 64 the kernel is held to 128 registers so that two
+// workgroups share a compute unit -- four waves per SIMD hide the element-wise work, which weighs
+// twice as much per MFMA there; at D = 128 the accumulators alone need more than that)
 template <int D>
-__global__ __launch_bounds__(512, 1) void fwd_kernel(FwdArgs p) {
+__global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   using TL = TileLayout<D>;
   constexpr int KS = D / 16;          // contraction steps of K Q^T
   constexpr int CB = D / 32;          // 32-channel blocks of O^T
