@@ -22,7 +22,6 @@ int check_shape(const dma_shape* s) {
   if (!s) return DMA_EINVAL;
   if (s->T <= 0 || s->n_docs <= 0 || s->k <= 0 || s->H_q <= 0 || s->H_kv <= 0) return DMA_EINVAL;
   if (s->H_q % s->H_kv != 0) return DMA_EINVAL;
-  if (s->n_docs > s->T) return DMA_EINVAL;
   if (s->softmax_scale < 0.f || s->softmax_scale != s->softmax_scale) return DMA_EINVAL;
   if (s->d != 64 && s->d != 128) return DMA_EUNSUPPORTED;
   if (s->dtype != DMA_BF16 && s->dtype != DMA_F32) return DMA_EUNSUPPORTED;

@@ -140,6 +140,12 @@ def check_close(name, got, ref, atol, rtol, frob, summand_abs=None, srel=0.0):
 DZ_SREL = 5e-3
 
 
+# fp32 debug path: dK, dV and dz of a key are sums over the rows that keep it, accumulated one row
+# after the other in fp32; judged against 1e-5 + 1e-5 |ref| + F32_SREL sum |terms| (17 ulps of the
+# summand mass; it is below the plain tolerance until a key is kept by about a thousand rows).
+F32_SREL = 1e-6
+
+
 def dz_allowance(dz_abs, dzD):
     """summand_abs for check_close(..., srel=DZ_SREL) on dz: the sum of |dS_ij| (bf16 rounding of the
     factors of dS), plus the stored-O term: O is kept in bf16, so D_i = dO_i . O_i is off by up to
