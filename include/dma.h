@@ -202,7 +202,7 @@ typedef enum {
   DMA_STAGE_EXPIRY = 2,     /* mask_gen: expiry of every key (Eq. 4)                      */
   DMA_STAGE_PLAN = 3,       /* mask_gen: slots, slot table, partial lists, topk_idx       */
   DMA_STAGE_FWD = 4,        /* fwd: the attention kernel                                  */
-  DMA_STAGE_BWD_ZERO = 5,   /* bwd: clearing the fp32 accumulators                        */
+  DMA_STAGE_BWD_ZERO = 5,   /* bwd: (empty: the dQ stage clears the fp32 accumulators)   */
   DMA_STAGE_BWD_DQ = 6,     /* bwd: D and dQ (query-stationary)                           */
   DMA_STAGE_BWD_DKV = 7,    /* bwd: dK, dV, dz on the slot columns (key-stationary)       */
   DMA_STAGE_BWD_PART = 8,   /* bwd: dK, dV, dz of keys entering / expiring inside a block */

@@ -696,7 +696,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   const size_t nkv = (size_t)s.T * s.H_kv * s.d;
   a.zero_n4 = ((wl.off_dV - wl.off_dK) / 4 + nkv + 3) / 4;  // (the layout pads both buffers to 256 bytes)
   a.dz_n = (size_t)s.H_q * s.T;
-  prof_begin(DMA_STAGE_BWD_ZERO, st);  // (no launch of its own any more: dq_kernel clears the accumulators)
+  prof_begin(DMA_STAGE_BWD_ZERO, st);  // (an empty stage: dq_kernel clears the accumulators)
   prof_end(DMA_STAGE_BWD_ZERO, st);
   const unsigned gq = xcd_grid(s.H_q, L.nblk_cap);
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
