@@ -334,7 +334,8 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     magnitudes for dK and dV, "dK": scale * sum_i |dS_ij| |q_ic| and "dV": sum_i P_ij |do_ic|, both
     [T, H_kv, d] (no part of the result: the yardstick for a reduced-precision sum of many terms), and
     "dzD": sum_i P_ij sum_c |do_ic o_ic| [H_q, T], the weight with which a relative error of the
-    stored o (hence of D_i) enters dz_j.
+    stored o (hence of D_i) enters dz_j, and "dQD": scale * sum_c' |do_ic' o_ic'| * sum_j P_ij |k_jc|
+    [T, H_q, d], the same for dQ_ic.
     """
     Q, K, V, z, dO = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO)
     T, H_q, d = Q.shape
@@ -351,6 +352,7 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     dK_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
     dV_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
     dzD = np.zeros((H_q, T)) if abs_out is not None else None
+    dQD = np.zeros((T, H_q, d)) if abs_out is not None else None
     for h in heads:
         g = h // G
         for a, b in zip(cu[:-1], cu[1:]):
@@ -378,12 +380,14 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
                     dK_abs[a:b, g] += scale * (np.abs(dS).T @ np.abs(q[r0:r1]))
                     dV_abs[a:b, g] += P.T @ np.abs(do[r0:r1])
                     dzD[h, a:b] += (P * np.abs(do[r0:r1] * o).sum(axis=1, keepdims=True)).sum(axis=0)
+                    dQD[a + r0:a + r1, h] = scale * np.abs(do[r0:r1] * o).sum(axis=1, keepdims=True) * (P @ np.abs(kk))
             dz[h, a:b] = dzd
             dz_abs[h, a:b] = dza
     if abs_out is not None:
         abs_out["dK"] = dK_abs
         abs_out["dV"] = dV_abs
         abs_out["dzD"] = dzD
+        abs_out["dQD"] = dQD
     if return_dz_abs:
         return dQ, dK, dV, dz, dz_abs
     return dQ, dK, dV, dz

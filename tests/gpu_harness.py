@@ -154,5 +154,12 @@ def dz_allowance(dz_abs, dzD):
     return np.asarray(dz_abs) + (2.0 ** -9 / DZ_SREL) * np.asarray(dzD)
 
 
+def dq_allowance(dQD):
+    """summand_abs for check_close(..., srel=DZ_SREL) on the bf16 dQ: the stored-O error of D_i (up to
+    2^-9 sum_c |dO_ic O_ic|) enters dQ_i = scale sum_j dS_ij k_j through every kept key, weighted by
+    P_ij; it only matters when a row keeps one or two keys (P of order one)."""
+    return (2.0 ** -9 / DZ_SREL) * np.asarray(dQD)
+
+
 def tol(is_bf16):
     return dict(atol=2e-2, rtol=1e-2, frob=1e-2) if is_bf16 else dict(atol=1e-5, rtol=1e-5, frob=1e-5)
