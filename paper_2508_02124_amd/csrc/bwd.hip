@@ -65,7 +65,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     for (size_t i = gid; i < p.dz_n; i += nth) p.dz[i] = 0.f;
   }
   int h, item;
-  if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
+  if (!xcd_map_interleaved(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
   const int bi = p.nblk_cap - 1 - item;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;

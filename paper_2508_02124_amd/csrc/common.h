@@ -295,6 +295,14 @@ __device__ __forceinline__ bool xcd_map(int wg, int H, int items_per_head, int& 
   item = idx - hq * items_per_head;
   return h < H;
 }
+// Same XCD assignment, but the heads of an XCD take turns item by item: with items ordered from long
+// to short the whole XCD then works from long to short and its last items are the shortest ones.
+__device__ __forceinline__ bool xcd_map_interleaved(int wg, int H, int items_per_head, int& h, int& item) {
+  const int x = wg & 7, idx = wg >> 3, hb = (H + 7) >> 3;
+  item = idx / hb;
+  h = x + 8 * (idx - item * hb);
+  return h < H;
+}
 static inline unsigned xcd_grid(int H, long items_per_head) { return (unsigned)(8l * ((H + 7) / 8) * items_per_head); }
 
 // document of a global row: largest d with cu[d] <= t

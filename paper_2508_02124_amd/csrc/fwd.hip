@@ -56,7 +56,7 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   __shared__ __align__(16) int e_ring[NS][KT];
 
   int h, item;
-  if (!xcd_map(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
+  if (!xcd_map_interleaved(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
   const int bi = p.nblk_cap - 1 - item;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;
