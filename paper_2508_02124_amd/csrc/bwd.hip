@@ -307,7 +307,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
   const int nchunk = (p.nblk_cap + (PARTIAL ? p.seg_part : p.seg) - 1) / (PARTIAL ? p.seg_part : p.seg);
   int h, item;
-  if (!xcd_map(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
+  if (!xcd_map_interleaved(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
   // Clean mode: the groups of a chunk are neighbours.  Partial mode: group-major, because the high
   // groups of most chunks are empty and workgroups go to the shader engines in turn: with the
   // groups as the fast index all the work would land on the engines that get groups 0 and 1.

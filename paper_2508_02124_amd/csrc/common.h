@@ -284,19 +284,11 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
 // Workgroups are dealt round-robin to the chip's 8 XCDs in launch order, and each XCD has its own
-// L2.  A 1-D grid of 8 * ceil(H / 8) * items_per_head workgroups is mapped so that XCD x works
-// through heads x, x + 8, ... one after the other, with consecutive items of a head running
-// side by side on that XCD: neighbouring query blocks of a head gather almost the same keys, and
-// the slot groups of a head sweep the same Q / dO tiles, so those re-reads hit in that L2.
-__device__ __forceinline__ bool xcd_map(int wg, int H, int items_per_head, int& h, int& item) {
-  const int x = wg & 7, idx = wg >> 3;
-  const int hq = idx / items_per_head;
-  h = x + 8 * hq;
-  item = idx - hq * items_per_head;
-  return h < H;
-}
-// Same XCD assignment, but the heads of an XCD take turns item by item: with items ordered from long
-// to short the whole XCD then works from long to short and its last items are the shortest ones.
+// L2.  A 1-D grid of 8 * ceil(H / 8) * items_per_head workgroups is mapped so that XCD x works on
+// heads x, x + 8, ...: neighbouring query blocks of a head gather almost the same keys, and the slot
+// groups of a head sweep the same Q / dO tiles, so those re-reads hit in that L2.  The heads of an
+// XCD take turns item by item: with items ordered from long to short the whole XCD then works from
+// long to short, and its last items are the shortest ones.
 __device__ __forceinline__ bool xcd_map_interleaved(int wg, int H, int items_per_head, int& h, int& item) {
   const int x = wg & 7, idx = wg >> 3, hb = (H + 7) >> 3;
   item = idx / hb;
