@@ -12,7 +12,10 @@ LIB = os.path.join(HERE, "libdma_hip.so")
 SOURCES = ["api.hip", "mask_gen.hip", "fwd.hip", "bwd.hip", "mask_bwd.hip", "xhead.hip", "decode.hip", "debug_f32.hip", "probe.hip"]
 # The attention kernels never produce a NaN from finite inputs (inf - inf is avoided explicitly), so
 # their max / compare chains may skip NaN canonicalisation; infinities stay honoured (-inf masks).
-EXTRA_FLAGS = {"fwd.hip": ["-fno-honor-nans"], "bwd.hip": ["-fno-honor-nans"]}
+# With IEEE mode off as well, a maximum is one instruction (no quieting of its inputs first).  The
+# device library's helpers are built with the mode on and would not inline into such kernels: these
+# two files read launch indices through builtins (wg_id, thread_id) and call no library function.
+EXTRA_FLAGS = {"fwd.hip": ["-fno-honor-nans", "-mno-amdgpu-ieee"], "bwd.hip": ["-fno-honor-nans", "-mno-amdgpu-ieee"]}
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -21,6 +21,7 @@
 // which is exactly the B-operand layout of the products that consume them; the other operand of
 // those products is read from row-major LDS tiles with transposing LDS reads.
 #include "common.h"
+#include <type_traits>
 
 namespace dma {
 
@@ -41,6 +42,7 @@ struct BwdArgs {
   float scale, c2;
   size_t zero_n4;  // float4 elements from dK32 to the end of dV32 (cleared by dq_kernel)
   size_t dz_n;     // elements of dz (cleared by dq_kernel)
+  unsigned grid_dq;  // workgroups of the dq_kernel launch
 };
 
 // ------------------------------------------------------------------ dQ (and D, LSE * log2 e)
@@ -59,19 +61,19 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   // (the fp32 dK / dV buffers and dz): every workgroup, also one without a block, takes its share of
   // the stores; this kernel is bound by the matrix cores, so they cost no time here.
   {
-    const size_t nth = (size_t)gridDim.x * 512, gid = (size_t)blockIdx.x * 512 + threadIdx.x;
+    const size_t nth = (size_t)p.grid_dq * 512, gid = (size_t)wg_id() * 512 + thread_id();
     float4* acc4 = reinterpret_cast<float4*>(p.dK32);
     for (size_t i = gid; i < p.zero_n4; i += nth) acc4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (size_t i = gid; i < p.dz_n; i += nth) p.dz[i] = 0.f;
   }
   int h, item;
-  if (!xcd_map_interleaved(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
+  if (!xcd_map_interleaved(wg_id(), p.H_q, p.nblk_cap, h, item)) return;
   const int bi = p.nblk_cap - 1 - item;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;
   const int row0 = info.y, row1 = info.z, doc0 = info.w;
   const int g = h / (p.H_q / p.H_kv);
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
+  const int tid = thread_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int ncol = min(p.k, row0 - doc0);
   const int nc = (ncol + KT - 1) / KT;
   const int np_keys = p.pcnt[(size_t)h * p.nblk_cap + bi];
@@ -80,11 +82,24 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   const int32_t* plist_row = p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART;
   const float* zqh = p.zq + (size_t)h * p.T;
   const int32_t* eh = p.expiry + (size_t)h * p.T;
-  const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
   const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
   const int32_t* c_zero = reinterpret_cast<const int32_t*>(p.consts + 260);
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
 
+  // gathered rows: wave-uniform base of the kv-head plus a 32-bit byte offset (id * row pitch + the
+  // lane's chunk); an empty slot (id < 0) copies row 0, which its score of -inf keeps out of every sum
+  const void* Kg = uniform_ptr(p.K + (size_t)g * D);
+  const void* Vg = uniform_ptr(p.V + (size_t)g * D);
+  const uint32_t row_pitch = (uint32_t)p.H_kv * D * 2;
+  uint32_t lane_chunk[WL];
+  int lane_row[WL];
+#pragma unroll
+  for (int j = 0; j < WL; j++) {
+    lane_row[j] = (w * WL + j) * RPL + l / CPR;
+    lane_chunk[j] = (uint32_t)(((l % CPR) ^ TL::swz(lane_row[j])) * 16);
+  }
+  const uint32_t ldsK = lds_addr(ringK) + (uint32_t)(w * WL * RPL * D * 2);
+  const uint32_t ldsV = lds_addr(ringV) + (uint32_t)(w * WL * RPL * D * 2);
   auto issue_ids = [&](int tt) {
     if (w == 0) {
       const int32_t* src = c_m1;
@@ -97,30 +112,22 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
       dma4(src, &ids_ring[tt % (2 * NS)][0]);
     }
   };
-  auto issue_kv = [&](int tt) {
+  auto issue_kv = [&](int tt, int st) {  // st = tt % NS (a constant in the main loop)
     const int* idr = ids_ring[tt % (2 * NS)];
-    uint16_t* kd = ringK + (tt % NS) * TILE;
-    uint16_t* vd = ringV + (tt % NS) * TILE;
+    int idv[WL];
+#pragma unroll
+    for (int j = 0; j < WL; j++) idv[j] = idr[lane_row[j]];
+    int idl = 0;
+    if (w == 1) idl = idr[l];
 #pragma unroll
     for (int j = 0; j < WL; j++) {
-      const int rbase = (w * WL + j) * RPL;
-      const int r = rbase + l / CPR;
-      const int c = (l % CPR) ^ TL::swz(r);
-      const int id = idr[r];
-      const uint16_t* ks = zero_row + 8 * c;
-      const uint16_t* vs = ks;
-      if (id >= 0) {
-        const size_t off = ((size_t)id * p.H_kv + g) * D + 8 * c;
-        ks = p.K + off;
-        vs = p.V + off;
-      }
-      dma16(ks, kd + rbase * D);
-      dma16(vs, vd + rbase * D);
+      const uint32_t off = mul24((uint32_t)max(idv[j], 0), row_pitch) + lane_chunk[j];
+      const uint32_t dst = (uint32_t)((st * TILE + j * RPL * D) * 2);
+      dma16s_pair(Kg, Vg, off, ldsK + dst, ldsV + dst);
     }
     if (w == 1) {
-      const int id = idr[l];
-      dma4(id >= 0 ? zqh + id : c_ninf, &z_ring[tt % NS][0]);
-      dma4(id >= 0 ? (const void*)(eh + id) : (const void*)c_zero, &e_ring[tt % NS][0]);
+      dma4(idl >= 0 ? zqh + idl : c_ninf, &z_ring[st][0]);
+      dma4(idl >= 0 ? (const void*)(eh + idl) : (const void*)c_zero, &e_ring[st][0]);
     }
   };
   auto wait_tile = [&]() {
@@ -134,7 +141,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   lds_barrier();
   for (int i = 0; i < NS - 1; i++) {
     issue_ids(NS - 1 + i);
-    issue_kv(i);
+    issue_kv(i, i);
   }
 
   const int qi = row0 + 32 * w + n;
@@ -163,15 +170,35 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     settle(qreg[ks]);
     settle(doreg[ks]);
   }
-  Dsum += __shfl_xor(Dsum, 32);
+  Dsum = half_swap_sum(Dsum);
   float lse2 = qvalid ? p.LSE[(size_t)h * p.T + qi] * LOG2E : INFINITY;
   settle(lse2);
   if (qvalid && hh == 0) {
     p.Dws[(size_t)h * p.T + qi] = Dsum;
     p.L2ws[(size_t)h * p.T + qi] = lse2;
   }
+  // fragment addresses with the ring bases folded in: inside the stage-unrolled main loop every LDS
+  // read is one of these registers plus an immediate
   FragOffsets<D> fo;
   fo.init(l);
+  uint32_t kfrag[KS], vfrag[KS], ktr[CB][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    kfrag[ks] = lds_addr(ringK) + 2 * fo.row[ks];
+    vfrag[ks] = lds_addr(ringV) + 2 * fo.row[ks];
+    settle(kfrag[ks]);
+    settle(vfrag[ks]);
+  }
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      ktr[cb][q] = lds_addr(ringK) + 2 * fo.tr[cb][q];
+      settle(ktr[cb][q]);
+    }
+  uint32_t zlane = lds_addr(&z_ring[0][4 * hh]);
+  const uint32_t jlane = lds_addr(&ids_ring[0][4 * hh]), elane = lds_addr(&e_ring[0][4 * hh]);
+  settle(zlane);
   f32x16 dqacc[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
@@ -179,22 +206,20 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     for (int v = 0; v < 16; v++) dqacc[cb][v] = 0.f;
   wait_vmcnt<0>();  // the ordinary loads and stores above; from here on only copies are in flight
 
-  for (int t = 0; t < nt; t++) {
+  // one key tile; ST = t % NS is a compile-time constant (the loop below is unrolled over the ring)
+  auto tile = [&](auto stc, const int t) {
+    constexpr int ST = decltype(stc)::value;
     if (t > 0) wait_tile();
     lds_barrier();
     issue_ids(t + 2 * NS - 2);
-    issue_kv(t + NS - 1);
-    const uint16_t* Ks = ringK + (t % NS) * TILE;
-    const uint16_t* Vs = ringV + (t % NS) * TILE;
-    const float* zs = z_ring[t % NS];
-    const int* js = ids_ring[t % (2 * NS)];
-    const int* es = e_ring[t % NS];
+    issue_kv(t + NS - 1, (ST + NS - 1) % NS);
+    const int ist = t % (2 * NS);
     const bool masked = t >= nc;
     if (masked) {
       // partial tile: skip it if none of its keys is active on any of this wave's 32 rows
-      const int jl = js[l], el = es[l];
+      const int jl = ids_ring[ist][l], el = e_ring[ST][l];
       const int rfirst = row0 + 32 * w;
-      if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) continue;
+      if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) return;
     }
 
 #pragma unroll
@@ -206,8 +231,7 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
         f32x16 sacc, dpacc;
 #pragma unroll
         for (int gq = 0; gq < 4; gq++) {
-          const int r = 32 * kb + 8 * gq + 4 * hh;
-          const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
+          const f32x4 zz = lds_load<f32x4>(zlane + 4 * (ST * KT + 32 * kb + 8 * gq));
 #pragma unroll
           for (int u = 0; u < 4; u++) {
             sacc[4 * gq + u] = zz[u];
@@ -217,21 +241,19 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
         if (masked) {
 #pragma unroll
           for (int gq = 0; gq < 4; gq++) {
-            const int r = 32 * kb + 8 * gq + 4 * hh;
-            const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
-            const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
-            const int jv[4] = {jj.x, jj.y, jj.z, jj.w}, ev[4] = {ee.x, ee.y, ee.z, ee.w};
+            const i32x4 jj = lds_load<i32x4>(jlane + 4 * (ist * KT + 32 * kb + 8 * gq));
+            const i32x4 ee = lds_load<i32x4>(elane + 4 * (ST * KT + 32 * kb + 8 * gq));
 #pragma unroll
             for (int u = 0; u < 4; u++) {
-              const bool ok = (jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]);
+              const bool ok = (jj[u] >= 0) & (qi >= jj[u]) & (qi < ee[u]);
               sacc[4 * gq + u] = ok ? sacc[4 * gq + u] : -INFINITY;
             }
           }
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-          sacc = mfma32(fo.row_frag(Ks, 32 * kb, ks), qreg[ks], sacc);
-          dpacc = mfma32(fo.row_frag(Vs, 32 * kb, ks), doreg[ks], dpacc);
+          sacc = mfma32(lds_load<bf16x8>(kfrag[ks] + 2 * (ST * TILE + 32 * kb * D)), qreg[ks], sacc);
+          dpacc = mfma32(lds_load<bf16x8>(vfrag[ks] + 2 * (ST * TILE + 32 * kb * D)), doreg[ks], dpacc);
         }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
@@ -244,10 +266,24 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
 #pragma unroll
       for (int c = 0; c < 2; c++)
 #pragma unroll
-        for (int cb = 0; cb < CB; cb++)
-          dqacc[cb] = mfma32(fo.tr_frag(Ks, 32 * kb + 16 * c, cb), dsb[c], dqacc[cb]);
+        for (int cb = 0; cb < CB; cb++) {
+          const s16x4 lo = lds_read_tr_at(ktr[cb][0] + 2 * (ST * TILE + (32 * kb + 16 * c) * D));
+          const s16x4 hi = lds_read_tr_at(ktr[cb][1] + 2 * (ST * TILE + (32 * kb + 16 * c) * D));
+          const bf16x8 kf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          dqacc[cb] = mfma32(kf, dsb[c], dqacc[cb]);
+        }
     }
+  };
+  for (int t = 0; t < nt; t += NS) {
+    tile(std::integral_constant<int, 0>{}, t);
+    if (t + 1 >= nt) break;
+    tile(std::integral_constant<int, 1>{}, t + 1);
+    if (t + 2 >= nt) break;
+    tile(std::integral_constant<int, 2>{}, t + 2);
+    if (t + 3 >= nt) break;
+    tile(std::integral_constant<int, 3>{}, t + 3);
   }
+  static_assert(NS == 4, "the main loop is unrolled over four ring stages");
 
   wait_vmcnt<0>();
   lds_barrier();
@@ -307,13 +343,13 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
   const int nchunk = (p.nblk_cap + (PARTIAL ? p.seg_part : p.seg) - 1) / (PARTIAL ? p.seg_part : p.seg);
   int h, item;
-  if (!xcd_map_interleaved(blockIdx.x, p.H_q, ngrp * nchunk, h, item)) return;
+  if (!xcd_map_interleaved(wg_id(), p.H_q, ngrp * nchunk, h, item)) return;
   // Clean mode: the groups of a chunk are neighbours.  Partial mode: group-major, because the high
   // groups of most chunks are empty and workgroups go to the shader engines in turn: with the
   // groups as the fast index all the work would land on the engines that get groups 0 and 1.
   const int chunk = PARTIAL ? item % nchunk : item / ngrp, grp = PARTIAL ? item / nchunk : item - chunk * ngrp;
   const int g = h / (p.H_q / p.H_kv);
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
+  const int tid = thread_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int kb4 = w & 3, role = w >> 2;
   const float* zqh = p.zq + (size_t)h * p.T;
   const float* Dh = p.Dws + (size_t)h * p.T;
@@ -642,9 +678,9 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 
 // dK, dV: fp32 accumulators -> bf16 outputs
 __global__ void cvt_bf16_kernel(const float* __restrict__ a, const float* __restrict__ b, uint16_t* __restrict__ oa,
-                                uint16_t* __restrict__ ob, size_t n4) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  const size_t st = (size_t)gridDim.x * blockDim.x;
+                                uint16_t* __restrict__ ob, size_t n4, unsigned nwg) {
+  size_t i = wg_id() * (size_t)256 + thread_id();  // launched with 256 threads
+  const size_t st = (size_t)nwg * 256;
   for (; i < n4; i += st) {
     const float4 x = reinterpret_cast<const float4*>(a)[i];
     const float4 y = reinterpret_cast<const float4*>(b)[i];
@@ -699,6 +735,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   prof_begin(DMA_STAGE_BWD_ZERO, st);  // (an empty stage: dq_kernel clears the accumulators)
   prof_end(DMA_STAGE_BWD_ZERO, st);
   const unsigned gq = xcd_grid(s.H_q, L.nblk_cap);
+  a.grid_dq = gq;
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
   const unsigned gpart = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg_part - 1) / a.seg_part) * (MAXPART / SG));
   prof_begin(DMA_STAGE_BWD_DQ, st);
@@ -714,7 +751,8 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   else dkv_kernel<64, true><<<gpart, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_PART, st);
   prof_begin(DMA_STAGE_BWD_CVT, st);
-  cvt_bf16_kernel<<<grid_for(nkv / 4, 1024), 256, 0, st>>>(a.dK32, a.dV32, (uint16_t*)dK, (uint16_t*)dV, nkv / 4);
+  const unsigned gcvt = grid_for(nkv / 4, 1024);
+  cvt_bf16_kernel<<<gcvt, 256, 0, st>>>(a.dK32, a.dV32, (uint16_t*)dK, (uint16_t*)dV, nkv / 4, gcvt);
   prof_end(DMA_STAGE_BWD_CVT, st);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }

@@ -21,6 +21,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -216,6 +217,34 @@ __device__ __forceinline__ void dma16s(const void* uniform_base, uint32_t lane_o
   asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
                : "=&s"(keep) : "v"(lane_off), "s"(sb), "s"(lds) : "memory");
 }
+// Two copies with one scalar base each and a shared per-lane 32-bit byte offset (the K and the V row
+// piece of one gathered key): M0 is saved and restored once around the pair.
+__device__ __forceinline__ void dma16s_pair(const void* base_a, const void* base_b, uint32_t lane_off,
+                                            uint32_t lds_a, uint32_t lds_b) {
+  uint32_t keep;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+      "s_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\ts_mov_b32 m0, %0"
+      : "=&s"(keep)
+      : "v"(lane_off), "s"(base_a), "s"(base_b), "s"(lds_a), "s"(lds_b)
+      : "memory");
+}
+// a * b for a, b < 2^24 (one full-rate instruction; the masks fold away)
+__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return (a & 0xffffffu) * (b & 0xffffffu); }
+__device__ __forceinline__ uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)(lds_vptr)p; }
+// Reads at a 32-bit LDS byte address (kept as an integer so that a pinned register keeps its address
+// space; a constant added at the call site becomes the instruction's immediate offset).
+template <typename T> __device__ __forceinline__ T lds_load(uint32_t a) {
+  return *(__attribute__((address_space(3))) const T*)(uintptr_t)a;
+}
+__device__ __forceinline__ s16x4 lds_read_tr_at(uint32_t a) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)a);
+}
+__device__ __forceinline__ const void* uniform_ptr(const void* p) {
+  const uint64_t b = (uint64_t)(uintptr_t)p;
+  return (const void*)(uintptr_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b));
+}
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
@@ -281,7 +310,27 @@ struct FragOffsets {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max(x of lane l, x of lane l ^ 32) in every lane: the two half-waves exchange their values with
+// one cross-half swap (no LDS round trip).
+__device__ __forceinline__ float half_swap_max(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Launch indices read from the hardware registers directly.  fwd.hip and bwd.hip are compiled with
+// IEEE mode off (maxima need no NaN quieting there); the device library's index helpers are built
+// with it on and would stay out-of-line calls in such a kernel.
+__device__ __forceinline__ int wg_id() { return (int)__builtin_amdgcn_workgroup_id_x(); }
+__device__ __forceinline__ int thread_id() { return (int)__builtin_amdgcn_workitem_id_x(); }
 
 // Workgroups are dealt round-robin to the chip's 8 XCDs in launch order, and each XCD has its own
 // L2.  A 1-D grid of 8 * ceil(H / 8) * items_per_head workgroups is mapped so that XCD x works on

@@ -15,6 +15,7 @@
 // as the B operand of O^T += V^T P^T.  The bias z is not added after the product: the accumulator
 // starts at z / scale, so scale * acc is the biased score and one FMA gives the exp2 argument.
 #include "common.h"
+#include <type_traits>
 
 namespace dma {
 
@@ -56,13 +57,13 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   __shared__ __align__(16) int e_ring[NS][KT];
 
   int h, item;
-  if (!xcd_map_interleaved(blockIdx.x, p.H_q, p.nblk_cap, h, item)) return;
+  if (!xcd_map_interleaved(wg_id(), p.H_q, p.nblk_cap, h, item)) return;
   const int bi = p.nblk_cap - 1 - item;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;
   const int row0 = info.y, row1 = info.z, doc0 = info.w;
   const int g = h / (p.H_q / p.H_kv);
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
+  const int tid = thread_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
   const int ncol = min(p.k, row0 - doc0);
   const int nc = (ncol + KT - 1) / KT;
   const int np_keys = p.pcnt[(size_t)h * p.nblk_cap + bi];
@@ -71,13 +72,27 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   const int32_t* plist_row = p.plist + ((size_t)h * p.nblk_cap + bi) * MAXPART;
   const float* zqh = p.zq + (size_t)h * p.T;
   const int32_t* eh = p.expiry + (size_t)h * p.T;
-  const uint16_t* zero_row = reinterpret_cast<const uint16_t*>(p.consts);
   const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
   const int32_t* c_zero = reinterpret_cast<const int32_t*>(p.consts + 260);
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
 
   // ---- asynchronous producers (every wave issues the same number of copies for every tile index,
-  // real or past the end, so the outstanding-copy counts below are constants)
+  // real or past the end, so the outstanding-copy counts below are constants).  A gathered row is
+  // addressed as a wave-uniform base (the kv-head's first row) plus a 32-bit byte offset
+  // id * row pitch + the lane's chunk; an empty slot (id < 0) copies row 0 instead, which its score
+  // of -inf keeps out of every sum.
+  const void* Kg = uniform_ptr(p.K + (size_t)g * D);
+  const void* Vg = uniform_ptr(p.V + (size_t)g * D);
+  const uint32_t row_pitch = (uint32_t)p.H_kv * D * 2;
+  uint32_t lane_chunk[WL];  // byte offset of the lane's 16-byte chunk within its row, per copy
+  int lane_row[WL];         // tile row the lane copies
+#pragma unroll
+  for (int j = 0; j < WL; j++) {
+    lane_row[j] = (w * WL + j) * RPL + l / CPR;
+    lane_chunk[j] = (uint32_t)(((l % CPR) ^ TL::swz(lane_row[j])) * 16);
+  }
+  const uint32_t ldsK = lds_addr(ringK) + (uint32_t)(w * WL * RPL * D * 2);
+  const uint32_t ldsV = lds_addr(ringV) + (uint32_t)(w * WL * RPL * D * 2);
   auto issue_ids = [&](int tt) {
     if (w == 0) {
       const int32_t* src = c_m1;
@@ -90,30 +105,22 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
       dma4(src, &ids_ring[tt % (2 * NS)][0]);
     }
   };
-  auto issue_kv = [&](int tt) {
+  auto issue_kv = [&](int tt, int st) {  // st = tt % NS (a constant in the main loop)
     const int* idr = ids_ring[tt % (2 * NS)];
-    uint16_t* kd = ringK + (tt % NS) * TILE;
-    uint16_t* vd = ringV + (tt % NS) * TILE;
+    int idv[WL];
+#pragma unroll
+    for (int j = 0; j < WL; j++) idv[j] = idr[lane_row[j]];
+    int idl = 0;
+    if (w == 1) idl = idr[l];
 #pragma unroll
     for (int j = 0; j < WL; j++) {
-      const int rbase = (w * WL + j) * RPL;
-      const int r = rbase + l / CPR;
-      const int c = (l % CPR) ^ TL::swz(r);
-      const int id = idr[r];
-      const uint16_t* ks = zero_row + 8 * c;
-      const uint16_t* vs = ks;
-      if (id >= 0) {
-        const size_t off = ((size_t)id * p.H_kv + g) * D + 8 * c;
-        ks = p.K + off;
-        vs = p.V + off;
-      }
-      dma16(ks, kd + rbase * D);
-      dma16(vs, vd + rbase * D);
+      const uint32_t off = mul24((uint32_t)max(idv[j], 0), row_pitch) + lane_chunk[j];
+      const uint32_t dst = (uint32_t)((st * TILE + j * RPL * D) * 2);
+      dma16s_pair(Kg, Vg, off, ldsK + dst, ldsV + dst);
     }
     if (w == 1) {
-      const int id = idr[l];
-      dma4(id >= 0 ? zqh + id : c_ninf, &z_ring[tt % NS][0]);
-      dma4(id >= 0 ? (const void*)(eh + id) : (const void*)c_zero, &e_ring[tt % NS][0]);
+      dma4(idl >= 0 ? zqh + idl : c_ninf, &z_ring[st][0]);
+      dma4(idl >= 0 ? (const void*)(eh + idl) : (const void*)c_zero, &e_ring[st][0]);
     }
   };
   // copies a wave issues per tile step, and how many may still be in flight when tile t is needed
@@ -128,7 +135,7 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   lds_barrier();
   for (int i = 0; i < NS - 1; i++) {
     issue_ids(NS - 1 + i);
-    issue_kv(i);
+    issue_kv(i, i);
   }
 
   // query fragments (B operand of K Q^T): lane holds row qi, channels 16*ks + 8*hh .. +8
@@ -145,8 +152,26 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) settle(qreg[ks]);
   }
+  // The lane's fragment addresses with the ring bases folded in: inside the (stage-unrolled) main
+  // loop every LDS read is one of these registers plus an immediate.
   FragOffsets<D> fo;
   fo.init(l);
+  uint32_t kfrag[KS], vfrag[CB][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    kfrag[ks] = lds_addr(ringK) + 2 * fo.row[ks];
+    settle(kfrag[ks]);
+  }
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      vfrag[cb][q] = lds_addr(ringV) + 2 * fo.tr[cb][q];
+      settle(vfrag[cb][q]);
+    }
+  uint32_t zlane = lds_addr(&z_ring[0][4 * hh]);
+  const uint32_t jlane = lds_addr(&ids_ring[0][4 * hh]), elane = lds_addr(&e_ring[0][4 * hh]);
+  settle(zlane);
   f32x16 oacc[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
@@ -157,20 +182,20 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   // that the per-tile counts below only ever see copies
   wait_vmcnt<0>();
 
-  for (int t = 0; t < nt; t++) {
+  // one key tile; ST = t % NS is a compile-time constant (the loop below is unrolled over the ring)
+  auto tile = [&](auto stc, const int t) {
+    constexpr int ST = decltype(stc)::value;
     if (t > 0) wait_tile();  // (t == 0: the wait above already drained everything)
     lds_barrier();
     issue_ids(t + 2 * NS - 2);
-    issue_kv(t + NS - 1);
-    const uint16_t* Ks = ringK + (t % NS) * TILE;
-    const uint16_t* Vs = ringV + (t % NS) * TILE;
-    const float* zs = z_ring[t % NS];
+    issue_kv(t + NS - 1, (ST + NS - 1) % NS);
+    const int ist = t % (2 * NS);  // stage of the tile's ids
     if (t >= nc) {
       // partial tile: skip it if none of its keys is active on any of this wave's 32 rows (the
       // lists are ordered by first / last active row, so about half of the wave-tiles drop out)
-      const int jl = ids_ring[t % (2 * NS)][l], el = e_ring[t % NS][l];
+      const int jl = ids_ring[ist][l], el = e_ring[ST][l];
       const int rfirst = row0 + 32 * w;
-      if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) continue;
+      if (!__any((jl >= 0) & (jl <= rfirst + 31) & (el > rfirst))) return;
     }
 
     // The accumulator of S^T = K Q^T starts at z / scale, so that scale * acc is the biased score;
@@ -180,25 +205,21 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int gq = 0; gq < 4; gq++) {
-        const int r = 32 * kb + 8 * gq + 4 * hh;
-        const f32x4 zz = *reinterpret_cast<const f32x4*>(&zs[r]);
+        const f32x4 zz = lds_load<f32x4>(zlane + 4 * (ST * KT + 32 * kb + 8 * gq));
 #pragma unroll
         for (int u = 0; u < 4; u++) sacc[kb][4 * gq + u] = zz[u];
       }
     if (t >= nc) {
-      const int* js = ids_ring[t % (2 * NS)];
-      const int* es = e_ring[t % NS];
+      const uint32_t js = jlane + 4 * ist * KT;
 #pragma unroll
       for (int kb = 0; kb < 2; kb++)
 #pragma unroll
         for (int gq = 0; gq < 4; gq++) {
-          const int r = 32 * kb + 8 * gq + 4 * hh;
-          const int4 jj = *reinterpret_cast<const int4*>(&js[r]);
-          const int4 ee = *reinterpret_cast<const int4*>(&es[r]);
-          const int jv[4] = {jj.x, jj.y, jj.z, jj.w}, ev[4] = {ee.x, ee.y, ee.z, ee.w};
+          const i32x4 jj = lds_load<i32x4>(js + 4 * (32 * kb + 8 * gq));
+          const i32x4 ee = lds_load<i32x4>(elane + 4 * (ST * KT + 32 * kb + 8 * gq));
 #pragma unroll
           for (int u = 0; u < 4; u++) {
-            const bool ok = (jv[u] >= 0) & (qi >= jv[u]) & (qi < ev[u]);
+            const bool ok = (jj[u] >= 0) & (qi >= jj[u]) & (qi < ee[u]);
             sacc[kb][4 * gq + u] = ok ? sacc[kb][4 * gq + u] : -INFINITY;
           }
         }
@@ -208,15 +229,16 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
       for (int kb = 0; kb < 2; kb++) {
-        sacc[kb] = mfma32(fo.row_frag(Ks, 32 * kb, ks), qreg[ks], sacc[kb]);
+        const bf16x8 kf = lds_load<bf16x8>(kfrag[ks] + 2 * (ST * TILE + 32 * kb * D));
+        sacc[kb] = mfma32(kf, qreg[ks], sacc[kb]);
       }
     // Online softmax in the exp2 domain with a lazily updated reference maximum: m_run moves only
     // when the tile's maximum exceeds it by more than MSLACK, so that the rescaling of O and l is
     // rare; until then the exponentials are at most 2^MSLACK, which fp32 accumulation absorbs.
     float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
-    for (int v = 1; v < 16; v++) mx = fmaxf(mx, fmaxf(sacc[0][v], sacc[1][v]));
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.c2;
+    for (int v = 1; v < 16; v++) mx = fmaxf(fmaxf(mx, sacc[0][v]), sacc[1][v]);  // one three-input maximum each
+    mx = half_swap_max(mx) * p.c2;
     const bool grow = mx > m_run + MSLACK;
     if (__any(grow)) {
       const float m_new = grow ? mx : m_run;
@@ -230,20 +252,37 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
     }
     const float msub = (m_run == -INFINITY) ? 0.f : m_run;  // row with nothing kept so far: exp2(-inf - 0) = 0
     bf16x8 pb[4];  // the four 16-key quarters
+    float ls2 = 0.f;  // (two chains: the sums stay fp32-exact in the weights, LSE feeds the backward)
 #pragma unroll
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
         const float pv = fast_exp2(fmaf(sacc[kb][v], p.c2, -msub));
-        lsum += pv;
+        if (kb == 0) lsum += pv; else ls2 += pv;
         pb[2 * kb + (v >> 3)][v & 7] = (__bf16)pv;
       }
+    lsum += ls2;
     // O^T += V^T P^T
 #pragma unroll
     for (int c = 0; c < 4; c++)
 #pragma unroll
-      for (int cb = 0; cb < CB; cb++) oacc[cb] = mfma32(fo.tr_frag(Vs, 16 * c, cb), pb[c], oacc[cb]);
+      for (int cb = 0; cb < CB; cb++) {
+        const s16x4 lo = lds_read_tr_at(vfrag[cb][0] + 2 * (ST * TILE + 16 * c * D));
+        const s16x4 hi = lds_read_tr_at(vfrag[cb][1] + 2 * (ST * TILE + 16 * c * D));
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        oacc[cb] = mfma32(vf, pb[c], oacc[cb]);
+      }
+  };
+  for (int t = 0; t < nt; t += NS) {
+    tile(std::integral_constant<int, 0>{}, t);
+    if (t + 1 >= nt) break;
+    tile(std::integral_constant<int, 1>{}, t + 1);
+    if (t + 2 >= nt) break;
+    tile(std::integral_constant<int, 2>{}, t + 2);
+    if (t + 3 >= nt) break;
+    tile(std::integral_constant<int, 3>{}, t + 3);
   }
+  static_assert(NS == 4, "the main loop is unrolled over four ring stages");
 
   // epilogue: drain the (dummy) copies still in flight, normalise, stage O through LDS for
   // coalesced rows, write LSE
@@ -252,7 +291,7 @@ __global__ __launch_bounds__(512, D == 64 ? 4 : 1) void fwd_kernel(FwdArgs p) {
   uint16_t* Os = ringK;  // [BQ][D] with the tile swizzle; NS * KT == BQ rows
   static_assert(NS * KT == BQ, "O staging aliases the K ring");
   {
-    const float ltot = lsum + __shfl_xor(lsum, 32);
+    const float ltot = half_swap_sum(lsum);
     const float inv = 1.f / ltot;
     if (hh == 0 && qi < row1) p.LSE[(size_t)h * p.T + qi] = (m_run + __builtin_amdgcn_logf(ltot)) * LN2;
 #pragma unroll
