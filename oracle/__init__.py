@@ -23,4 +23,6 @@ from .dma_oracle import (  # noqa: F401
     dma_decode,
     z_scores_xhead,
     xhead_backward,
+    expand_bias,
+    bias_backward,
 )

@@ -42,7 +42,10 @@ the gather-loop formulation of Listing 1; mask_backward: central finite
 differences of Eq. 3 and torch autograd of the forward formula; dma_decode:
 the last rows of the dense forward oracle and of topk_indices; z_scores_xhead /
 xhead_backward: a block-structured Delta reproduces the per-head functions,
-torch's linear + softplus + exp and its autograd, central finite differences.
+torch's linear + softplus + exp and its autograd, central finite differences;
+the bias argument / expand_bias / bias_backward: torch SDPA with the bias as attn_mask
+(forward and autograd, all four broadcast forms), finite differences, and a kept
+set that must not move with the bias; O_stored: the closed form of its shift.
 No function here is unpinned.
 """
 from __future__ import annotations
@@ -57,7 +60,7 @@ __all__ = [
     "expiry_from_kept", "expiry_sequential", "topk_indices", "dma_forward",
     "dma_backward", "dma_forward_gather_loop", "dma_scalar_bruteforce",
     "n_active_pairs", "dma_rows", "dma_keys", "mask_backward", "dma_decode",
-    "z_scores_xhead", "xhead_backward",
+    "z_scores_xhead", "xhead_backward", "expand_bias", "bias_backward",
 ]
 
 
@@ -287,9 +290,50 @@ def _as64(x):
     return np.asarray(x, dtype=np.float64)
 
 
+def expand_bias(bias, H_q, cu_seqlens, per_token=True):
+    """A caller-supplied attention bias with head / batch broadcasting, written out per (head, key):
+    bias [Hb, T] (per_token) or [Hb, n_max] indexed by the key's position in its document and shared
+    by all documents (batch broadcast); Hb = H_q or 1 (head broadcast).  Returns float64 [H_q, T]."""
+    bias = _as64(bias)
+    cu = [int(c) for c in cu_seqlens]
+    T = cu[-1]
+    Hb = bias.shape[0]
+    assert Hb in (1, H_q)
+    out = np.empty((H_q, T))
+    for h in range(H_q):
+        row = bias[h if Hb == H_q else 0]
+        if per_token:
+            out[h] = row[:T]
+        else:
+            for a, b in zip(cu[:-1], cu[1:]):
+                out[h, a:b] = row[: b - a]
+    return out
+
+
+def bias_backward(dz, bias_heads, cu_seqlens, per_token=True, n_max=None):
+    """Gradient of the broadcast bias from dz [H_q, T] (the bias enters the score exactly like z, so
+    d(loss)/d(bias as applied)[h, j] = dz[h, j]): summed over the heads and documents that share an
+    entry.  Returns [bias_heads, T] (per_token) or [bias_heads, n_max]."""
+    dz = _as64(dz)
+    H_q, T = dz.shape
+    cu = [int(c) for c in cu_seqlens]
+    d = dz if bias_heads == H_q else dz.sum(axis=0, keepdims=True)
+    if per_token:
+        return d.copy()
+    out = np.zeros((bias_heads, n_max))
+    for a, b in zip(cu[:-1], cu[1:]):
+        out[:, : b - a] += d[:, a:b]
+    return out
+
+
 def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
-                mask_method="sequential", row_chunk=1024):
+                mask_method="sequential", row_chunk=1024, bias=None):
     """Eq. 5-6 / Alg. 1 result: O [T, H_q, d], LSE [H_q, T].
+
+    bias [H_q, T] (optional): a further additive attention bias per (head, key), broadcast over the
+    query rows (Section 1, "Kernel Design": the kernel takes masks and biases with batch, head and
+    query broadcasting).  It is added to the scores of the kept pairs, S_ij = scale q_i.k_j + z_j +
+    b_j; the kept set is selected on z alone (Eq. 4 ranks the content scores).
 
     heads: iterable of q-head indices to compute (others are left as NaN).
     mask_method: "definition" (per-row stable sort, O(n^2 log n)) or
@@ -313,9 +357,10 @@ def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
                 continue
             q, kk, v, zb = Q[a:b, h], K[a:b, g], V[a:b, g], z[h, a:b]
             prov = _doc_keep_provider(zb, k, causal, mask_method)
+            sb = zb if bias is None else zb + _as64(bias)[h, a:b]
             for r0 in range(0, n, row_chunk):
                 r1 = min(n, r0 + row_chunk)
-                S = scale * (q[r0:r1] @ kk.T) + zb[None, :]
+                S = scale * (q[r0:r1] @ kk.T) + sb[None, :]
                 P, lse = _softmax_rows(S, prov(r0, r1))
                 O[a + r0:a + r1, h] = P @ v
                 LSE[h, a + r0:a + r1] = lse
@@ -323,19 +368,25 @@ def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
 
 
 def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=None,
-                 mask_method="sequential", row_chunk=1024, return_dz_abs=False, abs_out=None):
+                 mask_method="sequential", row_chunk=1024, abs_out=None, O_stored=None, bias=None):
     """Eq. 7-10 / Alg. 2 result: dQ [T, H_q, d], dK, dV [T, H_kv, d], dz [H_q, T].
+
+    bias [H_q, T]: as in dma_forward.  z and the bias enter the score as a sum, so dz is also the
+    gradient with respect to the bias as applied (see bias_backward for the broadcast forms).
 
     dK and dV are summed over the q-heads listed in `heads` that share a
     kv-head (all heads by default).  dV is the attention-path gradient only
-    (the path V -> z is not part of this function).  With return_dz_abs a fifth array
-    sum_i |dS_ij| [H_q, T] is returned: the magnitude of the summands of dz, against which a
-    reduced-precision dz is judged.  A dict passed as abs_out receives the same
-    magnitudes for dK and dV, "dK": scale * sum_i |dS_ij| |q_ic| and "dV": sum_i P_ij |do_ic|, both
-    [T, H_kv, d] (no part of the result: the yardstick for a reduced-precision sum of many terms), and
-    "dzD": sum_i P_ij sum_c |do_ic o_ic| [H_q, T], the weight with which a relative error of the
-    stored o (hence of D_i) enters dz_j, and "dQD": scale * sum_c' |do_ic' o_ic'| * sum_j P_ij |k_jc|
-    [T, H_q, d], the same for dQ_ic.
+    (the path V -> z is not part of this function).
+
+    O_stored [T, H_q, d]: Alg. 2 does not recompute O: it loads the forward's output from memory and
+    forms D_i = rowsum(dO_i o O_i) from it.  With O_stored given, D_i is formed from that array (the
+    buffer a backward kernel is handed, e.g. the forward result rounded to bf16); without it D_i uses
+    the exact O of Eq. 5 (then D_i equals the sum_j p_ij dp_ij of Eq. 8).  dS = P o (dP - D) is linear
+    in D, so the two results differ by dD_i = dO_i . (O_stored_i - O_i) entering as -P_ij dD_i.
+
+    A dict passed as abs_out receives the magnitudes of the summands of dK and dV,
+    "dK": scale * sum_i |dS_ij| |q_ic| and "dV": sum_i P_ij |do_ic|, both [T, H_kv, d] (no part of the
+    result: the yardstick for a sum of many reduced-precision terms).
     """
     Q, K, V, z, dO = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO)
     T, H_q, d = Q.shape
@@ -345,14 +396,12 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     heads = range(H_q) if heads is None else heads
     dQ = np.full((T, H_q, d), np.nan)
     dz = np.full((H_q, T), np.nan)
-    dz_abs = np.full((H_q, T), np.nan)
     dK = np.zeros((T, H_kv, d))
     dV = np.zeros((T, H_kv, d))
     cu = [int(c) for c in cu_seqlens]
     dK_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
     dV_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
-    dzD = np.zeros((H_q, T)) if abs_out is not None else None
-    dQD = np.zeros((T, H_q, d)) if abs_out is not None else None
+    O_st = None if O_stored is None else _as64(O_stored)
     for h in heads:
         g = h // G
         for a, b in zip(cu[:-1], cu[1:]):
@@ -361,13 +410,15 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
                 continue
             q, kk, v, zb, do = Q[a:b, h], K[a:b, g], V[a:b, g], z[h, a:b], dO[a:b, h]
             prov = _doc_keep_provider(zb, k, causal, mask_method)
+            sb = zb if bias is None else zb + _as64(bias)[h, a:b]
             dzd = np.zeros(n)
-            dza = np.zeros(n)
             for r0 in range(0, n, row_chunk):
                 r1 = min(n, r0 + row_chunk)
-                S = scale * (q[r0:r1] @ kk.T) + zb[None, :]
+                S = scale * (q[r0:r1] @ kk.T) + sb[None, :]
                 P, _ = _softmax_rows(S, prov(r0, r1))
                 o = P @ v
+                if O_st is not None:
+                    o = O_st[a + r0:a + r1, h]                      # Alg. 2 loads O_i from memory
                 D = (do[r0:r1] * o).sum(axis=1, keepdims=True)      # Alg. 2: D_i
                 dP = do[r0:r1] @ v.T                                # Eq. 8: dp_j = v_j . do
                 dS = P * (dP - D)                                   # Eq. 8
@@ -375,21 +426,13 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
                 dQ[a + r0:a + r1, h] = scale * (dS @ kk)            # Eq. 10
                 dK[a:b, g] += scale * (dS.T @ q[r0:r1])             # Eq. 10
                 dzd += dS.sum(axis=0)                               # Eq. 9, summed over rows
-                dza += np.abs(dS).sum(axis=0)
                 if dK_abs is not None:
                     dK_abs[a:b, g] += scale * (np.abs(dS).T @ np.abs(q[r0:r1]))
                     dV_abs[a:b, g] += P.T @ np.abs(do[r0:r1])
-                    dzD[h, a:b] += (P * np.abs(do[r0:r1] * o).sum(axis=1, keepdims=True)).sum(axis=0)
-                    dQD[a + r0:a + r1, h] = scale * np.abs(do[r0:r1] * o).sum(axis=1, keepdims=True) * (P @ np.abs(kk))
             dz[h, a:b] = dzd
-            dz_abs[h, a:b] = dza
     if abs_out is not None:
         abs_out["dK"] = dK_abs
         abs_out["dV"] = dV_abs
-        abs_out["dzD"] = dzD
-        abs_out["dQD"] = dQD
-    if return_dz_abs:
-        return dQ, dK, dV, dz, dz_abs
     return dQ, dK, dV, dz
 
 
@@ -476,11 +519,12 @@ class _ExpiryCache:
         return self.c[(h, a)]
 
 
-def dma_rows(Q, K, V, z, dO, cu_seqlens, k, rows, scale=None):
+def dma_rows(Q, K, V, z, dO, cu_seqlens, k, rows, scale=None, O_stored=None):
     """Eq. 5-6 and the dQ half of Eq. 10 for single (head, row) pairs, causal.
 
     rows: iterable of (h, i) with i a global row index.  Returns a list of dicts with keys
     O [d], LSE, dQ [d] (dQ only if dO is given), kept (global key indices, ascending).
+    O_stored: as in dma_backward (D_i from the stored output, Alg. 2).
     """
     Q, K, V, z = _as64(Q), _as64(K), _as64(V), _as64(z)
     dO = None if dO is None else _as64(dO)
@@ -504,7 +548,8 @@ def dma_rows(Q, K, V, z, dO, cu_seqlens, k, rows, scale=None):
         rec = dict(O=o, LSE=m + math.log(tot), kept=kept)
         if dO is not None:
             dp = V[kept, g] @ dO[i, h]
-            ds = p * (dp - float(dO[i, h] @ o))
+            o_D = o if O_stored is None else _as64(O_stored[i, h])
+            ds = p * (dp - float(dO[i, h] @ o_D))
             rec["dQ"] = scale * (ds @ K[kept, g])
         out.append(rec)
     return out
@@ -515,7 +560,8 @@ def dma_keys(Q, K, V, z, dO, LSE, O, cu_seqlens, k, keys, scale=None):
     oracle's own LSE [H_q, T] and O [T, H_q, d] for the q-heads of those kv-heads.
 
     keys: iterable of (g, j).  Returns a list of dicts: dK [d], dV [d] (summed over the q-heads of
-    group g), dz {h: value} and dz_abs {h: sum_i |dS_ij|}.
+    group g) and dz {h: value}.  D_i is formed from the O passed in (Alg. 2): pass the exact O of
+    Eq. 5 or the stored array a backward kernel was handed.
     """
     Q, K, V, z, dO, LSE, O = _as64(Q), _as64(K), _as64(V), _as64(z), _as64(dO), _as64(LSE), _as64(O)
     T, H_q, d = Q.shape
@@ -527,22 +573,21 @@ def dma_keys(Q, K, V, z, dO, LSE, O, cu_seqlens, k, keys, scale=None):
         a, b = _doc_of(cache.cu, j)
         dK = np.zeros(d)
         dV = np.zeros(d)
-        dz, dz_abs = {}, {}
+        dz = {}
         for h in range(g * G, (g + 1) * G):
             e = int(cache.get(h, a, b)[j - a])
             rows = np.arange(j, e)
             if rows.size == 0:
-                dz[h] = dz_abs[h] = 0.0
+                dz[h] = 0.0
                 continue
             s = scale * (Q[rows, h] @ K[j, g]) + z[h, j]
             p = np.exp(s - LSE[h, rows])
             D = (dO[rows, h] * O[rows, h]).sum(axis=1)
             ds = p * (dO[rows, h] @ V[j, g] - D)
             dz[h] = float(ds.sum())
-            dz_abs[h] = float(np.abs(ds).sum())
             dV += p @ dO[rows, h]
             dK += scale * (ds @ Q[rows, h])
-        out.append(dict(dK=dK, dV=dV, dz=dz, dz_abs=dz_abs))
+        out.append(dict(dK=dK, dV=dV, dz=dz))
     return out
 
 

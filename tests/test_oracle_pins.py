@@ -328,6 +328,174 @@ def test_sampled_rows_and_keys_match_dense_oracle():
             assert val == pytest.approx(dz[h, j], abs=1e-12)
 
 
+# ----------------------------------------------------------------------------- D_i from a stored O (Alg. 2)
+def _bf16_round(x):
+    """Round-to-nearest-even to 8 significant bits, written out on the bit pattern (a stand-in for a
+    stored low-precision O; independent of the workload module's converter)."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def test_stored_o_equal_to_exact_o_changes_nothing():
+    """Alg. 2's D_i = rowsum(dO o O) equals Eq. 8's sum_j p_ij dp_ij when O is the exact forward
+    result: the O_stored mode must then reproduce the default (a wrong row / head index into
+    O_stored, or D formed before the substitution, fails here)."""
+    n1, n2, k = 23, 30, 5
+    Q, K, V, dO, z = rand_case(n1 + n2, 4, 2, 8, seed=51, ties=True)
+    cu = [0, n1, n1 + n2]
+    O, _ = orc.dma_forward(Q, K, V, z, cu, k)
+    a = orc.dma_backward(Q, K, V, z, dO, cu, k)
+    b = orc.dma_backward(Q, K, V, z, dO, cu, k, O_stored=O, row_chunk=7)
+    for x, y in zip(a, b):
+        assert np.allclose(x, y, atol=1e-13)
+    rows = [(h, i) for h in range(4) for i in (0, 4, n1, n1 + n2 - 1)]
+    for ra, rb in zip(orc.dma_rows(Q, K, V, z, dO, cu, k, rows), orc.dma_rows(Q, K, V, z, dO, cu, k, rows, O_stored=O)):
+        assert np.allclose(ra["dQ"], rb["dQ"], atol=1e-13)
+
+
+def test_stored_o_rounded_shifts_the_gradients_by_the_closed_form():
+    """dS = P o (dP - D) is linear in D.  With a rounded O the row term moves by
+    dD_i = dO_i . (O~_i - O_i), hence exactly: dz_j -= sum_i P_ij dD_i, dQ_i -= scale dD_i sum_j P_ij k_j,
+    dK_j -= scale sum_i P_ij dD_i q_i, and dV does not move.  The shifts are written out with
+    explicit loops over (head, row, kept key); a sign slip, a missing scale or D applied to dV fails."""
+    n, H_q, H_kv, d, k = 26, 4, 2, 8, 4
+    G = H_q // H_kv
+    scale = 1.0 / math.sqrt(d)
+    Q, K, V, dO, z = rand_case(n, H_q, H_kv, d, seed=52)
+    cu = [0, n]
+    O, LSE = orc.dma_forward(Q, K, V, z, cu, k)
+    Or = _bf16_round(O)
+    assert np.abs(Or - O).max() > 1e-4                      # the rounding is visible
+    dQ0, dK0, dV0, dz0 = orc.dma_backward(Q, K, V, z, dO, cu, k)
+    dQ1, dK1, dV1, dz1 = orc.dma_backward(Q, K, V, z, dO, cu, k, O_stored=Or)
+    sdQ, sdK, sdz = np.zeros_like(dQ0), np.zeros_like(dK0), np.zeros_like(dz0)
+    for h in range(H_q):
+        keep = orc.kept_mask_definition(z[h], k)
+        for i in range(n):
+            dD = float(dO[i, h] @ (Or[i, h] - O[i, h]))
+            for j in np.flatnonzero(keep[i]):
+                p = math.exp(scale * float(Q[i, h] @ K[j, h // G]) + z[h, j] - LSE[h, i])
+                sdz[h, j] -= p * dD
+                sdQ[i, h] -= scale * p * dD * K[j, h // G]
+                sdK[j, h // G] -= scale * p * dD * Q[i, h]
+    assert np.allclose(dz1 - dz0, sdz, atol=1e-13) and np.abs(sdz).max() > 1e-5
+    assert np.allclose(dQ1 - dQ0, sdQ, atol=1e-13)
+    assert np.allclose(dK1 - dK0, sdK, atol=1e-13)
+    assert np.array_equal(dV1, dV0)
+    # the one-by-one functions take the same buffer
+    rows = [(h, i) for h in range(H_q) for i in (0, 3, n - 1)]
+    for (h, i), rec in zip(rows, orc.dma_rows(Q, K, V, z, dO, cu, k, rows, O_stored=Or)):
+        assert np.allclose(rec["dQ"], dQ1[i, h], atol=1e-13)
+    keys = [(g, j) for g in range(H_kv) for j in (0, 5, n - 1)]
+    for (g, j), rec in zip(keys, orc.dma_keys(Q, K, V, z, dO, LSE, Or, cu, k, keys)):
+        assert np.allclose(rec["dK"], dK1[j, g], atol=1e-12)
+        for h, val in rec["dz"].items():
+            assert val == pytest.approx(dz1[h, j], abs=1e-12)
+
+
+def test_summand_masses_of_dk_and_dv_match_triple_loops():
+    """abs_out["dK"] = scale sum_i |dS_ij| |q_ic| and abs_out["dV"] = sum_i P_ij |dO_ic| (summed over
+    the q-heads of the kv-head): the yardsticks a test may add to the tolerance of dK / dV for keep
+    windows of one to three keys.  Recomputed here with scalar loops from the scalar brute force's
+    quantities; a missing scale, |.| in the wrong place or a head not summed fails."""
+    n, H_q, H_kv, d, k = 14, 2, 1, 3, 3
+    scale = 0.7
+    Q, K, V, dO, z = rand_case(n, H_q, H_kv, d, seed=53)
+    mass = {}
+    orc.dma_backward(Q, K, V, z, dO, [0, n], k, scale=scale, abs_out=mass)
+    mK = [[0.0] * d for _ in range(n)]
+    mV = [[0.0] * d for _ in range(n)]
+    for h in range(H_q):
+        for i in range(n):
+            cand = sorted(range(i + 1), key=lambda j: (-z[h][j], j))[:k]
+            s = {j: scale * sum(Q[i, h, c] * K[j, 0, c] for c in range(d)) + z[h, j] for j in cand}
+            m = max(s.values())
+            tot = sum(math.exp(v - m) for v in s.values())
+            p = {j: math.exp(s[j] - m) / tot for j in cand}
+            dp = {j: sum(dO[i, h, c] * V[j, 0, c] for c in range(d)) for j in cand}
+            dot = sum(p[j] * dp[j] for j in cand)
+            for j in cand:
+                ds = p[j] * (dp[j] - dot)
+                for c in range(d):
+                    mK[j][c] += scale * abs(ds) * abs(Q[i, h, c])
+                    mV[j][c] += p[j] * abs(dO[i, h, c])
+    assert np.allclose(mass["dK"][:, 0], np.array(mK), atol=1e-13)
+    assert np.allclose(mass["dV"][:, 0], np.array(mV), atol=1e-13)
+    # and they bound the gradients they accompany
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, [0, n], k, scale=scale)
+    assert (np.abs(dK) <= mass["dK"] + 1e-12).all() and (np.abs(dV) <= mass["dV"] + 1e-12).all()
+
+
+# ----------------------------------------------------------------------------- caller-supplied attention bias
+@pytest.mark.parametrize("Hb,per_token", [(4, True), (1, True), (4, False), (1, False)])
+def test_bias_equals_sdpa_attn_mask_and_its_autograd(Hb, per_token):
+    """With k >= n everything causal is kept, so z + bias is an ordinary additive attn_mask of torch's
+    SDPA: O, dQ, dK, dV and the bias gradient (reduced over the broadcast dimensions by autograd) must
+    match, for a bias per (head, token), shared by the heads, indexed by the position in the document
+    (shared by the two documents), or both.  A bias dropped from the backward, added twice, or summed
+    over the wrong axis fails."""
+    n, H_q, H_kv, d = 19, 4, 2, 8
+    G = H_q // H_kv
+    Q, K, V, dO, z = rand_case(2 * n, H_q, H_kv, d, seed=61)
+    cu = [0, n, 2 * n]
+    r = np.random.default_rng(62)
+    braw = r.standard_normal((Hb, 2 * n if per_token else n))
+    bias = orc.expand_bias(braw, H_q, cu, per_token)
+    O, _ = orc.dma_forward(Q, K, V, z, cu, 10 * n, bias=bias)
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, cu, 10 * n, bias=bias)
+    dbias = orc.bias_backward(dz, Hb, cu, per_token, n_max=n)
+    tb = torch.tensor(braw, requires_grad=True)
+    tq, tk, tv = (torch.tensor(x, requires_grad=True) for x in (Q, K, V))
+    outs = []
+    for doc in range(2):
+        a, b = cu[doc], cu[doc + 1]
+        brow = tb[:, a:b] if per_token else tb                           # [Hb, n]
+        m = torch.tensor(z[:, a:b])[:, None, :] + brow[:, None, :].expand(Hb, n, n)      # [H_q, n, n] by broadcast
+        m = m + torch.triu(torch.full((n, n), float("-inf"), dtype=torch.float64), 1)
+        q = tq[a:b].permute(1, 0, 2)[None]
+        kk = tk[a:b].permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+        vv = tv[a:b].permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+        outs.append(torch.nn.functional.scaled_dot_product_attention(q, kk, vv, attn_mask=m[None])[0].permute(1, 0, 2))
+    to = torch.cat(outs)
+    to.backward(torch.tensor(dO))
+    assert np.allclose(O, to.detach().numpy(), atol=1e-12)
+    assert np.allclose(dQ, tq.grad.numpy(), atol=1e-12) and np.allclose(dK, tk.grad.numpy(), atol=1e-12)
+    assert np.allclose(dV, tv.grad.numpy(), atol=1e-12)
+    assert dbias.shape == braw.shape and np.allclose(dbias, tb.grad.numpy(), atol=1e-12)
+
+
+def test_bias_does_not_move_the_kept_set_and_zero_bias_changes_nothing():
+    """The selection ranks the content scores z alone (Eq. 4): a bias that would reorder z + b must leave
+    the kept set where it is (exact zeros of P in the same places), and b = 0 reproduces the unbiased
+    result.  Finite differences over the bias confirm dz as its gradient on a sparse window."""
+    n, H_q, H_kv, d, k = 24, 2, 1, 6, 4
+    Q, K, V, dO, z = rand_case(n, H_q, H_kv, d, seed=63)
+    cu = [0, n]
+    bias = np.random.default_rng(64).standard_normal((H_q, n)) * 5.0      # large enough to reorder z + b
+    O0, L0 = orc.dma_forward(Q, K, V, z, cu, k)
+    Oz, Lz = orc.dma_forward(Q, K, V, z, cu, k, bias=np.zeros((H_q, n)))
+    assert np.array_equal(O0, Oz) and np.array_equal(L0, Lz)
+    Ob, Lb = orc.dma_forward(Q, K, V, z, cu, k, bias=bias)
+    # same result as gathering each row's kept keys (chosen on z) and applying softmax with z + b
+    scale = 1.0 / math.sqrt(d)
+    for h in range(H_q):
+        keep = orc.kept_mask_definition(z[h], k)
+        for i in range(n):
+            idx = np.flatnonzero(keep[i])
+            sc = scale * (K[idx, 0] @ Q[i, h]) + z[h, idx] + bias[h, idx]
+            w = np.exp(sc - sc.max()); w /= w.sum()
+            assert np.allclose(Ob[i, h], w @ V[idx, 0], atol=1e-13)
+    dQ, dK, dV, dz = orc.dma_backward(Q, K, V, z, dO, cu, k, bias=bias)
+    eps = 1e-6
+    for (h, j) in [(0, 0), (1, 3), (0, n - 2), (1, n - 1)]:
+        bp, bm = bias.copy(), bias.copy()
+        bp[h, j] += eps; bm[h, j] -= eps
+        fp = (orc.dma_forward(Q, K, V, z, cu, k, bias=bp)[0] * dO).sum()
+        fm = (orc.dma_forward(Q, K, V, z, cu, k, bias=bm)[0] * dO).sum()
+        assert (fp - fm) / (2 * eps) == pytest.approx(dz[h, j], abs=1e-7)
+
+
 # ----------------------------------------------------------------------------- without the causal restriction
 @pytest.mark.parametrize("ties", [False, True])
 def test_noncausal_is_plain_attention_over_the_gathered_top_k(ties):
