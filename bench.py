@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, published
+HBM_PEAK_GBS = 8000.0               # MI355X HBM3E, published
 HEADLINE = "cfg3"
 
 
@@ -96,94 +97,10 @@ def measured_traffic(kernel):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default=HEADLINE, help="cfg1..cfg5 (default: the headline shape)")
-    ap.add_argument("--k", type=int, default=0, help="override the keep-window (cfg4 sweep)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--structured-z", action="store_true",
-                    help="reported-only variant: scores supplied by the caller, even heads increasing with the "
-                         "key index (a local band: each row keeps its k latest keys), odd heads i.i.d.")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; rerun with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def clean_pair_count(inp, eg, BQ=256):
+    """Kept (row, key) pairs whose key is resident for ALL rows of the pair's 256-row block (the pairs
+    dkv_kernel<clean> works on), summed over heads; counted on the host from the expiry array."""
     import numpy as np
-    import torch
-    from paper_2508_02124_amd import binding as B
-    from paper_2508_02124_amd import workloads as wlmod
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_harness import DeviceCase
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    wl = wlmod.CONFIGS[args.config]
-    if args.k:
-        wl = wl.with_k(args.k)
-    inp = wlmod.make_inputs(wl)
-    dev = torch.device("cuda:0")
-    z_override = None
-    if args.structured_z:
-        rz = np.random.default_rng(wl.seed + 7)
-        z_override = rz.uniform(0.05, 1.0, size=(wl.H_q, inp.T)).astype(np.float32)
-        z_override[0::2] = (0.05 + 0.95 * (np.arange(inp.T, dtype=np.float64) + 1) / inp.T).astype(np.float32)[None, :]
-    case = DeviceCase(inp, dev, z_override=z_override)
-    seqlens = np.diff(inp.cu_seqlens)
-    nact = n_active(seqlens, wl.k)
-    per_pair = 14 if wl.backward else 4
-    flops = float(per_pair) * wl.d * nact * wl.H_q
-
-    def step():
-        case.mask_gen()
-        case.fwd()
-        if wl.backward:
-            case.bwd()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if args.calibration_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)  # reads 256 MiB, writes 256 MiB: the yardstick for the HBM byte counters
-        torch.cuda.synchronize()
-        del src, dst
-
-    # Stage events are recorded inside the timed region, on every fourth step (each armed step
-    # records 20 events between the launches, which costs 0.05-0.15 ms of its 3.5 ms at the headline
-    # shape; the kernels' durations do not depend on it).
-    nst = len(B.STAGES)
-    armed = [i for i in range(args.steps) if i % 4 == 0]
-    evsets = [HipEvents(2 * nst) for _ in armed]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        B.dma_profile_events(evsets[armed.index(i)].arr if i in armed else None)
-        step()
-    B.dma_profile_events(None)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    used = [s for s in range(nst) if wl.backward or s <= 4]
-    stage_ms = {B.STAGES[s]: float(np.mean([e.elapsed(2 * s, 2 * s + 1) for e in evsets])) for s in used}
-    for e in evsets:
-        e.destroy()
-    mask_ms = sum(stage_ms[n] for n in ("z", "sort", "expiry", "plan"))
-    fwd_ms = stage_ms["fwd"]
-    bwd_ms = sum(v for n, v in stage_ms.items() if n.startswith("bwd")) if wl.backward else 0.0
-
-    # dominant kernel and its algorithmic FLOPs per launch (per kept pair: forward 4d = S and PV;
-    # dQ kernel 6d = S, dP, dQ; key-stationary kernel 8d = S, dP, dV, dK on the pairs of its launch)
-    eg = case.host("expiry").astype(np.int64)
-    BQ = 256
     clean_pairs = 0
     for a, b in zip(inp.cu_seqlens[:-1], inp.cu_seqlens[1:]):
         a, b = int(a), int(b)
@@ -199,17 +116,195 @@ def main():
         rows_last = n - ((n - 1) // BQ) * BQ                  # rows of the (possibly ragged) last block
         pairs = nb * BQ - np.where((nb > 0) & (last_full == (n - 1) // BQ), BQ - rows_last, 0)
         clean_pairs += int(pairs.sum())
+    return clean_pairs
+
+
+def time_workload(wl, steps, warmup, dev, structured_z=False, calibration_copy=False):
+    """Times `steps` steps (mask_gen + fwd [+ bwd]) of one workload.  Returns the timing record and the
+    device case.  Stage events are recorded inside the timed region on every second step (an armed
+    step records 20 events between the launches, 0.05-0.15 ms of a 3.3 ms step; the kernels'
+    durations do not depend on it); per-step durations come from one event per step boundary."""
+    import numpy as np
+    import torch
+    from paper_2508_02124_amd import binding as B
+    from paper_2508_02124_amd import workloads as wlmod
+    from paper_2508_02124_amd.device_case import DeviceCase
+    inp = wlmod.make_inputs(wl)
+    z_override = None
+    if structured_z:
+        rz = np.random.default_rng(wl.seed + 7)
+        z_override = rz.uniform(0.05, 1.0, size=(wl.H_q, inp.T)).astype(np.float32)
+        z_override[0::2] = (0.05 + 0.95 * (np.arange(inp.T, dtype=np.float64) + 1) / inp.T).astype(np.float32)[None, :]
+    case = DeviceCase(inp, dev, z_override=z_override)
+    seqlens = np.diff(inp.cu_seqlens)
+    nact = n_active(seqlens, wl.k)
+    per_pair = 14 if wl.backward else 4
+    flops = float(per_pair) * wl.d * nact * wl.H_q
+
+    def step():
+        case.mask_gen()
+        case.fwd()
+        if wl.backward:
+            case.bwd()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    if calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 256 MiB, writes 256 MiB: the yardstick for the HBM byte counters
+        torch.cuda.synchronize()
+        del src, dst
+
+    nst = len(B.STAGES)
+    armed = [i for i in range(steps) if i % 2 == 0]
+    evsets = [HipEvents(2 * nst) for _ in armed]
+    bounds = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    bounds[0].record()
+    for i in range(steps):
+        B.dma_profile_events(evsets[armed.index(i)].arr if i in armed else None)
+        step()
+        bounds[i + 1].record()
+    B.dma_profile_events(None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    step_ms = [bounds[i].elapsed_time(bounds[i + 1]) for i in range(steps)]
+
+    used = [s for s in range(nst) if wl.backward or s <= 4]
+    samples = {B.STAGES[s]: [e.elapsed(2 * s, 2 * s + 1) for e in evsets] for s in used}
+    for e in evsets:
+        e.destroy()
+    rec = {
+        "ms_per_step": ms_per_step,
+        "step_ms_median": float(np.median(step_ms)), "step_ms_min": float(np.min(step_ms)),
+        "stage_ms": {n: float(np.mean(v)) for n, v in samples.items()},
+        "stage_ms_median": {n: float(np.median(v)) for n, v in samples.items()},
+        "stage_ms_min": {n: float(np.min(v)) for n, v in samples.items()},
+        "flops": flops, "nact": int(nact), "seqlens": seqlens,
+    }
+    st = rec["stage_ms"]
+    rec["mask_gen_ms"] = sum(st[n] for n in ("z", "sort", "expiry", "plan"))
+    rec["fwd_ms"] = st["fwd"]
+    rec["bwd_ms"] = sum(v for n, v in st.items() if n.startswith("bwd")) if wl.backward else 0.0
+    return rec, case, inp
+
+
+def roofline_objects(wl, inp, case, rec, with_traffic):
+    """Roofline records of the kernels of the step.  MFMA kernels: algorithmic FLOPs of the launch
+    (per kept pair: forward 4d = S and PV; dQ kernel 6d = S, dP, dQ; key-stationary kernel 8d = S, dP,
+    dV, dK on the pairs of its launch) / mean launch duration / 2.5 PFLOP/s.  The score kernel of
+    mask generation is HBM-bound: bytes of V read once + z and z / scale written, / duration / 8 TB/s
+    (its stage also holds the block-table launch, a few microseconds)."""
+    import numpy as np
+    stage_ms = rec["stage_ms"]
+    nact = rec["nact"]
     stage_flops = {"fwd": 4.0 * wl.d * nact * wl.H_q}
     if wl.backward:
+        eg = case.host("expiry").astype(np.int64)
         stage_flops["bwd_dq"] = 6.0 * wl.d * nact * wl.H_q
-        stage_flops["bwd_dkv"] = 8.0 * wl.d * clean_pairs
-    dom = max(stage_flops, key=lambda n: stage_ms[n])
-    achieved = stage_flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
+        stage_flops["bwd_dkv"] = 8.0 * wl.d * clean_pair_count(inp, eg)
     kernel_names = {"fwd": "fwd_kernel", "bwd_dq": "dq_kernel", "bwd_dkv": "dkv_kernel<clean>"}
-    roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": measured_traffic(kernel_names[dom]) if wl.name == HEADLINE and not args.k else None,
-                "launch_ms": stage_ms[dom], "flops_per_launch": stage_flops[dom]}
+    objs = {}
+    for st, fl in stage_flops.items():
+        achieved = fl / (stage_ms[st] * 1e-3) / 1e12
+        objs[kernel_names[st]] = {
+            "bound": "mfma", "kernel": kernel_names[st], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": measured_traffic(kernel_names[st]) if with_traffic else None,
+            "launch_ms": stage_ms[st], "launch_ms_median": rec["stage_ms_median"][st],
+            "launch_ms_min": rec["stage_ms_min"][st], "flops_per_launch": fl}
+    zbytes = inp.T * wl.H_kv * wl.d * 2 + 2 * 4 * wl.H_q * inp.T
+    zach = zbytes / (stage_ms["z"] * 1e-3) / 1e9
+    objs["z_kernel"] = {"bound": "hbm", "kernel": "z_kernel (mask generation, Eq. 3)", "achieved": zach,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": zach / HBM_PEAK_GBS,
+                        "traffic": measured_traffic("z_kernel") if with_traffic else None,
+                        "launch_ms": stage_ms["z"], "launch_ms_median": rec["stage_ms_median"]["z"],
+                        "launch_ms_min": rec["stage_ms_min"]["z"], "bytes_per_launch": zbytes}
+    dom = max(stage_flops, key=lambda n: stage_ms[n])
+    return kernel_names[dom], objs
+
+
+SWEEP = [("cfg2", 0), ("cfg5", 0), ("cfg3", 512), ("cfg3", 1024), ("cfg3", 0),
+         ("cfg4", 1024), ("cfg4", 4096), ("cfg4", 16384), ("cfg4", 65536)]
+
+
+def run_sweep(args, dev):
+    """The benchmark spec's other shapes and the mask-density sweep of cfg4 (forward only), one record each:
+    time must follow the number of kept pairs (k L - k^2 / 2 per head), not L^2."""
+    import torch
+    from paper_2508_02124_amd import workloads as wlmod
+    rows = []
+    for name, k in SWEEP:
+        wl = wlmod.CONFIGS[name]
+        if k:
+            wl = wl.with_k(k)
+        steps = max(3, min(args.steps, 10 if name == "cfg4" else args.steps))
+        rec, case, inp = time_workload(wl, steps, args.warmup, dev)
+        kname, objs = roofline_objects(wl, inp, case, rec, False)
+        rows.append({
+            "workload": f"{wl.name}: T={inp.T} docs={len(rec['seqlens'])} H_q={wl.H_q} H_kv={wl.H_kv} d={wl.d} k={wl.k} "
+                        f"{'fwd+bwd' if wl.backward else 'fwd'}",
+            "kept_pairs_all_heads": rec["nact"] * wl.H_q, "steps": steps,
+            "ms_per_step": rec["ms_per_step"], "step_ms_median": rec["step_ms_median"], "step_ms_min": rec["step_ms_min"],
+            "mask_gen_ms": rec["mask_gen_ms"], "fwd_ms": rec["fwd_ms"], "bwd_ms": rec["bwd_ms"],
+            "stage_ms": rec["stage_ms"],
+            "effective_tflops": rec["flops"] / (rec["ms_per_step"] * 1e-3) / 1e12,
+            "fwd_kernel_tflops": objs["fwd_kernel"]["achieved"],
+            "ns_per_kept_pair_fwd": rec["fwd_ms"] * 1e6 / (rec["nact"] * wl.H_q),
+        })
+        print(f"[sweep] {rows[-1]['workload']}: {rows[-1]['ms_per_step']:.3f} ms/step, fwd {rows[-1]['fwd_ms']:.3f} ms",
+              file=sys.stderr, flush=True)
+        del case, inp
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "dma_shape_sweep", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "sweep": rows}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default=HEADLINE, help="cfg1..cfg5 (default: the headline shape)")
+    ap.add_argument("--k", type=int, default=0, help="override the keep-window (cfg4 sweep)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline line: cfg2, cfg5, cfg3 at k = 512 / 1024 / 2048 and the cfg4 "
+                         "mask-density sweep k = 1K / 4K / 16K / 64K, one record each in one JSON line")
+    ap.add_argument("--structured-z", action="store_true",
+                    help="reported-only variant: scores supplied by the caller, even heads increasing with the "
+                         "key index (a local band: each row keeps its k latest keys), odd heads i.i.d.")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2508_02124_amd import binding as B
+    from paper_2508_02124_amd import workloads as wlmod
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    if args.sweep:
+        run_sweep(args, dev)
+        return
+    wl = wlmod.CONFIGS[args.config]
+    if args.k:
+        wl = wl.with_k(args.k)
+    rec, case, inp = time_workload(wl, args.steps, args.warmup, dev, args.structured_z, args.calibration_copy)
+    ms_per_step, stage_ms, flops, nact, seqlens = rec["ms_per_step"], rec["stage_ms"], rec["flops"], rec["nact"], rec["seqlens"]
+    mask_ms, fwd_ms, bwd_ms = rec["mask_gen_ms"], rec["fwd_ms"], rec["bwd_ms"]
+    dom_kernel, rooflines = roofline_objects(wl, inp, case, rec, wl.name == HEADLINE and not args.k)
+    roofline = rooflines[dom_kernel]
 
     value = flops / (ms_per_step * 1e-3) / 1e12
 
@@ -256,8 +351,11 @@ def main():
         "mask_gen_ms": mask_ms, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "fwd_bwd_ms": fwd_ms + bwd_ms,
         "fwd_bwd_tflops": flops / ((fwd_ms + bwd_ms) * 1e-3) / 1e12,
-        "stage_ms": stage_ms, "algorithmic_gflop": flops / 1e9,
+        "step_ms_median": rec["step_ms_median"], "step_ms_min": rec["step_ms_min"],
+        "stage_ms": stage_ms, "stage_ms_median": rec["stage_ms_median"], "stage_ms_min": rec["stage_ms_min"],
+        "algorithmic_gflop": flops / 1e9,
         "roofline": roofline,
+        "rooflines": rooflines,
     }
     if wl.backward:
         # not part of the step: the gradient of the content scores (dz -> dW, dA, dV += dVz), HBM-bound

@@ -40,7 +40,8 @@ extern "C" {
 typedef enum {
   DMA_OK = 0,
   DMA_EINVAL = -1,       /* null pointer, misaligned pointer, T<=0, k<=0, n_docs<=0, H_q % H_kv != 0 */
-  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, more than 32 heads for the cross-head scores */
+  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, more than 32 heads for the cross-head scores,
+                            bf16 dma_fwd / dma_bwd with T >= 2^24 or K (or V) larger than 4 GiB            */
   DMA_EWORKSPACE = -3,   /* ws_bytes smaller than dma_workspace_bytes() */
   DMA_EHIP = -4          /* a launch failed (hipGetLastError) */
 } dma_status;
@@ -69,6 +70,28 @@ size_t dma_mask_bytes(const dma_shape* shape);
 size_t dma_workspace_bytes(const dma_shape* shape);
 
 /*
+ * Where the parts of the mask plan lie, for tools and tests that inspect what dma_mask_gen wrote
+ * (the occupancy structure of Section 4.2: per block of query rows, the keys resident for the whole
+ * block -- one slot column each -- and the keys that enter or expire inside it).  The attention
+ * entry points need none of this.  `out` is a HOST pointer; offsets are bytes from the start of the
+ * mask buffer.  Returns DMA_OK or the error of an invalid shape.
+ *   blocks         int32[nblk_cap][4]: {document, first row, end row, document start}; document -1 past the end
+ *   slot_table     int32[H_q][nblk_cap][kpad]: resident key of each slot column, -1 = none
+ *   partial_count  int32[H_q][nblk_cap];  partial_list int32[H_q][nblk_cap][max_partial]
+ *   header         int32[16], [0] = number of blocks;  zq float[H_q][T] = z / softmax_scale
+ */
+typedef struct {
+  int32_t block_rows;   /* query rows per block                          */
+  int32_t group_cols;   /* slot columns per key-stationary workgroup     */
+  int32_t max_partial;  /* capacity of a block's partial list            */
+  int32_t nblk_cap;     /* rows of the block table: T / block_rows + n_docs */
+  int32_t kpad;         /* slot-table row length                         */
+  int32_t reserved;
+  uint64_t off_header, off_zq, off_blocks, off_slot_table, off_partial_count, off_partial_list, total;
+} dma_mask_layout;
+int dma_mask_describe(const dma_shape* shape, dma_mask_layout* out);
+
+/*
  * Mask generation (Eq. 3, Eq. 4, Listing 1's mask block).
  *   V          in   [T, H_kv, d]
  *   W, A       in   per-q-head projection vector and gate.  W == NULL means the
@@ -91,6 +114,30 @@ size_t dma_workspace_bytes(const dma_shape* shape);
 int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
                  const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,
                  void* mask, void* stream);
+
+/*
+ * Mask generation with a further, caller-supplied attention bias (Section 1, "Kernel Design": the
+ * kernel takes masks and biases with batch, head and query broadcasting).  The bias holds one value
+ * per key, broadcast over the query rows; it is added to the scores of the kept pairs next to z,
+ *     S_ij = scale q_i . k_j + z[h, j] + bias[h, j],
+ * while the kept sets are selected on z alone (Eq. 4 ranks the content scores).  Everything else is
+ * dma_mask_gen; dma_fwd / dma_bwd are called as usual with the mask written here.
+ *   bias            in  float, finite (a large negative value acts as a key mask)
+ *   bias_heads      H_q: one row per q-head; 1: one row shared by all heads (head broadcast)
+ *   bias_per_token  != 0: bias is [bias_heads, T], packed like z;
+ *                   == 0: bias is [bias_heads, shape->max_seqlen], indexed by the key's position in
+ *                   its document and shared by all documents (batch broadcast); max_seqlen must be
+ *                   set and no document may be longer
+ * z and the bias enter the score as a sum, so the dz of dma_bwd is also the gradient with respect
+ * to the bias as applied; dma_bias_bwd reduces it over the heads and documents that share an entry:
+ *   dbias out [bias_heads, T] or [bias_heads, max_seqlen] float, fully overwritten (no atomics).
+ * A bias per (query, key) pair has no per-key structure and is not supported.
+ */
+int dma_mask_gen_bias(const dma_shape* shape, const void* V, const float* W, const float* A,
+                      const int32_t* cu_seqlens, const float* bias, int32_t bias_heads, int32_t bias_per_token,
+                      float* z, int32_t* expiry, int32_t* topk_idx, void* mask, void* stream);
+int dma_bias_bwd(const dma_shape* shape, const float* dz, const int32_t* cu_seqlens, int32_t bias_heads,
+                 int32_t bias_per_token, float* dbias, void* stream);
 
 /*
  * Forward (Eq. 5-6; online softmax as in Alg. 1, query-stationary).

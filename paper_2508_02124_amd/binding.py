@@ -26,6 +26,16 @@ class DmaShape(ctypes.Structure):
     ]
 
 
+class DmaMaskLayout(ctypes.Structure):
+    _fields_ = [
+        ("block_rows", ctypes.c_int32), ("group_cols", ctypes.c_int32), ("max_partial", ctypes.c_int32),
+        ("nblk_cap", ctypes.c_int32), ("kpad", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("off_header", ctypes.c_uint64), ("off_zq", ctypes.c_uint64), ("off_blocks", ctypes.c_uint64),
+        ("off_slot_table", ctypes.c_uint64), ("off_partial_count", ctypes.c_uint64),
+        ("off_partial_list", ctypes.c_uint64), ("total", ctypes.c_uint64),
+    ]
+
+
 class DmaError(RuntimeError):
     def __init__(self, status, what):
         super().__init__(f"{what}: {strerror(status)} (status {status})")
@@ -49,8 +59,14 @@ def lib():
         L.dma_mask_bytes.restype = sz
         L.dma_workspace_bytes.argtypes = [shp]
         L.dma_workspace_bytes.restype = sz
+        L.dma_mask_describe.argtypes = [shp, ctypes.POINTER(DmaMaskLayout)]
+        L.dma_mask_describe.restype = i32
         L.dma_mask_gen.argtypes = [shp] + [vp] * 9
         L.dma_mask_gen.restype = i32
+        L.dma_mask_gen_bias.argtypes = [shp] + [vp] * 5 + [i32, i32] + [vp] * 5
+        L.dma_mask_gen_bias.restype = i32
+        L.dma_bias_bwd.argtypes = [shp, vp, vp, i32, i32, vp, vp]
+        L.dma_bias_bwd.restype = i32
         L.dma_fwd.argtypes = [shp] + [vp] * 10 + [sz, vp]
         L.dma_fwd.restype = i32
         L.dma_bwd.argtypes = [shp] + [vp] * 15 + [sz, vp]
@@ -135,6 +151,13 @@ def dma_workspace_bytes(shape):
     return int(lib().dma_workspace_bytes(ctypes.byref(shape)))
 
 
+def dma_mask_describe(shape):
+    """The layout of the mask plan (a DmaMaskLayout) for this shape."""
+    out = DmaMaskLayout()
+    _check(lib().dma_mask_describe(ctypes.byref(shape), ctypes.byref(out)), "dma_mask_describe")
+    return out
+
+
 def _check(status, what):
     if status != DMA_OK:
         raise DmaError(status, what)
@@ -143,6 +166,18 @@ def _check(status, what):
 def dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, topk_idx, mask, stream=None):
     _check(lib().dma_mask_gen(ctypes.byref(shape), _ptr(V), _ptr(W), _ptr(A), _ptr(cu_seqlens), _ptr(z),
                               _ptr(expiry), _ptr(topk_idx), _ptr(mask), _stream(stream)), "dma_mask_gen")
+
+
+def dma_mask_gen_bias(shape, V, W, A, cu_seqlens, bias, bias_heads, bias_per_token, z, expiry, topk_idx, mask,
+                      stream=None):
+    _check(lib().dma_mask_gen_bias(ctypes.byref(shape), _ptr(V), _ptr(W), _ptr(A), _ptr(cu_seqlens), _ptr(bias),
+                                   int(bias_heads), int(bool(bias_per_token)), _ptr(z), _ptr(expiry), _ptr(topk_idx),
+                                   _ptr(mask), _stream(stream)), "dma_mask_gen_bias")
+
+
+def dma_bias_bwd(shape, dz, cu_seqlens, bias_heads, bias_per_token, dbias, stream=None):
+    _check(lib().dma_bias_bwd(ctypes.byref(shape), _ptr(dz), _ptr(cu_seqlens), int(bias_heads),
+                              int(bool(bias_per_token)), _ptr(dbias), _stream(stream)), "dma_bias_bwd")
 
 
 def dma_fwd(shape, Q, K, V, z, expiry, mask, cu_seqlens, O, LSE, ws, ws_bytes, stream=None):

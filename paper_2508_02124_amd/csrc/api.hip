@@ -29,6 +29,15 @@ int check_shape(const dma_shape* s) {
   return DMA_OK;
 }
 
+// The bf16 attention kernels address a gathered K / V row as a 32-bit byte offset from the kv-head's
+// first row (row index below 2^24, row pitch below 2^24, K and V at most 4 GiB each).
+int check_gather_limits(const dma_shape& s) {
+  if (s.dtype != DMA_BF16) return DMA_OK;
+  const unsigned long long pitch = (unsigned long long)s.H_kv * s.d * 2;
+  if (s.T >= (1 << 24) || pitch >= (1ull << 24) || (unsigned long long)s.T * pitch > (1ull << 32)) return DMA_EUNSUPPORTED;
+  return DMA_OK;
+}
+
 size_t ws_bytes_for(const dma_shape& s) {
   if (s.dtype == DMA_F32) return align_up((size_t)s.H_q * s.T * 4, 256);
   return ws_layout(s).total;
@@ -57,6 +66,19 @@ size_t dma_workspace_bytes(const dma_shape* shape) {
   return ws_bytes_for(*shape);
 }
 
+int dma_mask_describe(const dma_shape* shape, dma_mask_layout* out) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!out) return DMA_EINVAL;
+  const PlanLayout L = plan_layout(*shape);
+  out->block_rows = BQ; out->group_cols = SG; out->max_partial = MAXPART;
+  out->nblk_cap = L.nblk_cap; out->kpad = L.kpad; out->reserved = 0;
+  out->off_header = L.off_hdr; out->off_zq = L.off_zq; out->off_blocks = L.off_blk;
+  out->off_slot_table = L.off_slot; out->off_partial_count = L.off_pcnt; out->off_partial_list = L.off_plist;
+  out->total = L.total;
+  return DMA_OK;
+}
+
 int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
                  const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,
                  void* mask, void* stream) {
@@ -67,6 +89,33 @@ int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const fl
   if (!aligned16(V) || !aligned16(W) || !aligned16(z) || !aligned16(expiry) || !aligned16(mask)) return DMA_EINVAL;
   Ptrs p = make_ptrs(shape, mask);
   return launch_mask_gen(p, V, W, A, cu_seqlens, z, expiry, topk_idx, (hipStream_t)stream);
+}
+
+static int check_bias(const dma_shape* s, const float* bias, int bias_heads, int bias_per_token) {
+  if (!bias || !aligned16(bias)) return DMA_EINVAL;
+  if (bias_heads != 1 && bias_heads != s->H_q) return DMA_EINVAL;
+  if (!bias_per_token && s->max_seqlen <= 0) return DMA_EINVAL;  // the shared row's length must be stated
+  return DMA_OK;
+}
+
+int dma_mask_gen_bias(const dma_shape* shape, const void* V, const float* W, const float* A,
+                      const int32_t* cu_seqlens, const float* bias, int32_t bias_heads, int32_t bias_per_token,
+                      float* z, int32_t* expiry, int32_t* topk_idx, void* mask, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if ((rc = check_bias(shape, bias, bias_heads, bias_per_token)) != DMA_OK) return rc;
+  if ((rc = dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, topk_idx, mask, stream)) != DMA_OK) return rc;
+  Ptrs p = make_ptrs(shape, mask);
+  return launch_bias_add(p, bias, bias_heads, bias_per_token != 0, cu_seqlens, (hipStream_t)stream);
+}
+
+int dma_bias_bwd(const dma_shape* shape, const float* dz, const int32_t* cu_seqlens, int32_t bias_heads,
+                 int32_t bias_per_token, float* dbias, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!dz || !cu_seqlens || !aligned16(dz)) return DMA_EINVAL;
+  if ((rc = check_bias(shape, dbias, bias_heads, bias_per_token)) != DMA_OK) return rc;
+  return launch_bias_bwd(*shape, dz, bias_heads, bias_per_token != 0, cu_seqlens, dbias, (hipStream_t)stream);
 }
 
 int dma_fwd(const dma_shape* shape, const void* Q, const void* K, const void* V, const float* z,
@@ -80,6 +129,7 @@ int dma_fwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(z) || !aligned16(LSE) ||
       !aligned16(mask))
     return DMA_EINVAL;
+  if ((rc = check_gather_limits(*shape)) != DMA_OK) return rc;
   Ptrs p = make_ptrs(shape, mask);
   if (shape->dtype == DMA_F32)
     return launch_fwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, z, expiry, cu_seqlens, (float*)O, LSE,
@@ -100,6 +150,7 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
       !aligned16(ws))
     return DMA_EINVAL;
   if (!ws || ws_bytes < ws_bytes_for(*shape)) return DMA_EWORKSPACE;
+  if ((rc = check_gather_limits(*shape)) != DMA_OK) return rc;
   Ptrs p = make_ptrs(shape, mask);
   if (shape->dtype == DMA_F32)
     return launch_bwd_f32(p, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, (const float*)dO, LSE,
@@ -135,11 +186,14 @@ int dma_scores_xhead_bwd(const dma_shape* shape, const void* V, const float* Del
   return launch_xhead_bwd(*shape, V, Delta, A, dz, dDelta, dA, dV, accumulate != 0, (hipStream_t)stream);
 }
 
+static size_t decode_list_bytes(const dma_shape& s) {
+  const size_t kcap = (size_t)(s.k < s.T ? s.k : s.T);
+  return align_up((size_t)s.n_docs * s.H_q * kcap * 4, 256);
+}
+
 size_t dma_decode_kept_bytes(const dma_shape* shape) {
   if (check_shape(shape) != DMA_OK) return 0;
-  const size_t kcap = (size_t)(shape->k < shape->T ? shape->k : shape->T);
-  return align_up((size_t)shape->n_docs * shape->H_q * kcap * 4, 256) + align_up(decode_part_floats(*shape) * 4, 256) +
-         align_up(decode_sel_words(*shape) * 4, 256);
+  return decode_list_bytes(*shape) + decode_scratch_bytes(*shape);
 }
 
 int dma_decode(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
@@ -151,7 +205,8 @@ int dma_decode(const dma_shape* shape, const void* q, const void* K, const void*
     return DMA_EINVAL;
   if (!kept || kept_bytes < dma_decode_kept_bytes(shape)) return DMA_EWORKSPACE;
   const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->d);
-  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, nullptr, 0, o, lse, kept, (hipStream_t)stream);
+  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, nullptr, 0, o, lse, kept,
+                       reinterpret_cast<char*>(kept) + decode_list_bytes(*shape), (hipStream_t)stream);
 }
 
 int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
@@ -165,7 +220,7 @@ int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const 
   if (!kept || kept_bytes < dma_decode_kept_bytes(shape)) return DMA_EWORKSPACE;
   const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->d);
   return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, seq_lens, refresh == 0, o, lse, kept,
-                       (hipStream_t)stream);
+                       reinterpret_cast<char*>(kept) + decode_list_bytes(*shape), (hipStream_t)stream);
 }
 
 void dma_profile_events(void** events) { dma::g_stage_events = events; }
@@ -184,13 +239,13 @@ const char* dma_strerror(int status) {
   switch (status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
-    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: K and V at most 4 GiB each, fewer than 2^24 tokens)";
     case DMA_EWORKSPACE: return "workspace missing or smaller than dma_workspace_bytes()";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";
   }
 }
 
-int dma_version(void) { return 120; }
+int dma_version(void) { return 130; }
 
 }  // extern "C"

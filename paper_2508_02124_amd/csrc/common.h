@@ -122,6 +122,9 @@ struct Ptrs {  // everything the kernels need, resolved by the host API
 
 int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A, const int32_t* cu,
                     float* z, int32_t* expiry, int32_t* topk_idx, hipStream_t st);
+int launch_bias_add(const Ptrs& p, const float* bias, int bias_heads, int per_token, const int32_t* cu, hipStream_t st);
+int launch_bias_bwd(const dma_shape& s, const float* dz, int bias_heads, int per_token, const int32_t* cu, float* dbias,
+                    hipStream_t st);
 int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const float* z,
                const int32_t* expiry, const int32_t* cu, void* O, float* LSE, hipStream_t st);
 int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const void* O, const void* dO,
@@ -142,9 +145,10 @@ int launch_xhead_bwd(const dma_shape& s, const void* V, const float* Delta, cons
 
 size_t decode_part_floats(const dma_shape& s);
 size_t decode_sel_words(const dma_shape& s);
+size_t decode_scratch_bytes(const dma_shape& s);   // partial outputs + selection words of one call
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
                   const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
-                  hipStream_t st);
+                  void* part_and_sel, hipStream_t st);
 
 int launch_probe_mfma(float* sink, int nwg, int iters, hipStream_t st);
 int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);

@@ -20,7 +20,7 @@ __device__ __forceinline__ float wave_max(float x) {
 // (D_t = dO_t . O_t, dQ_t), with P recomputed from LSE.
 template <int D, int MODE>
 __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
-                                                     const float* __restrict__ V, const float* __restrict__ z,
+                                                     const float* __restrict__ V, const float* __restrict__ zq,
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
                                                      int n_docs, int causal, int T, int H_q, int H_kv, float scale,
                                                      float* __restrict__ O, float* __restrict__ LSE,
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
         const float* kr = K + ((size_t)j * H_kv + g) * D;
         float s = 0.f;
         for (int c = 0; c < D; c++) s = fmaf(qs[c], kr[c], s);
-        m = fmaxf(m, s * scale + z[(size_t)h * T + j]);
+        m = fmaxf(m, (s + zq[(size_t)h * T + j]) * scale);
       }
     }
     m = wave_max(m);
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
       const float* vr = V + ((size_t)j * H_kv + g) * D;
       float s = 0.f;
       for (int c = 0; c < D; c++) s = fmaf(qs[c], kr[c], s);
-      s = s * scale + z[(size_t)h * T + j];
+      s = (s + zq[(size_t)h * T + j]) * scale;  // zq = (z + bias) / scale, as the plan holds it
       if (MODE == 0) {
         const float pr = expf(s - m);
         lsum += pr;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
 // Lane l owns channels l, l + 64, ...; rows are walked in order, so the result is deterministic.
 template <int D>
 __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
-                                                     const float* __restrict__ V, const float* __restrict__ z,
+                                                     const float* __restrict__ V, const float* __restrict__ zq,
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
                                                      int n_docs, int causal, int T, int H_q, int H_kv,
                                                      float scale, const float* __restrict__ LSE,
@@ -117,19 +117,20 @@ __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q
   constexpr int CPL = D / 64;
   const int t = blockIdx.x, g = blockIdx.y, l = threadIdx.x;
   const int G = H_q / H_kv;
-  float kc[CPL], vc[CPL], dk[CPL], dv[CPL];
+  float kc[CPL], vc[CPL];
+  double dk[CPL], dv[CPL];  // sums over up to n rows: accumulated in fp64 so that their rounding stays below 1e-5
 #pragma unroll
   for (int u = 0; u < CPL; u++) {
     kc[u] = K[((size_t)t * H_kv + g) * D + l + 64 * u];
     vc[u] = V[((size_t)t * H_kv + g) * D + l + 64 * u];
-    dk[u] = 0.f;
-    dv[u] = 0.f;
+    dk[u] = 0.0;
+    dv[u] = 0.0;
   }
   for (int hh = 0; hh < G; hh++) {
     const int h = g * G + hh;
     const int e = expiry[(size_t)h * T + t];
-    const float zt = z[(size_t)h * T + t];
-    float dzacc = 0.f;
+    const float zt = zq[(size_t)h * T + t];
+    double dzacc = 0.0;
     int i0 = t, i1 = e;  // rows that keep this key: causal t .. e - 1; otherwise the whole document or none
     if (!causal) {
       const int doc = find_doc(cu, n_docs, t);
@@ -149,33 +150,35 @@ __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q
       }
       s = wave_sum(s);
       dp = wave_sum(dp);
-      const float pr = expf(s * scale + zt - LSE[(size_t)h * T + i]);
+      const float pr = expf((s + zt) * scale - LSE[(size_t)h * T + i]);
       const float ds = pr * (dp - Dws[(size_t)h * T + i]);
       dzacc += ds;
 #pragma unroll
       for (int u = 0; u < CPL; u++) {
-        dk[u] = fmaf(ds, qv[u], dk[u]);
-        dv[u] = fmaf(pr, dov[u], dv[u]);
+        dk[u] += (double)ds * (double)qv[u];
+        dv[u] += (double)pr * (double)dov[u];
       }
     }
-    if (l == 0) dz[(size_t)h * T + t] = dzacc;
+    if (l == 0) dz[(size_t)h * T + t] = (float)dzacc;
   }
 #pragma unroll
   for (int u = 0; u < CPL; u++) {
-    dK[((size_t)t * H_kv + g) * D + l + 64 * u] = dk[u] * scale;
-    dV[((size_t)t * H_kv + g) * D + l + 64 * u] = dv[u];
+    dK[((size_t)t * H_kv + g) * D + l + 64 * u] = (float)(dk[u] * (double)scale);
+    dV[((size_t)t * H_kv + g) * D + l + 64 * u] = (float)dv[u];
   }
 }
 
 int launch_fwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V, const float* z,
                    const int32_t* expiry, const int32_t* cu, float* O, float* LSE, hipStream_t st) {
   const dma_shape& s = p.s;
+  (void)z;
+  const float* zq = (const float*)(p.plan + p.pl.off_zq);  // the bias as the plan holds it: (z [+ caller bias]) / scale
   dim3 grid(s.T, s.H_q);
   if (s.d == 128)
-    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
                                                 nullptr, nullptr, nullptr);
   else
-    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
                                                nullptr, nullptr, nullptr);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
@@ -184,16 +187,18 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
                    const float* LSE, const float* z, const int32_t* expiry, const int32_t* cu, float* dQ, float* dK,
                    float* dV, float* dz, char* ws, hipStream_t st) {
   const dma_shape& s = p.s;
+  (void)z;
+  const float* zq = (const float*)(p.plan + p.pl.off_zq);
   float* Dws = (float*)ws;
   dim3 grid(s.T, s.H_q), gridk(s.T, s.H_kv);
   if (s.d == 128) {
-    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
+    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
                                                 const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
   } else {
-    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
+    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
                                                const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, z, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
   }
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }

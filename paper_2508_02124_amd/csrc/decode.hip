@@ -478,14 +478,18 @@ static void launch_decode_t(const dma_shape& s, float c2, const void* q, const v
 
 // incremental == 0: the kept sets are selected from all scores; otherwise they are carried over from
 // the previous step and updated with the newest key of every sequence.
+size_t decode_scratch_bytes(const dma_shape& s) {
+  return align_up(decode_part_floats(s) * 4, 256) + align_up(decode_sel_words(s) * 4, 256);
+}
+
+// part_and_sel: the scratch region (decode_scratch_bytes): partial outputs, then histograms and counts
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
                   const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
-                  hipStream_t st) {
+                  void* part_and_sel, hipStream_t st) {
   const float c2 = scale * LOG2E;
   const size_t kcap = (size_t)(s.k < s.T ? s.k : s.T);
   const int nsplit = (int)((kcap + DEC_CHUNK - 1) / DEC_CHUNK);
-  float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(kept) +
-                                         align_up((size_t)s.n_docs * s.H_q * kcap * 4, 256));
+  float* part = reinterpret_cast<float*>(part_and_sel);
   const int nbh = s.n_docs * s.H_q;
   DecSel ds;
   ds.z = z; ds.cu = cu; ds.lens = lens; ds.kept = kept;

@@ -716,6 +716,60 @@ __global__ __launch_bounds__(64) void topk_idx_kernel(const int32_t* __restrict_
 }
 
 // ------------------------------------------------------------------ host side
+// A caller-supplied attention bias, one value per key (broadcast over the query rows), is added to
+// the start values of the score accumulators only: zq += bias / scale.  The selection keeps ranking z.
+// bias is [bias_heads, T] (per_token) or [bias_heads, n_max] indexed by the key's position in its
+// document (shared by all documents); bias_heads = H_q or 1.
+__global__ __launch_bounds__(256) void bias_add_kernel(const float* __restrict__ bias, const int32_t* __restrict__ cu,
+                                                       int n_docs, int bias_heads, int per_token, int n_max,
+                                                       float* __restrict__ zq, float inv_scale, int T) {
+  const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+  if (t >= T) return;
+  const size_t row = bias_heads == 1 ? 0 : (size_t)h;
+  float b;
+  if (per_token) b = bias[row * T + t];
+  else b = bias[row * n_max + (t - cu[find_doc(cu, n_docs, t)])];
+  zq[(size_t)h * T + t] += b * inv_scale;
+}
+
+// Gradient of that bias from dz (the bias enters the score exactly like z): summed over the heads and
+// the documents that share an entry.  One thread per output element, no atomics.
+__global__ __launch_bounds__(256) void bias_bwd_kernel(const float* __restrict__ dz, const int32_t* __restrict__ cu,
+                                                       int n_docs, int bias_heads, int per_token, int n_max, int H_q,
+                                                       int T, float* __restrict__ dbias) {
+  const int n_out = per_token ? T : n_max;
+  const int x = blockIdx.x * 256 + threadIdx.x, bh = blockIdx.y;
+  if (x >= n_out) return;
+  const int h0 = bias_heads == 1 ? 0 : bh, h1 = bias_heads == 1 ? H_q : bh + 1;
+  float acc = 0.f;
+  if (per_token) {
+    for (int h = h0; h < h1; h++) acc += dz[(size_t)h * T + x];
+  } else {
+    for (int d = 0; d < n_docs; d++) {
+      const int a = cu[d], b = cu[d + 1];
+      if (x < b - a)
+        for (int h = h0; h < h1; h++) acc += dz[(size_t)h * T + a + x];
+    }
+  }
+  dbias[(size_t)bh * n_out + x] = acc;
+}
+
+int launch_bias_add(const Ptrs& p, const float* bias, int bias_heads, int per_token, const int32_t* cu, hipStream_t st) {
+  const dma_shape& s = p.s;
+  float* zq = (float*)(p.plan + p.pl.off_zq);
+  bias_add_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(bias, cu, s.n_docs, bias_heads, per_token, s.max_seqlen,
+                                                                 zq, 1.0f / p.scale, s.T);
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
+int launch_bias_bwd(const dma_shape& s, const float* dz, int bias_heads, int per_token, const int32_t* cu, float* dbias,
+                    hipStream_t st) {
+  const int n_out = per_token ? s.T : s.max_seqlen;
+  bias_bwd_kernel<<<dim3((n_out + 255) / 256, bias_heads), 256, 0, st>>>(dz, cu, s.n_docs, bias_heads, per_token,
+                                                                        s.max_seqlen, s.H_q, s.T, dbias);
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
 int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A, const int32_t* cu,
                     float* z, int32_t* expiry, int32_t* topk_idx, hipStream_t st) {
   const dma_shape& s = p.s;

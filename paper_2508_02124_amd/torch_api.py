@@ -48,10 +48,19 @@ class DynamicMaskAttentionFunction(torch.autograd.Function):
     """O = DMA(Q, K, V; W, A) on packed variable-length documents; differentiable in Q, K, V, W, A."""
 
     @staticmethod
-    def forward(ctx, Q, K, V, W, A, cu_seqlens, k, max_seqlen=0, softmax_scale=0.0):
+    def forward(ctx, Q, K, V, W, A, cu_seqlens, k, max_seqlen=0, softmax_scale=0.0, bias=None):
         _check_inputs(Q, K, V, W, A, cu_seqlens)
         Q, K, V, W, A = (t.contiguous() for t in (Q, K, V, W, A))
         T, H_q, d = Q.shape
+        bias_heads, bias_per_token = 0, True
+        if bias is not None:
+            # one value per key, broadcast over the query rows: [H_q or 1, T] (packed like the tokens) or
+            # [H_q or 1, max_seqlen] (by position in the document, shared by all documents)
+            if (not bias.is_cuda or bias.dtype != torch.float32 or bias.dim() != 2 or bias.shape[0] not in (1, H_q)
+                    or bias.shape[1] not in (T, max_seqlen)):
+                raise ValueError("bias must be a float32 GPU tensor [H_q or 1, T] or [H_q or 1, max_seqlen]")
+            bias = bias.contiguous()
+            bias_heads, bias_per_token = bias.shape[0], bias.shape[1] == T
         shape = B.make_shape(T, cu_seqlens.numel() - 1, H_q, K.shape[1], d, k, causal=True,
                              dtype=_dtype_code(Q), softmax_scale=softmax_scale, max_seqlen=max_seqlen)
         dev = Q.device
@@ -65,12 +74,15 @@ class DynamicMaskAttentionFunction(torch.autograd.Function):
         xhead = K.shape[1] > 1 and W.shape[1] == K.shape[1] * d
         if xhead:
             B.dma_scores_xhead(shape, V, W, A, z)
-            B.dma_mask_gen(shape, V, None, None, cu_seqlens, z, expiry, None, mask)
+        Wm, Am = (None, None) if xhead else (W, A)          # cross-head: the scores are supplied to dma_mask_gen
+        if bias is None:
+            B.dma_mask_gen(shape, V, Wm, Am, cu_seqlens, z, expiry, None, mask)
         else:
-            B.dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, None, mask)
+            B.dma_mask_gen_bias(shape, V, Wm, Am, cu_seqlens, bias, bias_heads, bias_per_token, z, expiry, None, mask)
         B.dma_fwd(shape, Q, K, V, z, expiry, mask, cu_seqlens, O, LSE, ws, ws_bytes)
         ctx.save_for_backward(Q, K, V, W, A, cu_seqlens, z, expiry, mask, O, LSE)
         ctx.shape, ctx.ws, ctx.ws_bytes, ctx.xhead = shape, ws, ws_bytes, xhead
+        ctx.bias_form = None if bias is None else (bias_heads, bias_per_token, tuple(bias.shape))
         return O
 
     @staticmethod
@@ -84,12 +96,19 @@ class DynamicMaskAttentionFunction(torch.autograd.Function):
         B.dma_bwd(shape, Q, K, V, O, dO, LSE, z, expiry, mask, cu_seqlens, dQ, dK, dV, dz, ctx.ws, ctx.ws_bytes)
         # dz -> dW, dA, and the part of dV that flows through the content scores, added in place
         (B.dma_scores_xhead_bwd if ctx.xhead else B.dma_mask_bwd)(shape, V, W, A, dz, dW, dA, dV, True)
-        return dQ, dK, dV, dW, dA, None, None, None, None
+        dbias = None
+        if ctx.bias_form is not None:   # the bias enters the score like z: its gradient is dz, reduced over what shares it
+            bias_heads, bias_per_token, bshape = ctx.bias_form
+            dbias = torch.empty(bshape, dtype=torch.float32, device=dz.device)
+            B.dma_bias_bwd(shape, dz, cu_seqlens, bias_heads, bias_per_token, dbias)
+        return dQ, dK, dV, dW, dA, None, None, None, None, dbias
 
 
-def dynamic_mask_attention(Q, K, V, W, A, cu_seqlens, k, max_seqlen=0, softmax_scale=0.0):
-    """Functional form; see DynamicMaskAttentionFunction."""
-    return DynamicMaskAttentionFunction.apply(Q, K, V, W, A, cu_seqlens, k, max_seqlen, softmax_scale)
+def dynamic_mask_attention(Q, K, V, W, A, cu_seqlens, k, max_seqlen=0, softmax_scale=0.0, bias=None):
+    """Functional form; see DynamicMaskAttentionFunction.  bias (optional, differentiable): a further
+    additive attention bias per key, [H_q or 1, T] or [H_q or 1, max_seqlen] (Section 1: biases with
+    batch, head and query broadcasting); it does not take part in the selection of the kept keys."""
+    return DynamicMaskAttentionFunction.apply(Q, K, V, W, A, cu_seqlens, k, max_seqlen, softmax_scale, bias)
 
 
 class DynamicMaskAttention(torch.nn.Module):

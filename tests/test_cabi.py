@@ -100,6 +100,14 @@ def test_error_codes_before_any_launch(lib):
     with pytest.raises(B.DmaError) as e:
         B.dma_decode_step(ok, p, p, p, p, p, p, 0, p, p, p, 8, stream=0)            # kept buffer too small
     assert e.value.status == B.DMA_EWORKSPACE
+    # bf16 attention addresses gathered K / V rows with 32-bit offsets: K (or V) beyond 4 GiB is refused
+    huge = B.make_shape(T=1 << 23, n_docs=1, H_q=8, H_kv=8, d=128, k=64)       # 8 Mi tokens x 2 KiB = 16 GiB
+    with pytest.raises(B.DmaError) as e:
+        B.dma_fwd(huge, p, p, p, p, p, p, p, p, p, None, 0, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
+    with pytest.raises(B.DmaError) as e:
+        B.dma_bwd(huge, p, p, p, p, p, p, p, p, p, p, p, p, p, p, p, 1 << 62, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
     assert B.dma_decode_kept_bytes(ok) >= 2 * 64 * 4
     assert "workspace" in B.strerror(B.DMA_EWORKSPACE)
     assert B.strerror(0) == "ok"

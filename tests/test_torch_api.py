@@ -40,7 +40,7 @@ CASES = {
 @pytest.mark.parametrize("name", list(CASES))
 def test_function_against_oracle(gpu, name, dtype):
     print(f"[case] autograd {name} {dtype}", flush=True)
-    from gpu_harness import DZ_SREL, check_close, tol
+    from gpu_harness import check_close, tol
     seed, H_q, H_kv, d, k, seqlens = CASES[name]
     inp = wlmod.make_inputs(wlmod.small_workload(name, seed, H_q, H_kv, d, k, seqlens), dtype=dtype)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -63,30 +63,22 @@ def test_function_against_oracle(gpu, name, dtype):
     zg = z.cpu().numpy().astype(np.float64)
 
     rO, _ = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, k)
-    rdQ, rdK, rdV, rdz, dza = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, k, return_dz_abs=True)
+    host = lambda x: x.detach().float().cpu().numpy()
+    # bf16: the backward forms D_i from the stored bf16 O (Alg. 2), so the oracle is given that buffer
+    rdQ, rdK, rdV, rdz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, k,
+                                          O_stored=host(O) if dtype == "bf16" else None)
     rdW, rdA, rdVz = orc.mask_backward(inp.V, inp.W, inp.A, rdz, H_q)
     t = tol(dtype == "bf16")
-    host = lambda x: x.detach().float().cpu().numpy()
     print("  O", check_close("O", host(O), rO, **t), flush=True)
     print("  dQ", check_close("dQ", host(Q.grad), rdQ, **t), flush=True)
     print("  dK", check_close("dK", host(K.grad), rdK, **t), flush=True)
     print("  dV", check_close("dV", host(V.grad), rdV + rdVz, **t), flush=True)
-    # dW, dA: fp32 sums over all tokens of dz * (fp32 factors); fp32 path 1e-4 (fp32 exp / log / sums
-    # over T rows).  In the bf16 path dz carries the error its own test allows (DZ_SREL per summand
-    # dS_ij).  dA_h = sum_j dz_j z_j softplus(x_j) has a nearly constant positive factor, and the dz of
-    # one row sum to zero up to the rounding of the stored O, so dA is a small remainder of large
-    # terms: it is judged element-wise against DZ_SREL * sum_ij |dS_ij| z_j softplus(x_j).
-    if dtype == "bf16":
-        print("  dW", check_close("dW", host(W.grad), rdW, atol=5e-2, rtol=2e-2, frob=1e-2), flush=True)
-        zo = orc.z_scores(inp.V, inp.W, inp.A, H_q)
-        sp = np.log(zo) / np.asarray(inp.A, dtype=np.float64)[:, None]
-        massA = (dza * zo * sp).sum(axis=1)
-        print("  dA", check_close("dA", host(A.grad), rdA, atol=2e-2, rtol=1e-2, frob=np.inf,
-                                  summand_abs=massA, srel=DZ_SREL), flush=True)
-    else:
-        t32 = dict(atol=1e-4, rtol=1e-4, frob=1e-4)
-        print("  dW", check_close("dW", host(W.grad), rdW, **t32), flush=True)
-        print("  dA", check_close("dA", host(A.grad), rdA, **t32), flush=True)
+    # dW, dA: fp32 sums over all tokens of dz * (fp32 factors), fp32 atomics, fp32 exp / log: 1e-4
+    # in the fp32 path; in the bf16 path dz itself is exact to fp32 rounding (it never passes through
+    # the matrix cores), so dW and dA meet the plain bf16 tolerance
+    t32 = t if dtype == "bf16" else dict(atol=1e-4, rtol=1e-4, frob=1e-4)
+    print("  dW", check_close("dW", host(W.grad), rdW, **t32), flush=True)
+    print("  dA", check_close("dA", host(A.grad), rdA, **t32), flush=True)
 
 
 @pytest.mark.gpu
@@ -113,18 +105,18 @@ def test_function_cross_head_against_oracle(gpu, dtype):
     zg = z.cpu().numpy().astype(np.float64)
     assert (np.abs(zg - orc.z_scores_xhead(inp.V, Delta, inp.A)) / zg).max() <= 1e-5
     rO, _ = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, k)
-    rdQ, rdK, rdV, rdz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, k)
+    host = lambda x: x.detach().float().cpu().numpy()
+    rdQ, rdK, rdV, rdz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, k,
+                                          O_stored=host(O) if dtype == "bf16" else None)
     rdD, rdA, rdVz = orc.xhead_backward(inp.V, Delta, inp.A, rdz)
     t = tol(dtype == "bf16")
-    host = lambda x: x.detach().float().cpu().numpy()
     print("  O", check_close("O", host(O), rO, **t), flush=True)
     print("  dQ", check_close("dQ", host(Q.grad), rdQ, **t), flush=True)
     print("  dK", check_close("dK", host(K.grad), rdK, **t), flush=True)
     print("  dV", check_close("dV", host(V.grad), rdV + rdVz, **t), flush=True)
-    tw = dict(atol=5e-2, rtol=2e-2, frob=1e-2) if dtype == "bf16" else dict(atol=1e-4, rtol=1e-4, frob=1e-4)
+    tw = t if dtype == "bf16" else dict(atol=1e-4, rtol=1e-4, frob=1e-4)
     print("  dDelta", check_close("dDelta", host(W.grad), rdD, **tw), flush=True)
-    if dtype == "f32":                                 # (bf16: dA is a small remainder, judged in the test above)
-        print("  dA", check_close("dA", host(A.grad), rdA, **tw), flush=True)
+    print("  dA", check_close("dA", host(A.grad), rdA, **tw), flush=True)
 
 
 @pytest.mark.gpu
