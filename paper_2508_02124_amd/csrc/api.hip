@@ -39,7 +39,7 @@ int check_gather_limits(const dma_shape& s) {
 }
 
 size_t ws_bytes_for(const dma_shape& s) {
-  if (s.dtype == DMA_F32) return align_up((size_t)s.H_q * s.T * 4, 256);
+  if (s.dtype == DMA_F32) return align_up((size_t)s.H_q * s.T * 8, 256);  // D_i in fp64
   return ws_layout(s).total;
 }
 

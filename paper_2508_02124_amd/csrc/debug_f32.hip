@@ -10,6 +10,11 @@ __device__ __forceinline__ float wave_sum(float x) {
   for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
   return x;
 }
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+  return x;
+}
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
@@ -24,7 +29,7 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
                                                      int n_docs, int causal, int T, int H_q, int H_kv, float scale,
                                                      float* __restrict__ O, float* __restrict__ LSE,
-                                                     const float* __restrict__ dO, float* __restrict__ Dout,
+                                                     const float* __restrict__ dO, double* __restrict__ Dout,
                                                      float* __restrict__ dQ) {
   const int t = blockIdx.x, h = blockIdx.y, l = threadIdx.x;
   const int g = h / (H_q / H_kv);
@@ -36,14 +41,17 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
   __shared__ float qs[D], dos[D];
   const float* qrow = Q + ((size_t)t * H_q + h) * D;
   for (int c = l; c < D; c += 64) qs[c] = qrow[c];
-  float Dt = 0.f, lse = 0.f;
+  // D_i and dP_ij are both of size |dO| |v| while their difference can vanish (one kept key: exactly):
+  // both are formed in fp64 so that the difference keeps fp32 accuracy
+  double Dt = 0.0;
+  float lse = 0.f;
   if (MODE == 1) {
     const float* dorow = dO + ((size_t)t * H_q + h) * D;
     const float* orow = O + ((size_t)t * H_q + h) * D;
-    float part = 0.f;
+    double part = 0.0;
     for (int c = l; c < D; c += 64) {
       dos[c] = dorow[c];
-      part = fmaf(dorow[c], orow[c], part);
+      part += (double)dorow[c] * (double)orow[c];
     }
     Dt = wave_sum(part);
     lse = LSE[(size_t)h * T + t];
@@ -82,9 +90,9 @@ __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q
         for (int c = 0; c < D; c++) acc[c] = fmaf(pr, vr[c], acc[c]);
       } else {
         const float pr = expf(s - lse);
-        float dp = 0.f;
-        for (int c = 0; c < D; c++) dp = fmaf(dos[c], vr[c], dp);
-        const float ds = pr * (dp - Dt);
+        double dp = 0.0;
+        for (int c = 0; c < D; c++) dp += (double)dos[c] * (double)vr[c];
+        const float ds = pr * (float)(dp - Dt);
 #pragma unroll
         for (int c = 0; c < D; c++) acc[c] = fmaf(ds, kr[c], acc[c]);
       }
@@ -111,7 +119,7 @@ __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
                                                      int n_docs, int causal, int T, int H_q, int H_kv,
                                                      float scale, const float* __restrict__ LSE,
-                                                     const float* __restrict__ dO, const float* __restrict__ Dws,
+                                                     const float* __restrict__ dO, const double* __restrict__ Dws,
                                                      float* __restrict__ dK, float* __restrict__ dV,
                                                      float* __restrict__ dz) {
   constexpr int CPL = D / 64;
@@ -140,18 +148,19 @@ __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q
     for (int i = i0; i < i1; i++) {
       const float* qr = Q + ((size_t)i * H_q + h) * D;
       const float* dor = dO + ((size_t)i * H_q + h) * D;
-      float qv[CPL], dov[CPL], s = 0.f, dp = 0.f;
+      float qv[CPL], dov[CPL], s = 0.f;
+      double dp = 0.0;
 #pragma unroll
       for (int u = 0; u < CPL; u++) {
         qv[u] = qr[l + 64 * u];
         dov[u] = dor[l + 64 * u];
         s = fmaf(qv[u], kc[u], s);
-        dp = fmaf(dov[u], vc[u], dp);
+        dp += (double)dov[u] * (double)vc[u];
       }
       s = wave_sum(s);
       dp = wave_sum(dp);
       const float pr = expf((s + zt) * scale - LSE[(size_t)h * T + i]);
-      const float ds = pr * (dp - Dws[(size_t)h * T + i]);
+      const float ds = pr * (float)(dp - Dws[(size_t)h * T + i]);
       dzacc += ds;
 #pragma unroll
       for (int u = 0; u < CPL; u++) {
@@ -189,7 +198,7 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   const dma_shape& s = p.s;
   (void)z;
   const float* zq = (const float*)(p.plan + p.pl.off_zq);
-  float* Dws = (float*)ws;
+  double* Dws = (double*)ws;
   dim3 grid(s.T, s.H_q), gridk(s.T, s.H_kv);
   if (s.d == 128) {
     row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
