@@ -217,6 +217,26 @@ int dma_decode(const dma_shape* shape, const void* q, const void* K, const void*
                const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, size_t kept_bytes, void* stream);
 
 /*
+ * dma_decode for callers that cannot allocate device memory or pass a scratch region: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
+ * kernels and same results as dma_decode, but the kernels' scratch (per-chunk partial outputs, the
+ * selection's histograms and counts) lies in a device array owned by the library, of
+ * DMA_DECODE_STATIC_SCRATCH_BYTES on every GPU the library is used on (held until the process ends;
+ * its address is looked up on the first call on each device).  The call allocates and frees nothing.
+ *   kept  out [n_docs, H_q, min(k, T)] int32 only (no scratch behind it)
+ *   Shapes whose scratch, dma_decode_static_scratch_bytes(shape), exceeds the array are refused with
+ *   DMA_EWORKSPACE before anything is enqueued (e.g. 1 sequence x 32 heads x k = 2048 x d = 128
+ *   needs 0.32 MiB; about 12 such sequences fit).
+ *   Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ *   streams, two threads) race; calls on one stream are ordered and safe.  Nothing in the array
+ *   needs clearing by the caller (each call clears what it accumulates into with a fill kernel).
+ */
+#define DMA_DECODE_STATIC_SCRATCH_BYTES (4u << 20)
+size_t dma_decode_static_scratch_bytes(const dma_shape* shape);
+int dma_decode_static(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
+                      const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, void* stream);
+
+/*
  * Decode in a loop, with the kept sets carried from step to step (Eq. 4 as a one-in / one-out update:
  * the newest key joins the kept set, or replaces its worst member if it beats it).  For callers
  * that keep every sequence in a region of fixed capacity: sequence b owns rows

@@ -81,6 +81,10 @@ def lib():
         L.dma_decode_kept_bytes.restype = sz
         L.dma_decode.argtypes = [shp] + [vp] * 8 + [sz, vp]
         L.dma_decode.restype = i32
+        L.dma_decode_static_scratch_bytes.argtypes = [shp]
+        L.dma_decode_static_scratch_bytes.restype = sz
+        L.dma_decode_static.argtypes = [shp] + [vp] * 9
+        L.dma_decode_static.restype = i32
         L.dma_decode_step.argtypes = [shp] + [vp] * 6 + [i32] + [vp] * 3 + [sz, vp]
         L.dma_decode_step.restype = i32
         L.dma_probe_mfma.argtypes = [vp, i32, i32, vp]
@@ -192,6 +196,15 @@ def dma_decode_kept_bytes(shape):
 def dma_decode(shape, q, K, V, z, cu_seqlens, o, lse, kept, kept_bytes, stream=None):
     _check(lib().dma_decode(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(z), _ptr(cu_seqlens), _ptr(o),
                             _ptr(lse), _ptr(kept), int(kept_bytes), _stream(stream)), "dma_decode")
+
+
+def dma_decode_static_scratch_bytes(shape):
+    return int(lib().dma_decode_static_scratch_bytes(ctypes.byref(shape)))
+
+
+def dma_decode_static(shape, q, K, V, z, cu_seqlens, o, lse, kept, stream=None):
+    _check(lib().dma_decode_static(ctypes.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(z), _ptr(cu_seqlens),
+                                   _ptr(o), _ptr(lse), _ptr(kept), _stream(stream)), "dma_decode_static")
 
 
 def dma_decode_step(shape, q, K, V, z, cu_seqlens, seq_lens, refresh, o, lse, kept, kept_bytes, stream=None):

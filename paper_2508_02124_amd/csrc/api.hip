@@ -209,6 +209,25 @@ int dma_decode(const dma_shape* shape, const void* q, const void* K, const void*
                        reinterpret_cast<char*>(kept) + decode_list_bytes(*shape), (hipStream_t)stream);
 }
 
+size_t dma_decode_static_scratch_bytes(const dma_shape* shape) {
+  if (check_shape(shape) != DMA_OK) return 0;
+  return decode_scratch_bytes(*shape);
+}
+
+int dma_decode_static(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
+                      const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != DMA_OK) return rc;
+  if (!q || !K || !V || !z || !cu_seqlens || !o || !lse || !kept) return DMA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(z) || !aligned16(o) || !aligned16(kept))
+    return DMA_EINVAL;
+  if (decode_scratch_bytes(*shape) > DMA_DECODE_STATIC_SCRATCH_BYTES) return DMA_EWORKSPACE;
+  void* scratch_ptr = nullptr;
+  if ((rc = decode_static_scratch(&scratch_ptr)) != DMA_OK) return rc;
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->d);
+  return launch_decode(*shape, scale, q, K, V, z, cu_seqlens, nullptr, 0, o, lse, kept, scratch_ptr, (hipStream_t)stream);
+}
+
 int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
                     const int32_t* cu_seqlens, const int32_t* seq_lens, int refresh, void* o, float* lse,
                     int32_t* kept, size_t kept_bytes, void* stream) {
@@ -240,7 +259,7 @@ const char* dma_strerror(int status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
     case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: K and V at most 4 GiB each, fewer than 2^24 tokens)";
-    case DMA_EWORKSPACE: return "workspace missing or smaller than dma_workspace_bytes()";
+    case DMA_EWORKSPACE: return "workspace missing or too small (dma_workspace_bytes, dma_decode_kept_bytes), or the shape needs more than the library-owned scratch of dma_decode_static";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";
   }

@@ -146,6 +146,7 @@ int launch_xhead_bwd(const dma_shape& s, const void* V, const float* Delta, cons
 size_t decode_part_floats(const dma_shape& s);
 size_t decode_sel_words(const dma_shape& s);
 size_t decode_scratch_bytes(const dma_shape& s);   // partial outputs + selection words of one call
+int decode_static_scratch(void** out);             // the current device's copy of the library-owned scratch
 int launch_decode(const dma_shape& s, float scale, const void* q, const void* K, const void* V, const float* z,
                   const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
                   void* part_and_sel, hipStream_t st);

@@ -478,8 +478,27 @@ static void launch_decode_t(const dma_shape& s, float c2, const void* q, const v
 
 // incremental == 0: the kept sets are selected from all scores; otherwise they are carried over from
 // the previous step and updated with the newest key of every sequence.
+// Scratch of dma_decode_static: the per-chunk partial outputs and the selection's histograms and
+// counts of one call, held in the library's own device memory (every GPU the library runs on keeps
+// its copy until the process ends).  Host code never passes the array's name to a kernel: the
+// device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[DMA_DECODE_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[64] = {};
+
 size_t decode_scratch_bytes(const dma_shape& s) {
   return align_up(decode_part_floats(s) * 4, 256) + align_up(decode_sel_words(s) * 4, 256);
+}
+
+int decode_static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DMA_EHIP;
+  void* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return DMA_EHIP;
+    __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);  // (two first callers store the same address)
+  }
+  *out = ptr;
+  return DMA_OK;
 }
 
 // part_and_sel: the scratch region (decode_scratch_bytes): partial outputs, then histograms and counts
