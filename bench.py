@@ -121,7 +121,7 @@ def clean_pair_count(inp, eg, BQ=256):
 
 def time_workload(wl, steps, warmup, dev, structured_z=False, calibration_copy=False):
     """Times `steps` steps (mask_gen + fwd [+ bwd]) of one workload.  Returns the timing record and the
-    device case.  Stage events are recorded inside the timed region on every second step (an armed
+    device case.  Stage events are recorded inside the timed region on every fourth step (an armed
     step records 20 events between the launches, 0.05-0.15 ms of a 3.3 ms step; the kernels'
     durations do not depend on it); per-step durations come from one event per step boundary."""
     import numpy as np
@@ -158,7 +158,7 @@ def time_workload(wl, steps, warmup, dev, structured_z=False, calibration_copy=F
         del src, dst
 
     nst = len(B.STAGES)
-    armed = [i for i in range(steps) if i % 2 == 0]
+    armed = [i for i in range(steps) if i % 4 == 0]
     evsets = [HipEvents(2 * nst) for _ in armed]
     bounds = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()

@@ -46,11 +46,13 @@ struct BwdArgs {
 };
 
 // ------------------------------------------------------------------ dQ (and D, LSE * log2 e)
-template <int D>
-__global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
+// NW waves per workgroup: 8 (a whole 256-row block, four ring stages) or 4 (half a block, two ring
+// stages, two workgroups per compute unit), as in the forward kernel.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
-  constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, NW = 8, WL = KT / RPL / NW;
-  constexpr int NS = 4, TILE = KT * D;
+  constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, WL = KT / RPL / NW;
+  constexpr int NS = NW == 8 ? 4 : 2, TILE = KT * D, NT = NW * 64, HALVES = 8 / NW;
   __shared__ __align__(16) uint16_t ringK[NS * TILE];
   __shared__ __align__(16) uint16_t ringV[NS * TILE];
   __shared__ __align__(16) int ids_ring[2 * NS][KT];
@@ -61,20 +63,22 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
   // (the fp32 dK / dV buffers and dz): every workgroup, also one without a block, takes its share of
   // the stores; this kernel is bound by the matrix cores, so they cost no time here.
   {
-    const size_t nth = (size_t)p.grid_dq * 512, gid = (size_t)wg_id() * 512 + thread_id();
+    const size_t nth = (size_t)p.grid_dq * NT, gid = (size_t)wg_id() * NT + thread_id();
     float4* acc4 = reinterpret_cast<float4*>(p.dK32);
     for (size_t i = gid; i < p.zero_n4; i += nth) acc4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (size_t i = gid; i < p.dz_n; i += nth) p.dz[i] = 0.f;
   }
   int h, item;
-  if (!xcd_map_interleaved(wg_id(), p.H_q, p.nblk_cap, h, item)) return;
-  const int bi = p.nblk_cap - 1 - item;  // long blocks first
+  if (!xcd_map_interleaved(wg_id(), p.H_q, p.nblk_cap * HALVES, h, item)) return;
+  const int bi = p.nblk_cap - 1 - item / HALVES;  // long blocks first
   const int4 info = p.blk[bi];
   if (info.x < 0) return;
-  const int row0 = info.y, row1 = info.z, doc0 = info.w;
+  const int blk_row0 = info.y, row1 = info.z, doc0 = info.w;
+  const int row0 = blk_row0 + (item % HALVES) * (NW * 32);  // first row of this workgroup's part of the block
+  if (row0 >= row1) return;
   const int g = h / (p.H_q / p.H_kv);
   const int tid = thread_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, n = l & 31, hh = l >> 5;
-  const int ncol = min(p.k, row0 - doc0);
+  const int ncol = min(p.k, blk_row0 - doc0);
   const int nc = (ncol + KT - 1) / KT;
   const int np_keys = p.pcnt[(size_t)h * p.nblk_cap + bi];
   const int nt = nc + (np_keys + KT - 1) / KT;
@@ -278,17 +282,19 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     tile(std::integral_constant<int, 0>{}, t);
     if (t + 1 >= nt) break;
     tile(std::integral_constant<int, 1>{}, t + 1);
-    if (t + 2 >= nt) break;
-    tile(std::integral_constant<int, 2>{}, t + 2);
-    if (t + 3 >= nt) break;
-    tile(std::integral_constant<int, 3>{}, t + 3);
+    if constexpr (NS == 4) {
+      if (t + 2 >= nt) break;
+      tile(std::integral_constant<int, 2>{}, t + 2);
+      if (t + 3 >= nt) break;
+      tile(std::integral_constant<int, 3>{}, t + 3);
+    }
   }
-  static_assert(NS == 4, "the main loop is unrolled over four ring stages");
+  static_assert(NS == 4 || NS == 2, "the main loop is unrolled over the ring stages");
 
   wait_vmcnt<0>();
   lds_barrier();
-  uint16_t* Os = ringK;  // [BQ][D] staging with the tile swizzle
-  static_assert(NS * KT == BQ, "dQ staging aliases the K ring");
+  uint16_t* Os = ringK;  // [NW * 32][D] staging with the tile swizzle
+  static_assert(NS * KT >= NW * 32, "dQ staging aliases the K ring");
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
 #pragma unroll
@@ -300,8 +306,8 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(BwdArgs p) {
     }
   lds_barrier();
 #pragma unroll
-  for (int it = 0; it < BQ * CPR / 512; it++) {
-    const int c = tid + 512 * it, r = c / CPR, col = c % CPR;
+  for (int it = 0; it < NW * 32 * CPR / NT; it++) {
+    const int c = tid + NT * it, r = c / CPR, col = c % CPR;
     if (row0 + r < row1)
       *reinterpret_cast<uint4*>(p.dQ + ((size_t)(row0 + r) * p.H_q + h) * D + 8 * col) =
           *reinterpret_cast<const uint4*>(&Os[TL::off(r, col)]);
@@ -739,8 +745,9 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
   const unsigned gpart = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg_part - 1) / a.seg_part) * (MAXPART / SG));
   prof_begin(DMA_STAGE_BWD_DQ, st);
-  if (s.d == 128) dq_kernel<128><<<gq, 512, 0, st>>>(a);
-  else dq_kernel<64><<<gq, 512, 0, st>>>(a);
+  // (the half-block variant, NW = 4, measured the same or slower at every benchmark shape)
+  if (s.d == 128) dq_kernel<128, 8><<<gq, 512, 0, st>>>(a);
+  else dq_kernel<64, 8><<<gq, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_DQ, st);
   prof_begin(DMA_STAGE_BWD_DKV, st);
   if (s.d == 128) dkv_kernel<128, false><<<gclean, 512, 0, st>>>(a);
