@@ -188,8 +188,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p)
   uint32_t kfrag[KS], vfrag[KS], ktr[CB][2];
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) {
-    kfrag[ks] = lds_addr(ringK) + 2 * fo.row[ks];
-    vfrag[ks] = lds_addr(ringV) + 2 * fo.row[ks];
+    kfrag[ks] = lds_addr(ringK) + 2 * fo.row(ks);
+    vfrag[ks] = lds_addr(ringV) + 2 * fo.row(ks);
     settle(kfrag[ks]);
     settle(vfrag[ks]);
   }
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p)
   for (int cb = 0; cb < CB; cb++)
 #pragma unroll
     for (int q = 0; q < 2; q++) {
-      ktr[cb][q] = lds_addr(ringK) + 2 * fo.tr[cb][q];
+      ktr[cb][q] = lds_addr(ringK) + 2 * fo.tr(cb, q);
       settle(ktr[cb][q]);
     }
   uint32_t zlane = lds_addr(&z_ring[0][4 * hh]);
@@ -417,23 +417,14 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   // Rows past the end of the block (or every row of a block without columns) re-read a valid row:
   // their LSE is +inf and their D is 0, so whatever Q / dO they hold contributes exactly 0.
   const uint32_t row_stride = (uint32_t)p.H_q * D * 2;  // bytes between consecutive rows of Q / dO
-  int lane_r[WLW];        // tile row this lane copies
-  uint32_t lane_c[WLW];   // byte offset of its 16-byte chunk within the row
-  bool lane_do[WLW];
-#pragma unroll
-  for (int j = 0; j < WLW; j++) {
-    const int li = w + 8 * j;  // copy index: Q rows first, then dO rows
-    lane_do[j] = li >= NWL / 2;
-    const int rbase = (lane_do[j] ? li - NWL / 2 : li) * RPL;
-    lane_r[j] = rbase + l / CPR;
-    lane_c[j] = (uint32_t)(((l % CPR) ^ TL::swz(lane_r[j])) * 16);
-  }
-  uint32_t lane_off[WLW];  // byte offset of the lane's chunk from the step's first row, for a full step
-#pragma unroll
-  for (int j = 0; j < WLW; j++) {
-    lane_off[j] = (uint32_t)lane_r[j] * row_stride + lane_c[j];
-    settle(lane_off[j]);
-  }
+  // copy li = w + 8 j of a step takes Q rows (li < NWL / 2) or dO rows; its tile rows start at
+  // (li mod NWL / 2) * RPL, which is the same for every copy of a wave (NWL / 2 is 8 or 4)
+  static_assert((NWL / 2) == 8 || (NWL / 2 == 4 && WLW == 1), "copy layout of the key-stationary kernel");
+  const int copy_rbase = (w % (NWL / 2)) * RPL;
+  const int lane_r = copy_rbase + l / CPR;                                      // tile row this lane copies
+  const uint32_t lane_c = (uint32_t)(((l % CPR) ^ TL::swz(lane_r)) * 16);       // byte offset of its 16-byte chunk within the row
+  uint32_t lane_off = (uint32_t)lane_r * row_stride + lane_c;  // ... from the step's first row, for a full step
+  settle(lane_off);
   Cursor pc = {-1, 0, 0, 0};
   auto issue = [&](int v) {
     const int qs = v % NSUB;
@@ -443,12 +434,12 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     const int nvalid = pc.ncols > 0 ? min(max(pc.row1 - rowb, 0), SUB) : 0;
     const int rb = nvalid > 0 ? rowb : 0;  // base row of the copies (row 0 when nothing is valid)
     const size_t boff = ((size_t)rb * p.H_q + h) * D;
+    uint32_t off = lane_off;
+    if (nvalid < SUB) off = (uint32_t)min(lane_r, max(nvalid - 1, 0)) * row_stride + lane_c;  // (wave-uniform branch)
 #pragma unroll
     for (int j = 0; j < WLW; j++) {
-      uint32_t off = lane_off[j];
-      if (nvalid < SUB) off = (uint32_t)min(lane_r[j], max(nvalid - 1, 0)) * row_stride + lane_c[j];  // (wave-uniform branch)
-      const int rbase = ((lane_do[j] ? w + 8 * j - NWL / 2 : w + 8 * j)) * RPL;
-      dma16s((lane_do[j] ? p.dO : p.Q) + boff, off, (lane_do[j] ? ringdO : ringQ) + st * STILE + rbase * D);
+      const bool is_do = w + 8 * j >= NWL / 2;  // (wave-uniform; a constant per j at D = 128)
+      dma16s((is_do ? p.dO : p.Q) + boff, off, (is_do ? ringdO : ringQ) + st * STILE + copy_rbase * D);
     }
     if (w == 0) {
       const bool ok = n < nvalid;
@@ -549,6 +540,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     if (w == 0) wait_vmcnt<(NS - 3) * (WLW + 1)>();
     else wait_vmcnt<(NS - 3) * WLW>();
     lds_barrier();
+    fo.pin();
     issue(it + NS - 2);
 
     // role 1 first finishes the step whose dP it computed at the end of the previous period

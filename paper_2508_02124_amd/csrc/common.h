@@ -277,38 +277,40 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int rowbase, int
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// The lane's element offsets of the fragments it reads from a swizzled tile, computed once per
-// kernel and pinned in registers, so that a read in the main loops is base + offset + immediate:
-//   row[ks]    row fragment (16 bytes): tile[rowbase + n][16*ks + 8*hh .. +8), rowbase a multiple of 16
-//   tr[cb][q]  the two halves (q) of tr_frag(tile, rowbase, cb), rowbase a multiple of 16
-// (the swizzle only looks at the low four row bits, so rowbase adds rowbase * D elements).
+// The lane's element offsets of the fragments it reads from a swizzled tile:
+//   row(ks)    row fragment (16 bytes): tile[rowbase + n][16*ks + 8*hh .. +8), rowbase a multiple of 16
+//   tr(cb, q)  the two halves (q) of tr_frag(tile, rowbase, cb), rowbase a multiple of 16
+// (the swizzle only looks at the low four row bits, so rowbase adds rowbase * D elements).  The
+// swizzle XORs the chunk index, and the chunk bits that ks / cb select lie above the lane's own, so
+// row(ks) = row(0) ^ (16 ks) and tr(cb, q) = tr(0, q) ^ (32 cb): three registers hold all of them
+// and a read costs one XOR-and-add (the key-stationary kernel has no registers to spare for more).
 template <int D>
 struct FragOffsets {
-  int row[D / 16];
-  int tr[D / 32][2];
+  int row0;
+  int tr0[2];
   __device__ __forceinline__ void init(int l) {
     const int n = l & 31, hh = l >> 5, l16 = l & 15, b16 = (l >> 4) & 1;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-      row[ks] = TileLayout<D>::off(n & 15, 2 * ks + hh) + (n & 16) * D;
-      asm volatile("" : "+v"(row[ks]));
-    }
-#pragma unroll
-    for (int cb = 0; cb < D / 32; cb++) {
-      const int r = 4 * hh + (l16 >> 2);
-      const int c = 4 * cb + 2 * b16 + ((l16 & 3) >> 1);
-      tr[cb][0] = TileLayout<D>::off(r, c) + 4 * (l16 & 1);
-      tr[cb][1] = TileLayout<D>::off(r + 8, c) + 4 * (l16 & 1);
-      asm volatile("" : "+v"(tr[cb][0]));
-      asm volatile("" : "+v"(tr[cb][1]));
-    }
+    row0 = TileLayout<D>::off(n & 15, hh) + (n & 16) * D;
+    asm volatile("" : "+v"(row0));
+    const int r = 4 * hh + (l16 >> 2);
+    const int c = 2 * b16 + ((l16 & 3) >> 1);
+    tr0[0] = TileLayout<D>::off(r, c) + 4 * (l16 & 1);
+    tr0[1] = TileLayout<D>::off(r + 8, c) + 4 * (l16 & 1);
+    asm volatile("" : "+v"(tr0[0]));
+    asm volatile("" : "+v"(tr0[1]));
   }
+  // called inside a loop: keeps the compiler from hoisting every row(ks) / tr(cb, q) out of it again
+  __device__ __forceinline__ void pin() {
+    asm volatile("" : "+v"(row0), "+v"(tr0[0]), "+v"(tr0[1]));
+  }
+  __device__ __forceinline__ int row(int ks) const { return row0 ^ (16 * ks); }
+  __device__ __forceinline__ int tr(int cb, int q) const { return tr0[q] ^ (32 * cb); }
   __device__ __forceinline__ bf16x8 row_frag(const uint16_t* tile, int rowbase, int ks) const {
-    return *reinterpret_cast<const bf16x8*>(tile + row[ks] + rowbase * D);
+    return *reinterpret_cast<const bf16x8*>(tile + row(ks) + rowbase * D);
   }
   __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* tile, int rowbase, int cb) const {
-    const s16x4 lo = lds_read_tr(tile + tr[cb][0] + rowbase * D);
-    const s16x4 hi = lds_read_tr(tile + tr[cb][1] + rowbase * D);
+    const s16x4 lo = lds_read_tr(tile + tr(cb, 0) + rowbase * D);
+    const s16x4 hi = lds_read_tr(tile + tr(cb, 1) + rowbase * D);
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   }
 };

@@ -165,14 +165,14 @@ __global__ __launch_bounds__(NW * 64, D == 64 ? 4 : (NW == 8 ? 1 : 2)) void fwd_
   uint32_t kfrag[KS], vfrag[CB][2];
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) {
-    kfrag[ks] = lds_addr(ringK) + 2 * fo.row[ks];
+    kfrag[ks] = lds_addr(ringK) + 2 * fo.row(ks);
     settle(kfrag[ks]);
   }
 #pragma unroll
   for (int cb = 0; cb < CB; cb++)
 #pragma unroll
     for (int q = 0; q < 2; q++) {
-      vfrag[cb][q] = lds_addr(ringV) + 2 * fo.tr[cb][q];
+      vfrag[cb][q] = lds_addr(ringV) + 2 * fo.tr(cb, q);
       settle(vfrag[cb][q]);
     }
   uint32_t zlane = lds_addr(&z_ring[0][4 * hh]);
