@@ -41,7 +41,7 @@ typedef enum {
   DMA_OK = 0,
   DMA_EINVAL = -1,       /* null pointer, misaligned pointer, T<=0, k<=0, n_docs<=0, H_q % H_kv != 0 */
   DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, more than 32 heads for the cross-head scores,
-                            bf16 dma_fwd / dma_bwd with T >= 2^24 or K (or V) larger than 4 GiB            */
+                            bf16 dma_fwd / dma_bwd with T >= 2^24 or Q (or K, V) larger than 4 GiB         */
   DMA_EWORKSPACE = -3,   /* ws_bytes smaller than dma_workspace_bytes() */
   DMA_EHIP = -4          /* a launch failed (hipGetLastError) */
 } dma_status;

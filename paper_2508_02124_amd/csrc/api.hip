@@ -35,6 +35,8 @@ int check_gather_limits(const dma_shape& s) {
   if (s.dtype != DMA_BF16) return DMA_OK;
   const unsigned long long pitch = (unsigned long long)s.H_kv * s.d * 2;
   if (s.T >= (1 << 24) || pitch >= (1ull << 24) || (unsigned long long)s.T * pitch > (1ull << 32)) return DMA_EUNSUPPORTED;
+  // (the key-stationary backward addresses Q / dO rows the same way: at most 4 GiB each)
+  if ((unsigned long long)s.T * s.H_q * s.d * 2 > (1ull << 32)) return DMA_EUNSUPPORTED;
   return DMA_OK;
 }
 
@@ -258,7 +260,7 @@ const char* dma_strerror(int status) {
   switch (status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
-    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: K and V at most 4 GiB each, fewer than 2^24 tokens)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: Q, K, V at most 4 GiB each, fewer than 2^24 tokens)";
     case DMA_EWORKSPACE: return "workspace missing or too small (dma_workspace_bytes, dma_decode_kept_bytes), or the shape needs more than the library-owned scratch of dma_decode_static";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";

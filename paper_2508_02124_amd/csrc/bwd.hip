@@ -333,11 +333,9 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   constexpr int SUB = 32;                 // query rows per pipeline step
   constexpr int NSUB = BQ / SUB;          // steps per query block
   constexpr int NWL = 2 * (SUB / RPL);    // 16-byte wave copies per step (Q rows, then dO rows)
-  constexpr int WLW = NWL / 8;            // ... per wave
   constexpr int NS = 5;                   // ring stages
   constexpr int STILE = SUB * D;
   constexpr int LDS_ST = 32 + 4;          // staging row: the 32 channels of one flush pass, padded
-  static_assert(WLW >= 1, "tile too small for eight waves");
   __shared__ __align__(16) uint16_t ringQ[NS * STILE];
   __shared__ __align__(16) uint16_t ringdO[NS * STILE];
   __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) D
@@ -413,38 +411,62 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   };
 
   // ---- producer: copies of step v (32 query rows of Q and dO, their LSE/D, and at a block's first
-  // step the block's column ids).  Every wave issues the same number of copies for every step.
-  // Rows past the end of the block (or every row of a block without columns) re-read a valid row:
-  // their LSE is +inf and their D is 0, so whatever Q / dO they hold contributes exactly 0.
+  // step the block's column ids).  Only the four role-0 waves issue copies: the role-1 waves carry
+  // the longer chain of a step (they run the dS / dK^T part of the previous step before their dP),
+  // while the role-0 waves have idle time at every barrier.  Every issuing wave issues the same
+  // number of copies for every step.  Rows past the end of the block (or every row of a block without
+  // columns) re-read a valid row: their LSE is +inf and their D is 0, so whatever Q / dO they hold
+  // contributes exactly 0.
+  constexpr int WLW0 = NWL / 4;   // copies per issuing wave and step: first half Q rows, second half dO rows
+  constexpr int NLO = WLW0 / 2;   // distinct row positions among them
+  static_assert(WLW0 == 2 * NLO && NLO >= 1, "copy layout of the key-stationary kernel");
   const uint32_t row_stride = (uint32_t)p.H_q * D * 2;  // bytes between consecutive rows of Q / dO
-  // copy li = w + 8 j of a step takes Q rows (li < NWL / 2) or dO rows; its tile rows start at
-  // (li mod NWL / 2) * RPL, which is the same for every copy of a wave (NWL / 2 is 8 or 4)
-  static_assert((NWL / 2) == 8 || (NWL / 2 == 4 && WLW == 1), "copy layout of the key-stationary kernel");
-  const int copy_rbase = (w % (NWL / 2)) * RPL;
-  const int lane_r = copy_rbase + l / CPR;                                      // tile row this lane copies
-  const uint32_t lane_c = (uint32_t)(((l % CPR) ^ TL::swz(lane_r)) * 16);       // byte offset of its 16-byte chunk within the row
-  uint32_t lane_off = (uint32_t)lane_r * row_stride + lane_c;  // ... from the step's first row, for a full step
-  settle(lane_off);
+  int lane_r[NLO];          // tile row this lane copies (copy j takes rows (kb4 + 4 (j mod NLO)) * RPL ...)
+  uint32_t lane_c[NLO];     // byte offset of its 16-byte chunk within the row
+  uint32_t lane_off[NLO];   // ... from the step's first row, for a full step
+#pragma unroll
+  for (int u = 0; u < NLO; u++) {
+    lane_r[u] = (kb4 + 4 * u) * RPL + l / CPR;
+    lane_c[u] = (uint32_t)(((l % CPR) ^ TL::swz(lane_r[u])) * 16);
+    lane_off[u] = (uint32_t)lane_r[u] * row_stride + lane_c[u];
+    settle(lane_off[u]);
+  }
+  const char* Qh = (const char*)uniform_ptr(reinterpret_cast<const char*>(p.Q) + (size_t)h * D * 2);   // row 0 of this head
+  const char* dOh = (const char*)uniform_ptr(reinterpret_cast<const char*>(p.dO) + (size_t)h * D * 2);
   Cursor pc = {-1, 0, 0, 0};
+  int issue_st = 0;   // ring stage of the next step to issue (steps are issued in order: v mod NS without a division)
   auto issue = [&](int v) {
+    if (role != 0) return;
     const int qs = v % NSUB;
     if (qs == 0) pc = load_cursor(v / NSUB);
-    const int st = v % NS;
+    const int st = issue_st;
+    issue_st = issue_st + 1 == NS ? 0 : issue_st + 1;
     const int rowb = pc.row0 + SUB * qs;
-    const int nvalid = pc.ncols > 0 ? min(max(pc.row1 - rowb, 0), SUB) : 0;
-    const int rb = nvalid > 0 ? rowb : 0;  // base row of the copies (row 0 when nothing is valid)
-    const size_t boff = ((size_t)rb * p.H_q + h) * D;
-    uint32_t off = lane_off;
-    if (nvalid < SUB) off = (uint32_t)min(lane_r, max(nvalid - 1, 0)) * row_stride + lane_c;  // (wave-uniform branch)
+    const int left = pc.ncols > 0 ? pc.row1 - rowb : 0;   // rows of the block from this step on (wave-uniform)
+    uint16_t* dstQ = ringQ + st * STILE;
+    uint16_t* dstdO = ringdO + st * STILE;
+    if (left >= SUB) {  // a full step: scalar base of the step's first row + the lane's fixed offset
+      const uint32_t boff = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)rowb * row_stride));  // (below 4 GiB: checked on the host)
 #pragma unroll
-    for (int j = 0; j < WLW; j++) {
-      const bool is_do = w + 8 * j >= NWL / 2;  // (wave-uniform; a constant per j at D = 128)
-      dma16s((is_do ? p.dO : p.Q) + boff, off, (is_do ? ringdO : ringQ) + st * STILE + copy_rbase * D);
-    }
-    if (w == 0) {
-      const bool ok = n < nvalid;
-      const float* src = hh == 0 ? (ok ? L2h + rowb + n : c_pinf) : (ok ? Dh + rowb + n : c_zero_f);
-      dma4(src, &meta[st][0]);
+      for (int j = 0; j < WLW0; j++) {
+        const int u = j % NLO;
+        dma16s((j >= NLO ? dOh : Qh) + boff, lane_off[u], (j >= NLO ? dstdO : dstQ) + (kb4 + 4 * u) * RPL * D);
+      }
+      if (w == 0) dma4(hh == 0 ? L2h + rowb + n : Dh + rowb + n, &meta[st][0]);
+    } else {  // the ragged last step of a block, or a block without columns: rows past the end repeat a valid one
+      const int nvalid = max(left, 0);
+      const uint32_t boff = (uint32_t)(nvalid > 0 ? rowb : 0) * row_stride;
+#pragma unroll
+      for (int j = 0; j < WLW0; j++) {
+        const int u = j % NLO;
+        const uint32_t off = (uint32_t)min(lane_r[u], max(nvalid - 1, 0)) * row_stride + lane_c[u];
+        dma16s((j >= NLO ? dOh : Qh) + boff, off, (j >= NLO ? dstdO : dstQ) + (kb4 + 4 * u) * RPL * D);
+      }
+      if (w == 0) {
+        const bool ok = n < nvalid;
+        const float* src = hh == 0 ? (ok ? L2h + rowb + n : c_pinf) : (ok ? Dh + rowb + n : c_zero_f);
+        dma4(src, &meta[st][0]);
+      }
     }
     if (qs == 0 && (w == 1 || w == 2)) {
       const int bi = pc.bi;
@@ -537,8 +559,8 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   for (int it = 0; it <= nsteps; it++) {
     // copies of step `it` must have landed: at most NS-3 later steps' worth may still be in flight
     // (the occasional id copies and the flush traffic only make this wait more conservative)
-    if (w == 0) wait_vmcnt<(NS - 3) * (WLW + 1)>();
-    else wait_vmcnt<(NS - 3) * WLW>();
+    if (w == 0) wait_vmcnt<(NS - 3) * (WLW0 + 1)>();
+    else wait_vmcnt<(NS - 3) * WLW0>();
     lds_barrier();
     fo.pin();
     issue(it + NS - 2);
