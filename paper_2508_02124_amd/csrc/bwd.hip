@@ -604,14 +604,9 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
       const int newid = (cl < ncols) ? idbuf[(v / NSUB) & 1][cl] : -1;
       const bool changed = newid != curid;
       if (__any(changed)) {
-        flush(changed);  // finished keys out, then re-arm the changed columns
+        // The new keys' rows are requested first and arrive while the finished keys are flushed
+        // (the flush reads the accumulators and the old ids only).
         if (changed) {
-#pragma unroll
-          for (int cb = 0; cb < CB; cb++)
-#pragma unroll
-            for (int vv = 0; vv < 16; vv++) acc[cb][vv] = 0.f;
-          dzacc = 0.f;
-          curid = newid;
           if (newid >= 0) {
             const uint16_t* src = (role == 0 ? p.K : p.V) + ((size_t)newid * p.H_kv + g) * D + 8 * hh;
 #pragma unroll
@@ -621,11 +616,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
             if (PARTIAL) {
               kj = newid;
               ke = p.expiry[(size_t)h * p.T + newid];
-              settle(ke);
             }
-            settle(zq);
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) settle(breg[ks]);
           } else {
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) breg[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
@@ -634,6 +625,19 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
             ke = 0;
           }
         }
+        flush(changed);  // finished keys out, then re-arm the changed columns
+        if (changed) {
+#pragma unroll
+          for (int cb = 0; cb < CB; cb++)
+#pragma unroll
+            for (int vv = 0; vv < 16; vv++) acc[cb][vv] = 0.f;
+          dzacc = 0.f;
+          curid = newid;
+        }
+        if (PARTIAL) settle(ke);
+        settle(zq);
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) settle(breg[ks]);
       }
     }
     if (ncols == 0 || row0 + SUB * qs >= row1) continue;  // nothing to do this step (same for both roles)
