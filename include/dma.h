@@ -40,7 +40,8 @@ extern "C" {
 typedef enum {
   DMA_OK = 0,
   DMA_EINVAL = -1,       /* null pointer, misaligned pointer, T<=0, k<=0, n_docs<=0, H_q % H_kv != 0 */
-  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, more than 32 heads for the cross-head scores,
+  DMA_EUNSUPPORTED = -2, /* d not in {64,128}, unknown dtype, more than 256 q-heads per kv-head,
+                            more than 32 heads for the cross-head scores,
                             bf16 dma_fwd / dma_bwd with T >= 2^24 or Q (or K, V) larger than 4 GiB         */
   DMA_EWORKSPACE = -3,   /* ws_bytes smaller than dma_workspace_bytes() */
   DMA_EHIP = -4          /* a launch failed (hipGetLastError) */
@@ -65,7 +66,14 @@ typedef struct {
 
 /* Size in bytes of the opaque mask plan written by dma_mask_gen (slot table,
  * per-block key lists and scratch of the selection), and of the scratch
- * workspace dma_fwd / dma_bwd need.  0 if the shape is invalid. */
+ * workspace dma_fwd / dma_bwd need.  0 if the shape is invalid.
+ * The plan is not linear in T: its slot table holds one int32 per (q-head, block of
+ * 256 query rows, slot), slots = min(k, max_seqlen) rounded up to 128, i.e. about
+ * H_q * T * min(k, max_seqlen) / 64 bytes, on top of about 40 bytes per (q-head, token)
+ * (scores, expiry, key lists, scratch of the selection).  Examples with H_q = 32: 36 MiB
+ * at T = 16384, k = 2048; 111 MiB at T = 65536, k = 1024; 0.58 GiB at k = 16384; 2.1 GiB
+ * at T = k = 65536 (every key kept: the quadratic corner).  There is no cap: a caller
+ * that sweeps k towards T pays this. */
 size_t dma_mask_bytes(const dma_shape* shape);
 size_t dma_workspace_bytes(const dma_shape* shape);
 

@@ -26,6 +26,8 @@ int check_shape(const dma_shape* s) {
   if (s->d != 64 && s->d != 128) return DMA_EUNSUPPORTED;
   if (s->dtype != DMA_BF16 && s->dtype != DMA_F32) return DMA_EUNSUPPORTED;
   if (s->H_q > 65535 || s->H_kv > 65535) return DMA_EUNSUPPORTED;
+  // the score kernel holds the projection vectors of one kv-head's group in LDS, 256 bytes per q-head
+  if (s->H_q / s->H_kv > 256) return DMA_EUNSUPPORTED;
   return DMA_OK;
 }
 

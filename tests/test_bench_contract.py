@@ -48,5 +48,15 @@ def test_small_config_json_line(gpu):
     assert "workload" in d["config"]
     rf = d["roofline"]
     assert rf["bound"] == "mfma" and rf["peak"] == 2500.0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-12
+    # one record per kernel of the step: the three matrix-core kernels and the HBM-bound score kernel
+    rfs = d["rooflines"]
+    assert set(rfs) == {"fwd_kernel", "dq_kernel", "dkv_kernel<clean>", "z_kernel"} and rf["kernel"] in rfs
+    for name, o in rfs.items():
+        assert o["bound"] == ("hbm" if name == "z_kernel" else "mfma") and o["peak"] == (8000.0 if name == "z_kernel" else 2500.0)
+        assert abs(o["frac"] - o["achieved"] / o["peak"]) < 1e-12
+        assert 0 < o["launch_ms_min"] <= o["launch_ms_median"] and o["launch_ms"] > 0
+    assert 0 < d["step_ms_min"] <= d["step_ms_median"]
+    for st in ("z", "fwd", "bwd_dq", "bwd_dkv", "bwd_part"):
+        assert d["stage_ms_min"][st] <= d["stage_ms_median"][st], st
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]

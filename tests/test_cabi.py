@@ -108,6 +108,12 @@ def test_error_codes_before_any_launch(lib):
     with pytest.raises(B.DmaError) as e:
         B.dma_bwd(huge, p, p, p, p, p, p, p, p, p, p, p, p, p, p, p, 1 << 62, stream=0)
     assert e.value.status == B.DMA_EUNSUPPORTED
+    # the score kernel keeps a group's projection vectors in LDS: more than 256 q-heads per kv-head is refused
+    wide = B.make_shape(T=256, n_docs=1, H_q=257, H_kv=1, d=64, k=64)
+    assert B.dma_mask_bytes(wide) == 0
+    with pytest.raises(B.DmaError) as e:
+        B.dma_mask_gen(wide, p, p, p, p, p, p, None, p, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
     assert B.dma_decode_kept_bytes(ok) >= 2 * 64 * 4
     assert "workspace" in B.strerror(B.DMA_EWORKSPACE)
     assert B.strerror(0) == "ok"
