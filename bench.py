@@ -288,6 +288,7 @@ def main():
     import numpy as np
     import torch
     from paper_2508_02124_amd import binding as B
+    from paper_2508_02124_amd import probe as P
     from paper_2508_02124_amd import workloads as wlmod
 
     if not torch.cuda.is_available():
@@ -313,11 +314,11 @@ def main():
     ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     nwg, iters = 4 * prop.multi_processor_count, 4096
     sink = torch.empty(nwg * 512, device=dev)
-    B.dma_probe_mfma(sink, nwg, 64)
+    P.dma_probe_mfma(sink, nwg, 64)
     best = float("inf")
     for _ in range(3):                                   # best of three 4 ms runs (the clock ramps up)
         ev2[0].record()
-        B.dma_probe_mfma(sink, nwg, iters)
+        P.dma_probe_mfma(sink, nwg, iters)
         ev2[1].record()
         torch.cuda.synchronize()
         best = min(best, ev2[0].elapsed_time(ev2[1]))
@@ -325,11 +326,11 @@ def main():
     cbytes = 1 << 30
     csrc = torch.empty(cbytes, dtype=torch.uint8, device=dev).fill_(3)
     cdst = torch.empty_like(csrc)
-    B.dma_probe_copy(csrc, cdst, cbytes)
+    P.dma_probe_copy(csrc, cdst, cbytes)
     best = float("inf")
     for _ in range(3):
         ev2[0].record()
-        B.dma_probe_copy(csrc, cdst, cbytes)
+        P.dma_probe_copy(csrc, cdst, cbytes)
         ev2[1].record()
         torch.cuda.synchronize()
         best = min(best, ev2[0].elapsed_time(ev2[1]))

@@ -19,8 +19,11 @@
  *     cu_seqlens = {0, L, 2L, ...}.
  *   - q-head h reads kv-head h / (H_q / H_kv) (contiguous grouping).
  *   - The `dma_shape` argument is a HOST pointer, read during the call.
- *   - The caller owns every buffer.  The library allocates nothing, frees
- *     nothing and keeps no pointer after the call returns.
+ *   - The caller owns every buffer.  The compute entry points allocate nothing,
+ *     free nothing and keep no pointer after the call returns.  The library's only
+ *     state between calls: the host array of event handles that dma_profile_events
+ *     was given (per host thread, until it is called with NULL), and the address of
+ *     dma_decode_static's own device scratch array (per GPU).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and the call returns without synchronising.
  *   - Return value: DMA_OK (0) or a negative dma_status.  All argument checks
@@ -116,8 +119,11 @@ int dma_mask_describe(const dma_shape* shape, dma_mask_layout* out);
  *                   indices in ascending order, padded with -1 (debug; O(T k) memory).
  *   mask       out  dma_mask_bytes(shape) bytes; consumed by dma_fwd / dma_bwd.  It also holds
  *                   z / softmax_scale (the attention kernels start their score accumulators
- *                   at it), so dma_fwd / dma_bwd must be called with the same shape,
- *                   softmax_scale included, and z must not change in between.
+ *                   at it) and that softmax_scale itself.  The plan is the authority on both:
+ *                   dma_fwd / dma_bwd read the scores and the scale from it, not from their
+ *                   own z and shape->softmax_scale arguments (which therefore cannot disagree
+ *                   with the stored scores); a changed z or scale needs a new dma_mask_gen.
+ *                   The other fields of the shape must be the ones the plan was made with.
  */
 int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
                  const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,
@@ -269,7 +275,10 @@ int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const 
  * 2 * DMA_N_STAGES hipEvent_t handles (as void*) owned by the caller, or NULL to switch the aid
  * off (the default).  While set -- per host thread -- every entry point records events[2*s] on its
  * stream immediately before stage s and events[2*s + 1] immediately after it.  Nothing is
- * synchronised; the caller reads the events after synchronising the stream itself.
+ * synchronised; the caller reads the events after synchronising the stream itself.  The library
+ * keeps the `events` pointer (not a copy of the array) until the next call of this function on the
+ * same host thread: the array must stay valid that long.  A measurement aid: the step's results do
+ * not depend on it.
  */
 typedef enum {
   DMA_STAGE_Z = 0,          /* mask_gen: block table + content scores (Eq. 3)            */
@@ -285,18 +294,6 @@ typedef enum {
   DMA_N_STAGES = 10
 } dma_stage;
 void dma_profile_events(void** events);
-
-/*
- * Roofline yardsticks measured on the device at hand (not operations of the paper):
- *   dma_probe_mfma  n_workgroups workgroups of 8 waves run `iters` rounds of 8 independent
- *                   32x32x16 bf16 MFMA chains from registers: n_workgroups * 8 * iters * 8 * 32768 flops.
- *                   sink: DEVICE buffer of n_workgroups * 512 floats (receives sums; contents are
- *                   of no interest).
- *   dma_probe_copy  plain streaming copy of `bytes` (a multiple of 16) from src to dst (DEVICE).
- * Both enqueue one kernel on `stream` and return; the caller times them with events.
- */
-int dma_probe_mfma(float* sink, int n_workgroups, int iters, void* stream);
-int dma_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 const char* dma_strerror(int status);
 int dma_version(void);

@@ -87,10 +87,6 @@ def lib():
         L.dma_decode_static.restype = i32
         L.dma_decode_step.argtypes = [shp] + [vp] * 6 + [i32] + [vp] * 3 + [sz, vp]
         L.dma_decode_step.restype = i32
-        L.dma_probe_mfma.argtypes = [vp, i32, i32, vp]
-        L.dma_probe_mfma.restype = i32
-        L.dma_probe_copy.argtypes = [vp, vp, sz, vp]
-        L.dma_probe_copy.restype = i32
         L.dma_profile_events.argtypes = [vp]
         L.dma_profile_events.restype = None
         L.dma_strerror.argtypes = [i32]
@@ -137,14 +133,6 @@ STAGES = ("z", "sort", "expiry", "plan", "fwd", "bwd_zero", "bwd_dq", "bwd_dkv",
 def dma_profile_events(events):
     """events: a ctypes array of 2 * len(STAGES) hipEvent_t handles (c_void_p), or None."""
     lib().dma_profile_events(events)
-
-
-def dma_probe_mfma(sink, n_workgroups, iters, stream=None):
-    _check(lib().dma_probe_mfma(_ptr(sink), int(n_workgroups), int(iters), _stream(stream)), "dma_probe_mfma")
-
-
-def dma_probe_copy(src, dst, nbytes, stream=None):
-    _check(lib().dma_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)), "dma_probe_copy")
 
 
 def dma_mask_bytes(shape):

@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument validation, layout computation, dispatch.  No allocation, no
-// synchronisation, no retained state.
+// synchronisation.  State kept between calls: the caller's array of stage events while
+// dma_profile_events has one set (per host thread), nothing else in this file.
 #include "common.h"
 
 using namespace dma;
@@ -247,16 +248,6 @@ int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const 
 }
 
 void dma_profile_events(void** events) { dma::g_stage_events = events; }
-
-int dma_probe_mfma(float* sink, int n_workgroups, int iters, void* stream) {
-  if (!sink || n_workgroups <= 0 || iters <= 0) return DMA_EINVAL;
-  return launch_probe_mfma(sink, n_workgroups, iters, (hipStream_t)stream);
-}
-
-int dma_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
-  if (!src || !dst || bytes == 0 || bytes % 16 || !aligned16(src) || !aligned16(dst)) return DMA_EINVAL;
-  return launch_probe_copy(src, dst, bytes, (hipStream_t)stream);
-}
 
 const char* dma_strerror(int status) {
   switch (status) {

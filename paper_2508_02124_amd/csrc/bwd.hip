@@ -35,11 +35,10 @@ struct BwdArgs {
   const int32_t* slot_tab;
   const int32_t* pcnt;
   const int32_t* plist;
-  const char* consts;  // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1; +268: float +inf
+  const char* consts;  // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1; +268: float +inf; +272: softmax scale, scale * log2(e)
   int T, H_q, H_kv, k, nblk_cap, kpad;
   int seg;       // query blocks swept by one clean-mode work item of dkv_kernel
   int seg_part;  // ... by one partial-mode work item
-  float scale, c2;
   size_t zero_n4;  // float4 elements from dK32 to the end of dV32 (cleared by dq_kernel)
   size_t dz_n;     // elements of dz (cleared by dq_kernel)
   unsigned grid_dq;  // workgroups of the dq_kernel launch
@@ -89,6 +88,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p)
   const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
   const int32_t* c_zero = reinterpret_cast<const int32_t*>(p.consts + 260);
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
+  const float scale = *reinterpret_cast<const float*>(p.consts + PLAN_SCALE_OFF);
+  const float c2 = *reinterpret_cast<const float*>(p.consts + PLAN_C2_OFF);
 
   // gathered rows: wave-uniform base of the kv-head plus a 32-bit byte offset (id * row pitch + the
   // lane's chunk); an empty slot (id < 0) copies row 0, which its score of -inf keeps out of every sum
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p)
         }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          const float pv = fast_exp2(fmaf(sacc[v], p.c2, -lse2));
+          const float pv = fast_exp2(fmaf(sacc[v], c2, -lse2));
           const float ds = pv * (dpacc[v] - Dsum);
           dsb[v >> 3][v & 7] = (__bf16)ds;
         }
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p)
     for (int gq = 0; gq < 4; gq++) {
       bf16x4 o4;
 #pragma unroll
-      for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[cb][4 * gq + u] * p.scale);
+      for (int u = 0; u < 4; u++) o4[u] = (__bf16)(dqacc[cb][4 * gq + u] * scale);
       *reinterpret_cast<bf16x4*>(&Os[TL::off(32 * w + n, 4 * cb + gq) + 4 * hh]) = o4;
     }
   lds_barrier();
@@ -361,6 +362,8 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   const float* c_zero_f = reinterpret_cast<const float*>(p.consts + 260);
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
   const float* c_pinf = reinterpret_cast<const float*>(p.consts + 268);
+  const float scale = *reinterpret_cast<const float*>(p.consts + PLAN_SCALE_OFF);
+  const float c2 = *reinterpret_cast<const float*>(p.consts + PLAN_C2_OFF);
 
   const int seg = PARTIAL ? p.seg_part : p.seg;
   const int bi_begin = chunk * seg, bi_end = min(bi_begin + seg, p.nblk_cap);
@@ -502,7 +505,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     const unsigned fm = (unsigned)(__ballot(doit) & 0xffffffffull);
     if (fm == 0) return;
     if (role == 1 && doit && hh == 0) atomicAdd(p.dz + (size_t)h * p.T + curid, dzt);
-    const float mul = role == 1 ? p.scale : 1.f;
+    const float mul = role == 1 ? scale : 1.f;
     float* dst = role == 1 ? p.dK32 : p.dV32;
     const bool dense = __popc(fm) > 6;  // many columns (a partial-mode block change, the end of a sweep)
     int* stage_id = reinterpret_cast<int*>(stage);
@@ -681,7 +684,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
 #pragma unroll
       for (int u = 0; u < 4; u++) {
         const int vv = 4 * gq + u;
-        float pv = fast_exp2(fmaf(sacc[vv], p.c2, -ls[u]));
+        float pv = fast_exp2(fmaf(sacc[vv], c2, -ls[u]));
         if (PARTIAL) {
           const int row = row0 + SUB * qs + r + u;
           pv = ((row >= kj) & (row < ke)) ? pv : 0.f;
@@ -742,7 +745,6 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   a.plist = (const int32_t*)(p.plan + L.off_plist);
   a.consts = p.plan + L.off_consts;
   a.T = s.T; a.H_q = s.H_q; a.H_kv = s.H_kv; a.k = s.k; a.nblk_cap = L.nblk_cap; a.kpad = L.kpad;
-  a.scale = p.scale; a.c2 = p.scale * LOG2E;
   {  // sweep length of a clean-mode work item: as long as possible while keeping >= 512 work items
     const long groups = (long)(L.kpad / SG) * s.H_q;
     long seg = (long)L.nblk_cap * groups / 512;

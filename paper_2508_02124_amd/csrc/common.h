@@ -15,6 +15,9 @@ constexpr int SG = 128;        // slot columns per workgroup of the key-stationa
 constexpr int SEG_MIN = 4096;  // keys per segment of the selection (what one workgroup sorts in LDS): 4096 when
 constexpr int SEG_MAX = 16384; // no document is longer than four such segments (more workgroups), else 16384
 constexpr float LOG2E = 1.4426950408889634f;
+// byte offsets in the plan's constant block of the softmax scale the stored z / scale was written with,
+// and of scale * log2(e)
+constexpr int PLAN_SCALE_OFF = 272, PLAN_C2_OFF = 276;
 constexpr float LN2 = 0.6931471805599453f;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -35,7 +38,8 @@ struct PlanLayout {
   int wcap;        // 64-bit words per wavelet level per head (every segment has two spare words)
   int nseg_cap;    // upper bound on the number of segments: T / seg + n_docs + 1
   size_t off_hdr;      // int32[16]: [0] number of blocks
-  size_t off_consts;   // 512 B: [0,256) zeros (a dummy K/V row); then float -inf, int32 0, int32 -1, float +inf
+  size_t off_consts;   // 512 B: [0,256) zeros (a dummy K/V row); then float -inf, int32 0, int32 -1, float +inf,
+                       // float softmax scale, float scale * log2(e) (what zq was divided by: the attention kernels read it here)
   size_t off_zq;       // float[H_q][T]: z / softmax_scale, the bias as the start value of a Q K^T accumulator
   size_t off_blk;      // int4[nblk_cap]: {doc, row0, row1, doc_start}; doc = -1 past the end
   size_t off_docblk;   // int32[n_docs + 1]: first block of each document
@@ -151,8 +155,6 @@ int launch_decode(const dma_shape& s, float scale, const void* q, const void* K,
                   const int32_t* cu, const int32_t* lens, int incremental, void* o, float* lse, int32_t* kept,
                   void* part_and_sel, hipStream_t st);
 
-int launch_probe_mfma(float* sink, int nwg, int iters, hipStream_t st);
-int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 // stage events (see dma_profile_events): no-ops unless the caller armed them on this thread
 void prof_begin(int stage, hipStream_t st);

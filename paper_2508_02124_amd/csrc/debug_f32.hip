@@ -27,11 +27,12 @@ template <int D, int MODE>
 __global__ __launch_bounds__(64) void row_f32_kernel(const float* __restrict__ Q, const float* __restrict__ K,
                                                      const float* __restrict__ V, const float* __restrict__ zq,
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
-                                                     int n_docs, int causal, int T, int H_q, int H_kv, float scale,
+                                                     int n_docs, int causal, int T, int H_q, int H_kv, const float* __restrict__ plan_scale,
                                                      float* __restrict__ O, float* __restrict__ LSE,
                                                      const float* __restrict__ dO, double* __restrict__ Dout,
                                                      float* __restrict__ dQ) {
   const int t = blockIdx.x, h = blockIdx.y, l = threadIdx.x;
+  const float scale = *plan_scale;  // the plan's: the one zq was divided by
   const int g = h / (H_q / H_kv);
   const int doc = find_doc(cu, n_docs, t);
   const int a = cu[doc];
@@ -118,12 +119,13 @@ __global__ __launch_bounds__(64) void key_f32_kernel(const float* __restrict__ Q
                                                      const float* __restrict__ V, const float* __restrict__ zq,
                                                      const int32_t* __restrict__ expiry, const int32_t* __restrict__ cu,
                                                      int n_docs, int causal, int T, int H_q, int H_kv,
-                                                     float scale, const float* __restrict__ LSE,
+                                                     const float* __restrict__ plan_scale, const float* __restrict__ LSE,
                                                      const float* __restrict__ dO, const double* __restrict__ Dws,
                                                      float* __restrict__ dK, float* __restrict__ dV,
                                                      float* __restrict__ dz) {
   constexpr int CPL = D / 64;
   const int t = blockIdx.x, g = blockIdx.y, l = threadIdx.x;
+  const float scale = *plan_scale;
   const int G = H_q / H_kv;
   float kc[CPL], vc[CPL];
   double dk[CPL], dv[CPL];  // sums over up to n rows: accumulated in fp64 so that their rounding stays below 1e-5
@@ -182,12 +184,13 @@ int launch_fwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   const dma_shape& s = p.s;
   (void)z;
   const float* zq = (const float*)(p.plan + p.pl.off_zq);  // the bias as the plan holds it: (z [+ caller bias]) / scale
+  const float* sc = (const float*)(p.plan + p.pl.off_consts + PLAN_SCALE_OFF);  // the scale zq was written with
   dim3 grid(s.T, s.H_q);
   if (s.d == 128)
-    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, O, LSE,
                                                 nullptr, nullptr, nullptr);
   else
-    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, O, LSE,
+    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, O, LSE,
                                                nullptr, nullptr, nullptr);
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
@@ -198,16 +201,17 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   const dma_shape& s = p.s;
   (void)z;
   const float* zq = (const float*)(p.plan + p.pl.off_zq);
+  const float* sc = (const float*)(p.plan + p.pl.off_consts + PLAN_SCALE_OFF);
   double* Dws = (double*)ws;
   dim3 grid(s.T, s.H_q), gridk(s.T, s.H_kv);
   if (s.d == 128) {
-    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
+    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc,
                                                 const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, LSE, dO, Dws, dK, dV, dz);
   } else {
-    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale,
+    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc,
                                                const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, p.scale, LSE, dO, Dws, dK, dV, dz);
+    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, LSE, dO, Dws, dK, dV, dz);
   }
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }

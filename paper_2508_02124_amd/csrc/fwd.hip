@@ -29,9 +29,8 @@ struct FwdArgs {
   const int32_t* slot_tab;
   const int32_t* pcnt;
   const int32_t* plist;
-  const char* consts;   // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1
+  const char* consts;   // [0,256) zeros; +256: float -inf; +260: int 0; +264: int -1; +272: softmax scale, scale * log2(e)
   int T, H_q, H_kv, k, nblk_cap, kpad;
-  float c2;  // softmax scale * log2(e)
 };
 
 constexpr float MSLACK = 8.f;  // log2 slack of the lazily updated softmax reference maximum
@@ -81,6 +80,7 @@ __global__ __launch_bounds__(NW * 64, D == 64 ? 4 : (NW == 8 ? 1 : 2)) void fwd_
   const float* c_ninf = reinterpret_cast<const float*>(p.consts + 256);
   const int32_t* c_zero = reinterpret_cast<const int32_t*>(p.consts + 260);
   const int32_t* c_m1 = reinterpret_cast<const int32_t*>(p.consts + 264);
+  const float c2 = *reinterpret_cast<const float*>(p.consts + PLAN_C2_OFF);  // softmax scale * log2(e)
 
   // ---- asynchronous producers (every wave issues the same number of copies for every tile index,
   // real or past the end, so the outstanding-copy counts below are constants).  A gathered row is
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(NW * 64, D == 64 ? 4 : (NW == 8 ? 1 : 2)) void fwd_
     float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
     for (int v = 1; v < 16; v++) mx = fmaxf(fmaxf(mx, sacc[0][v]), sacc[1][v]);  // one three-input maximum each
-    mx = half_swap_max(mx) * p.c2;
+    mx = half_swap_max(mx) * c2;
     const bool grow = mx > m_run + MSLACK;
     if (__any(grow)) {
       const float m_new = grow ? mx : m_run;
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(NW * 64, D == 64 ? 4 : (NW == 8 ? 1 : 2)) void fwd_
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int v = 0; v < 16; v++) {
-        const float pv = fast_exp2(fmaf(sacc[kb][v], p.c2, -msub));
+        const float pv = fast_exp2(fmaf(sacc[kb][v], c2, -msub));
         if (kb == 0) lsum += pv; else ls2 += pv;
         pb[2 * kb + (v >> 3)][v & 7] = (__bf16)pv;
       }
@@ -337,7 +337,6 @@ int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   a.plist = (const int32_t*)(p.plan + L.off_plist);
   a.consts = p.plan + L.off_consts;
   a.T = s.T; a.H_q = s.H_q; a.H_kv = s.H_kv; a.k = s.k; a.nblk_cap = L.nblk_cap; a.kpad = L.kpad;
-  a.c2 = p.scale * LOG2E;
   prof_begin(DMA_STAGE_FWD, st);
   // Small problems (fewer than four 256-row blocks per compute unit, e.g. 2 x 4096 tokens x 16 heads) run
   // the half-block variant: twice as many, shorter work items balance better over the chip (-7 % there);

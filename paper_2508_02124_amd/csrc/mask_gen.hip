@@ -21,13 +21,17 @@
 namespace dma {
 
 // The plan's constant block: a zero K/V row for empty slots, then the -inf / 0 / -1 / +inf scalars
-// the asynchronous copies point at for empty ids (words 64, 65, 66, 67).
-__device__ __forceinline__ void plan_consts(uint32_t* consts, size_t i) {
+// the asynchronous copies point at for empty ids (words 64, 65, 66, 67), then the softmax scale that
+// z / scale is written with and scale * log2(e) (words 68, 69): the attention kernels take the scale
+// from here, so it cannot differ from the one in the stored scores.
+__device__ __forceinline__ void plan_consts(uint32_t* consts, size_t i, float scale) {
   if (i < 128) {
     uint32_t v = 0u;
     if (i == 64) v = 0xff800000u;       // float -inf
     if (i == 66) v = 0xffffffffu;       // int -1
     if (i == 67) v = 0x7f800000u;       // float +inf
+    if (i == 68) v = __float_as_uint(scale);
+    if (i == 69) v = __float_as_uint(scale * LOG2E);
     consts[i] = v;
   }
 }
@@ -37,9 +41,9 @@ __device__ __forceinline__ void plan_consts(uint32_t* consts, size_t i) {
 // number of resident slot columns of the block.  Causal: w = first row of the document (the keys
 // before the block); otherwise every block of a document has min(k, n) columns.
 __global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int nblk_cap, int k, int causal, int4* blk,
-                               int32_t* docblk, int32_t* hdr, uint32_t* consts) {
+                               int32_t* docblk, int32_t* hdr, uint32_t* consts, float scale) {
   __shared__ int s_total;
-  plan_consts(consts, threadIdx.x);
+  plan_consts(consts, threadIdx.x, scale);
   if (threadIdx.x == 0) {
     int acc = 0;
     for (int d = 0; d < n_docs; d++) {
@@ -786,7 +790,7 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
 
   prof_begin(DMA_STAGE_Z, st);
   blkinfo_kernel<<<1, 256, 0, st>>>(cu, s.n_docs, L.nblk_cap, s.k, s.causal, blk, docblk, hdr,
-                                   (uint32_t*)(base + L.off_consts));
+                                   (uint32_t*)(base + L.off_consts), p.scale);
   float* zq = (float*)(base + L.off_zq);
   const float inv_scale = 1.0f / p.scale;
   if (W) {

@@ -1,6 +1,8 @@
-// Measurement aids for the roofline report (no part of the method): the rate the matrix cores reach
-// from registers alone with the instruction the attention kernels use, and a plain streaming copy.
+// Measurement aids for the roofline report (no part of the method, and a library of their own:
+// libdma_probe.so, include/dma_probe.h): the rate the matrix cores reach from registers alone with the
+// instruction the attention kernels use, and a plain streaming copy.
 #include "common.h"
+#include "../../include/dma_probe.h"
 
 namespace dma {
 
@@ -37,14 +39,21 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict
   for (; i < n16; i += st) dst[i] = src[i];
 }
 
-int launch_probe_mfma(float* sink, int nwg, int iters, hipStream_t st) {
-  probe_mfma_kernel<<<nwg, 512, 0, st>>>(sink, iters);
-  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
-}
-
-int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
-  probe_copy_kernel<<<8192, 256, 0, st>>>((const uint4*)src, (uint4*)dst, bytes / 16);
-  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
-}
-
 }  // namespace dma
+
+extern "C" {
+
+int dma_probe_mfma(float* sink, int n_workgroups, int iters, void* stream) {
+  if (!sink || n_workgroups <= 0 || iters <= 0) return DMA_EINVAL;
+  dma::probe_mfma_kernel<<<n_workgroups, 512, 0, (hipStream_t)stream>>>(sink, iters);
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
+int dma_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  const bool aligned = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0;
+  if (!src || !dst || bytes == 0 || bytes % 16 || !aligned) return DMA_EINVAL;
+  dma::probe_copy_kernel<<<8192, 256, 0, (hipStream_t)stream>>>((const uint4*)src, (uint4*)dst, bytes / 16);
+  return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
+}
+
+}  // extern "C"

@@ -212,6 +212,30 @@ def run_backward(gpu, wl, dtype):
     check_gradients(case, zg, dtype)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_plan_decides_the_softmax_scale(gpu, dtype):
+    """The plan holds z / scale and the scale itself; dma_fwd / dma_bwd take both from it, so a shape
+    whose softmax_scale differs from the one given to dma_mask_gen cannot split the scores from their bias."""
+    print(f"[case] plan-authoritative scale {dtype}", flush=True)
+    wl = wlmod.small_workload("scale_in_plan", 31, 4, 2, 64 if dtype == "f32" else 128, 40, (300, 45))
+    inp = wlmod.make_inputs(wl, dtype=dtype)
+    case = DeviceCase(inp, gpu)
+    case.shape.softmax_scale = 0.2
+    case.mask_gen()
+    case.shape.softmax_scale = 0.9            # not the plan's: must be ignored
+    case.fwd()
+    case.bwd()
+    zg = case.host("z").astype(np.float64)
+    t = tol(dtype == "bf16")
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k, scale=0.2)
+    check_close("O", case.host("O"), O, **t)
+    check_close("LSE", case.host("LSE"), LSE, **t)
+    dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, scale=0.2,
+                                      O_stored=case.host("O") if dtype == "bf16" else None)
+    for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
+        check_close(nm, case.host(nm), ref, **t)
+
+
 @pytest.mark.parametrize("name", ["cfg1", "ragged_varlen_d64", "multi_tile_d128", "gqa8_d64", "many_tiny_docs"])
 def test_backward_on_reference_forward_results(gpu, name):
     """dma_bwd as an entry point of its own: O and LSE are inputs.  It is handed the oracle's forward
