@@ -430,6 +430,12 @@ __global__ __launch_bounds__(256) void expiry_kernel(SortArgs p) {
 // the lower index, i.e. to the earlier segment).  Those same counts say how many of the keys ranked
 // ahead of it lie in each segment, so the k-th smallest index among them is found by walking the
 // segments in index order and asking the wavelet matrix of the one that holds it.
+// RANK (no causal restriction): only the key's rank in the whole document is needed (every segment is
+// searched).  Otherwise only the expiry is: the segments are searched in index order and the walk stops
+// at the one that holds the k-th earlier-ranked key -- for most keys of a long document the first
+// segment already holds k better keys, and an answer in an earlier segment needs no quantile query
+// (every index there is below the key's own, so the key is never kept).
+template <bool RANK>
 __global__ __launch_bounds__(256) void merge_expiry_kernel(SortArgs p) {
   const int t = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
   if (t >= p.T) return;
@@ -454,32 +460,26 @@ __global__ __launch_bounds__(256) void merge_expiry_kernel(SortArgs p) {
     }
     return lo;
   };
-  constexpr int NC = 8;  // counts kept in registers (documents of up to 8 segments search only once)
-  int cnt[NC];
-  int R = 0;
-#pragma unroll
-  for (int s = 0; s < NC; s++) {
-    cnt[s] = s < nseg ? before(s) : 0;
-    R += cnt[s];
+  if (RANK) {
+    int R = 0;
+    for (int s = 0; s < nseg; s++) R += before(s);
+    p.si0[hd + R] = (uint32_t)j;  // rank order of the whole document
+    return;
   }
-  for (int s = NC; s < nseg; s++) R += before(s);
-  p.si0[hd + R] = (uint32_t)j;  // rank order of the whole document
   int e = b;
-  if (R >= p.k) {
-    uint32_t kk = (uint32_t)p.k - 1u;
-    for (int s = 0; s < nseg; s++) {
-      int cs = 0;
-#pragma unroll
-      for (int q = 0; q < NC; q++) cs = s == q ? cnt[q] : cs;
-      const uint32_t c = (uint32_t)(s < NC ? cs : before(s));
-      if (kk < c) {
+  uint32_t kk = (uint32_t)p.k - 1u;
+  for (int s = 0; s < nseg; s++) {
+    const uint32_t c = (uint32_t)before(s);
+    if (kk < c) {
+      e = a + j;
+      if (s >= ps) {
         const int ns = min(SEG, n - s * SEG);
         const int val = (int)wavelet_kth(p, h, seg_slot(SEG, a, d, s), seg_woff(SEG, a, d, s), dev_ceil_log2(ns), c, kk);
         e = a + max(j, s * SEG + val);
-        break;
       }
-      kk -= c;
+      break;
     }
+    kk -= c;
   }
   p.expiry[hd + j] = e;
 }
@@ -840,16 +840,15 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
     prof_begin(DMA_STAGE_PLAN, st);
     fill(slot_tab, (size_t)s.H_q * L.nblk_cap * L.kpad, -1);
     fill(pcnt, (size_t)s.H_q * L.nblk_cap, 0);
-    // (documents of several segments get their whole-document rank order from the merge kernel; the
-    // causal expiry it also writes is overwritten below)
-    if (s.T > L.seg) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    // (documents of several segments get their whole-document rank order from the merge kernel)
+    if (s.T > L.seg) merge_expiry_kernel<true><<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     noncausal_plan_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(cu, s.n_docs, sa.si0, docblk, expiry, slot_tab,
                                                                         s.T, s.k, L.nblk_cap, L.kpad);
   } else {
     prof_begin(DMA_STAGE_EXPIRY, st);
     // (documents of one segment / of several segments; a single document is one or the other)
     if (s.n_docs > 1 || s.T <= L.seg) expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
-    if (s.T > L.seg) merge_expiry_kernel<<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
+    if (s.T > L.seg) merge_expiry_kernel<false><<<dim3((s.T + 255) / 256, s.H_q), 256, 0, st>>>(sa);
     prof_end(DMA_STAGE_EXPIRY, st);
     prof_begin(DMA_STAGE_PLAN, st);
     slot_kernel<<<dim3(s.n_docs, s.H_q), 1024, 0, st>>>(cu, expiry, parent, slotid, s.T, s.k);

@@ -361,7 +361,7 @@ def test_documents_of_several_segments_next_to_short_ones(gpu, causal):
 
 
 def test_document_of_ten_segments(gpu):
-    """More segments than the merge kernel keeps counts for in registers (8): one 150000-token document."""
+    """A long walk over the selection's segments: one 150000-token document (ten segments of 16384 keys)."""
     print("[case] 150000-token document (10 segments), expiry exhaustive, sampled rows", flush=True)
     wl = wlmod.Workload("tenseg", 1008, H_q=2, H_kv=1, d=64, k=1000, seqlens=(150000,), backward=False)
     inp = wlmod.make_inputs(wl)
