@@ -42,18 +42,31 @@ __device__ __forceinline__ void plan_consts(uint32_t* consts, size_t i, float sc
 // before the block); otherwise every block of a document has min(k, n) columns.
 __global__ void blkinfo_kernel(const int32_t* __restrict__ cu, int n_docs, int nblk_cap, int k, int causal, int4* blk,
                                int32_t* docblk, int32_t* hdr, uint32_t* consts, float scale) {
-  __shared__ int s_total;
+  __shared__ int s_total, s_scan[256];
   plan_consts(consts, threadIdx.x, scale);
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int d = 0; d < n_docs; d++) {
-      docblk[d] = acc;
-      int n = cu[d + 1] - cu[d];
-      acc += (n + BQ - 1) / BQ;
+  // docblk = exclusive prefix sum of the documents' block counts: 256 documents per round, a
+  // Hillis-Steele scan in LDS inside the round, the running total carried between rounds
+  const int tid = threadIdx.x;
+  int base = 0;
+  for (int d0 = 0; d0 < n_docs; d0 += 256) {
+    const int d = d0 + tid;
+    const int nb = d < n_docs ? (cu[d + 1] - cu[d] + BQ - 1) / BQ : 0;
+    s_scan[tid] = nb;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+      const int v = tid >= off ? s_scan[tid - off] : 0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
     }
-    docblk[n_docs] = acc;
-    hdr[0] = acc;
-    s_total = acc;
+    if (d < n_docs) docblk[d] = base + s_scan[tid] - nb;
+    base += s_scan[255];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    docblk[n_docs] = base;
+    hdr[0] = base;
+    s_total = base;
   }
   __syncthreads();
   for (int i = threadIdx.x; i < s_total; i += blockDim.x) {  // one block per thread
