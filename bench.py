@@ -228,7 +228,7 @@ def roofline_objects(wl, inp, case, rec, with_traffic):
     return kernel_names[dom], objs
 
 
-SWEEP = [("cfg2", 0), ("cfg5", 0), ("cfg3", 512), ("cfg3", 1024), ("cfg3", 0),
+SWEEP = [("cfg2", 0), ("cfg5", 0), ("cfg3", 512), ("cfg3", 1024), ("cfg3", 0), ("cfg3_d256", 0),
          ("cfg4", 1024), ("cfg4", 4096), ("cfg4", 16384), ("cfg4", 65536)]
 
 
@@ -269,7 +269,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default=HEADLINE, help="cfg1..cfg5 (default: the headline shape)")
+    ap.add_argument("--config", default=HEADLINE, help="cfg1..cfg5 or cfg3_d256 (default: the headline shape)")
     ap.add_argument("--k", type=int, default=0, help="override the keep-window (cfg4 sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
@@ -374,7 +374,7 @@ def main():
         out["mask_bwd"] = {"ms": mb_ms, "algorithmic_bytes": mb_bytes, "GB/s": mb_bytes / (mb_ms * 1e-3) / 1e9,
                            "hbm_peak_GB/s": 8000.0}
         # not part of the step: the scores from the full cross-head Delta (Eq. 3) and their chain rule
-        if wl.H_q <= 32:
+        if wl.H_q <= 32 and wl.d <= 128:     # (the cross-head kernels take head dimensions 64 and 128)
             Dl = torch.randn((wl.H_q, wl.H_kv * wl.d), device=dev) / float(np.sqrt(wl.H_kv * wl.d))
             dDl = torch.empty_like(Dl)
             zx = torch.empty_like(case.z)

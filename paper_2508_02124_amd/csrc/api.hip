@@ -19,12 +19,14 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_shape(const dma_shape* s) {
+// max_d: 256 for the entry points of the training step (mask generation, forward, backward, the score
+// gradient, their size queries and the bias reductions), 128 for the others (cross-head scores, decode).
+int check_shape(const dma_shape* s, int max_d = 128) {
   if (!s) return DMA_EINVAL;
   if (s->T <= 0 || s->n_docs <= 0 || s->k <= 0 || s->H_q <= 0 || s->H_kv <= 0) return DMA_EINVAL;
   if (s->H_q % s->H_kv != 0) return DMA_EINVAL;
   if (s->softmax_scale < 0.f || s->softmax_scale != s->softmax_scale) return DMA_EINVAL;
-  if (s->d != 64 && s->d != 128) return DMA_EUNSUPPORTED;
+  if (s->d != 64 && s->d != 128 && !(s->d == 256 && max_d >= 256)) return DMA_EUNSUPPORTED;
   if (s->dtype != DMA_BF16 && s->dtype != DMA_F32) return DMA_EUNSUPPORTED;
   if (s->H_q > 65535 || s->H_kv > 65535) return DMA_EUNSUPPORTED;
   // the score kernel holds the projection vectors of one kv-head's group in LDS, 256 bytes per q-head
@@ -62,17 +64,17 @@ Ptrs make_ptrs(const dma_shape* s, const void* mask) {
 extern "C" {
 
 size_t dma_mask_bytes(const dma_shape* shape) {
-  if (check_shape(shape) != DMA_OK) return 0;
+  if (check_shape(shape, 256) != DMA_OK) return 0;
   return plan_layout(*shape).total;
 }
 
 size_t dma_workspace_bytes(const dma_shape* shape) {
-  if (check_shape(shape) != DMA_OK) return 0;
+  if (check_shape(shape, 256) != DMA_OK) return 0;
   return ws_bytes_for(*shape);
 }
 
 int dma_mask_describe(const dma_shape* shape, dma_mask_layout* out) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!out) return DMA_EINVAL;
   const PlanLayout L = plan_layout(*shape);
@@ -87,7 +89,7 @@ int dma_mask_describe(const dma_shape* shape, dma_mask_layout* out) {
 int dma_mask_gen(const dma_shape* shape, const void* V, const float* W, const float* A,
                  const int32_t* cu_seqlens, float* z, int32_t* expiry, int32_t* topk_idx,
                  void* mask, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!cu_seqlens || !z || !expiry || !mask) return DMA_EINVAL;
   if (W && (!V || !A)) return DMA_EINVAL;
@@ -106,7 +108,7 @@ static int check_bias(const dma_shape* s, const float* bias, int bias_heads, int
 int dma_mask_gen_bias(const dma_shape* shape, const void* V, const float* W, const float* A,
                       const int32_t* cu_seqlens, const float* bias, int32_t bias_heads, int32_t bias_per_token,
                       float* z, int32_t* expiry, int32_t* topk_idx, void* mask, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if ((rc = check_bias(shape, bias, bias_heads, bias_per_token)) != DMA_OK) return rc;
   if ((rc = dma_mask_gen(shape, V, W, A, cu_seqlens, z, expiry, topk_idx, mask, stream)) != DMA_OK) return rc;
@@ -116,7 +118,7 @@ int dma_mask_gen_bias(const dma_shape* shape, const void* V, const float* W, con
 
 int dma_bias_bwd(const dma_shape* shape, const float* dz, const int32_t* cu_seqlens, int32_t bias_heads,
                  int32_t bias_per_token, float* dbias, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!dz || !cu_seqlens || !aligned16(dz)) return DMA_EINVAL;
   if ((rc = check_bias(shape, dbias, bias_heads, bias_per_token)) != DMA_OK) return rc;
@@ -128,7 +130,7 @@ int dma_fwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
             void* O, float* LSE, void* ws, size_t ws_bytes, void* stream) {
   (void)ws;
   (void)ws_bytes;
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!Q || !K || !V || !z || !expiry || !mask || !cu_seqlens || !O || !LSE) return DMA_EINVAL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(z) || !aligned16(LSE) ||
@@ -146,7 +148,7 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
             const void* dO, const float* LSE, const float* z, const int32_t* expiry,
             const void* mask, const int32_t* cu_seqlens,
             void* dQ, void* dK, void* dV, float* dz, void* ws, size_t ws_bytes, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!Q || !K || !V || !O || !dO || !LSE || !z || !expiry || !mask || !cu_seqlens || !dQ || !dK || !dV || !dz)
     return DMA_EINVAL;
@@ -166,7 +168,7 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
 
 int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const float* A, const float* dz,
                  float* dW, float* dA, void* dV, int accumulate, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!V || !W || !A || !dz || !dW || !dA || !dV) return DMA_EINVAL;
   if (!aligned16(V) || !aligned16(W) || !aligned16(dz) || !aligned16(dW) || !aligned16(dV)) return DMA_EINVAL;
@@ -253,13 +255,13 @@ const char* dma_strerror(int status) {
   switch (status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
-    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64 or 128, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: Q, K, V at most 4 GiB each, fewer than 2^24 tokens)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64, 128 or 256 -- 256 for mask generation, forward and backward only --, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: Q, K, V at most 4 GiB each, fewer than 2^24 tokens)";
     case DMA_EWORKSPACE: return "workspace missing or too small (dma_workspace_bytes, dma_decode_kept_bytes), or the shape needs more than the library-owned scratch of dma_decode_static";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";
   }
 }
 
-int dma_version(void) { return 130; }
+int dma_version(void) { return 140; }
 
 }  // extern "C"

@@ -48,7 +48,7 @@ struct BwdArgs {
 // NW waves per workgroup: 8 (a whole 256-row block, four ring stages) or 4 (half a block, two ring
 // stages, two workgroups per compute unit), as in the forward kernel.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void dq_kernel(BwdArgs p) {
+__global__ __launch_bounds__(NW * 64, (NW == 8 || D == 256) ? 1 : 2) void dq_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
   constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, WL = KT / RPL / NW;
   constexpr int NS = NW == 8 ? 4 : 2, TILE = KT * D, NT = NW * 64, HALVES = 8 / NW;
@@ -334,15 +334,17 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   constexpr int SUB = 32;                 // query rows per pipeline step
   constexpr int NSUB = BQ / SUB;          // steps per query block
   constexpr int NWL = 2 * (SUB / RPL);    // 16-byte wave copies per step (Q rows, then dO rows)
-  constexpr int NS = 5;                   // ring stages
+  constexpr int NS = D == 256 ? 3 : 5;    // ring stages (a stage of 512-byte rows is 32 KiB)
   constexpr int STILE = SUB * D;
   constexpr int LDS_ST = 32 + 4;          // staging row: the 32 channels of one flush pass, padded
+  constexpr int NCH = D == 256 ? 2 : 1;   // column halves of a flush pass (LDS is short at 256 channels)
+  constexpr int STC = 32 / NCH;           // columns staged at a time
   __shared__ __align__(16) uint16_t ringQ[NS * STILE];
   __shared__ __align__(16) uint16_t ringdO[NS * STILE];
   __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) D
   __shared__ __align__(16) int idbuf[2][SG];     // column ids of the current / next block
   __shared__ __align__(16) int4 binfo[MAXSWEEP + 1];  // block table of this work item's sweep
-  __shared__ __align__(16) float stage_all[8 * 32 * LDS_ST];  // per wave: [32 columns][32 channels] fp32, flush staging
+  __shared__ __align__(16) float stage_all[8 * STC * LDS_ST];  // per wave: [STC columns][32 channels] fp32, flush staging
   __shared__ __align__(16) f32x4 pbuf[2][4][4][64];  // P hand-off (fp32): [step parity][column block][row group][lane]
 
   const int ngrp = PARTIAL ? MAXPART / SG : p.kpad / SG;
@@ -495,7 +497,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     for (int v = 0; v < 16; v++) acc[cb][v] = 0.f;
   float dzacc = 0.f;
 
-  float* stage = stage_all + w * 32 * LDS_ST;
+  float* stage = stage_all + w * STC * LDS_ST;
   // Flush the columns whose lanes pass doit = true (wave-uniform call).  The accumulator is
   // transposed through the wave's LDS staging area, 32 channels at a time, so that
   // each atomic instruction adds consecutive channels of one key.
@@ -509,41 +511,47 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     float* dst = role == 1 ? p.dK32 : p.dV32;
     const bool dense = __popc(fm) > 6;  // many columns (a partial-mode block change, the end of a sweep)
     int* stage_id = reinterpret_cast<int*>(stage);
-    if (dense && hh == 0) stage_id[n * LDS_ST + 32] = doit ? curid : -1;
+    if (NCH == 1 && dense && hh == 0) stage_id[n * LDS_ST + 32] = doit ? curid : -1;
 #pragma unroll
     for (int cb = 0; cb < CB; cb++) {
-      if (doit) {
 #pragma unroll
-        for (int gq = 0; gq < 4; gq++) {
-          f32x4 v4;
+      for (int ch = 0; ch < NCH; ch++) {  // columns STC * ch .. + STC - 1 of the wave's 32
+        const bool mine = NCH == 1 || (n >> 4) == ch;
+        const int sr = n & (STC - 1);     // staging row of this lane's column
+        if (NCH > 1 && dense && hh == 0 && mine) stage_id[sr * LDS_ST + 32] = doit ? curid : -1;
+        if (doit && mine) {
 #pragma unroll
-          for (int u = 0; u < 4; u++) v4[u] = acc[cb][4 * gq + u] * mul;
-          *reinterpret_cast<f32x4*>(&stage[n * LDS_ST + 8 * gq + 4 * hh]) = v4;
-        }
-      }
-      if (dense) {
-        // every pass handles the column pair (2i, 2i+1): the ids sit in the padding of the staging
-        // rows, so the 16 passes are independent of each other and pipeline
+          for (int gq = 0; gq < 4; gq++) {
+            f32x4 v4;
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-          const int c = 2 * i + hh;
-          const int id = stage_id[c * LDS_ST + 32];
-          if (id >= 0) atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
-        }
-      } else {
-        unsigned m = fm;
-        while (m) {  // two flushed columns per pass: lanes 0-31 and 32-63 take one column each
-          const int c0 = __ffs(m) - 1;
-          m &= m - 1;
-          int c1 = c0;
-          if (m) {
-            c1 = __ffs(m) - 1;
-            m &= m - 1;
+            for (int u = 0; u < 4; u++) v4[u] = acc[cb][4 * gq + u] * mul;
+            *reinterpret_cast<f32x4*>(&stage[sr * LDS_ST + 8 * gq + 4 * hh]) = v4;
           }
-          const int c = hh == 0 ? c0 : c1;
-          const int id = __shfl(curid, c);
-          if (hh == 0 || c1 != c0)
-            atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
+        }
+        if (dense) {
+          // every pass handles the column pair (2i, 2i+1): the ids sit in the padding of the staging
+          // rows, so the passes are independent of each other and pipeline
+#pragma unroll
+          for (int i = 0; i < STC / 2; i++) {
+            const int c = 2 * i + hh;
+            const int id = stage_id[c * LDS_ST + 32];
+            if (id >= 0) atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[c * LDS_ST + n]);
+          }
+        } else {
+          unsigned m = NCH == 1 ? fm : fm & (0xffffu << (16 * ch));
+          while (m) {  // two flushed columns per pass: lanes 0-31 and 32-63 take one column each
+            const int c0 = __ffs(m) - 1;
+            m &= m - 1;
+            int c1 = c0;
+            if (m) {
+              c1 = __ffs(m) - 1;
+              m &= m - 1;
+            }
+            const int c = hh == 0 ? c0 : c1;
+            const int id = __shfl(curid, c);
+            if (hh == 0 || c1 != c0)
+              atomicAdd(dst + ((size_t)id * p.H_kv + g) * D + 32 * cb + n, stage[(c & (STC - 1)) * LDS_ST + n]);
+          }
         }
       }
     }
@@ -760,21 +768,25 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   a.dz_n = (size_t)s.H_q * s.T;
   prof_begin(DMA_STAGE_BWD_ZERO, st);  // (an empty stage: dq_kernel clears the accumulators)
   prof_end(DMA_STAGE_BWD_ZERO, st);
-  const unsigned gq = xcd_grid(s.H_q, L.nblk_cap);
+  // (at 256 channels the query-stationary kernels run as half blocks: four waves with the whole register file each)
+  const unsigned gq = s.d == 256 ? xcd_grid(s.H_q, 2l * L.nblk_cap) : xcd_grid(s.H_q, L.nblk_cap);
   a.grid_dq = gq;
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
   const unsigned gpart = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg_part - 1) / a.seg_part) * (MAXPART / SG));
   prof_begin(DMA_STAGE_BWD_DQ, st);
   // (the half-block variant, NW = 4, measured the same or slower at every benchmark shape)
-  if (s.d == 128) dq_kernel<128, 8><<<gq, 512, 0, st>>>(a);
+  if (s.d == 256) dq_kernel<256, 4><<<gq, 256, 0, st>>>(a);
+  else if (s.d == 128) dq_kernel<128, 8><<<gq, 512, 0, st>>>(a);
   else dq_kernel<64, 8><<<gq, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_DQ, st);
   prof_begin(DMA_STAGE_BWD_DKV, st);
-  if (s.d == 128) dkv_kernel<128, false><<<gclean, 512, 0, st>>>(a);
+  if (s.d == 256) dkv_kernel<256, false><<<gclean, 512, 0, st>>>(a);
+  else if (s.d == 128) dkv_kernel<128, false><<<gclean, 512, 0, st>>>(a);
   else dkv_kernel<64, false><<<gclean, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_DKV, st);
   prof_begin(DMA_STAGE_BWD_PART, st);
-  if (s.d == 128) dkv_kernel<128, true><<<gpart, 512, 0, st>>>(a);
+  if (s.d == 256) dkv_kernel<256, true><<<gpart, 512, 0, st>>>(a);
+  else if (s.d == 128) dkv_kernel<128, true><<<gpart, 512, 0, st>>>(a);
   else dkv_kernel<64, true><<<gpart, 512, 0, st>>>(a);
   prof_end(DMA_STAGE_BWD_PART, st);
   prof_begin(DMA_STAGE_BWD_CVT, st);

@@ -187,6 +187,10 @@ template <> struct TileLayout<128> {
   static __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
   static __device__ __forceinline__ int off(int r, int c) { return r * 128 + ((c ^ swz(r)) << 3); }
 };
+template <> struct TileLayout<256> {  // rows of 32 chunks: the low four chunk bits are swizzled as at 128
+  static __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+  static __device__ __forceinline__ int off(int r, int c) { return r * 256 + ((c ^ swz(r)) << 3); }
+};
 template <> struct TileLayout<64> {
   static __device__ __forceinline__ int swz(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
   static __device__ __forceinline__ int off(int r, int c) { return r * 64 + ((c ^ swz(r)) << 3); }

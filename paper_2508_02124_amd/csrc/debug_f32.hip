@@ -186,12 +186,13 @@ int launch_fwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   const float* zq = (const float*)(p.plan + p.pl.off_zq);  // the bias as the plan holds it: (z [+ caller bias]) / scale
   const float* sc = (const float*)(p.plan + p.pl.off_consts + PLAN_SCALE_OFF);  // the scale zq was written with
   dim3 grid(s.T, s.H_q);
-  if (s.d == 128)
-    row_f32_kernel<128, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, O, LSE,
-                                                nullptr, nullptr, nullptr);
-  else
-    row_f32_kernel<64, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, O, LSE,
-                                               nullptr, nullptr, nullptr);
+#define DMA_ROW0(DD) \
+  row_f32_kernel<DD, 0><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, O, LSE, \
+                                             nullptr, nullptr, nullptr)
+  if (s.d == 256) DMA_ROW0(256);
+  else if (s.d == 128) DMA_ROW0(128);
+  else DMA_ROW0(64);
+#undef DMA_ROW0
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
 
@@ -204,15 +205,17 @@ int launch_bwd_f32(const Ptrs& p, const float* Q, const float* K, const float* V
   const float* sc = (const float*)(p.plan + p.pl.off_consts + PLAN_SCALE_OFF);
   double* Dws = (double*)ws;
   dim3 grid(s.T, s.H_q), gridk(s.T, s.H_kv);
-  if (s.d == 128) {
-    row_f32_kernel<128, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc,
-                                                const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<128><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, LSE, dO, Dws, dK, dV, dz);
-  } else {
-    row_f32_kernel<64, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc,
-                                               const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);
-    key_f32_kernel<64><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, LSE, dO, Dws, dK, dV, dz);
-  }
+#define DMA_BWD32(DD)                                                                                                    \
+  do {                                                                                                                   \
+    row_f32_kernel<DD, 1><<<grid, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc,        \
+                                               const_cast<float*>(O), const_cast<float*>(LSE), dO, Dws, dQ);             \
+    key_f32_kernel<DD><<<gridk, 64, 0, st>>>(Q, K, V, zq, expiry, cu, s.n_docs, s.causal, s.T, s.H_q, s.H_kv, sc, LSE, dO, \
+                                             Dws, dK, dV, dz);                                                           \
+  } while (0)
+  if (s.d == 256) DMA_BWD32(256);
+  else if (s.d == 128) DMA_BWD32(128);
+  else DMA_BWD32(64);
+#undef DMA_BWD32
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
 

@@ -42,7 +42,7 @@ constexpr float MSLACK = 8.f;  // log2 slack of the lazily updated softmax refer
 // two ring stages, two workgroups per compute unit: the two waves of a SIMD then belong to different
 // workgroups and do not meet at the same barriers).
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, D == 64 ? 4 : (NW == 8 ? 1 : 2)) void fwd_kernel(FwdArgs p) {
+__global__ __launch_bounds__(NW * 64, D == 64 ? 4 : ((NW == 8 || D == 256) ? 1 : 2)) void fwd_kernel(FwdArgs p) {
   using TL = TileLayout<D>;
   constexpr int KS = D / 16;          // contraction steps of K Q^T
   constexpr int CB = D / 32;          // 32-channel blocks of O^T
@@ -342,7 +342,10 @@ int launch_fwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   // the half-block variant: twice as many, shorter work items balance better over the chip (-7 % there);
   // at the headline size the two variants measure the same and the whole-block one gathers half as much.
   const bool half_blocks = s.d == 128 && (long)s.H_q * L.nblk_cap < 1024;
-  if (half_blocks) fwd_kernel<128, 4><<<xcd_grid(s.H_q, 2l * L.nblk_cap), 256, 0, st>>>(a);
+  // 256 channels: half blocks of four waves, one per SIMD with the whole register file (the output
+  // accumulators alone are 128 registers per wave).
+  if (s.d == 256) fwd_kernel<256, 4><<<xcd_grid(s.H_q, 2l * L.nblk_cap), 256, 0, st>>>(a);
+  else if (half_blocks) fwd_kernel<128, 4><<<xcd_grid(s.H_q, 2l * L.nblk_cap), 256, 0, st>>>(a);
   else if (s.d == 128) fwd_kernel<128, 8><<<xcd_grid(s.H_q, L.nblk_cap), 512, 0, st>>>(a);
   else fwd_kernel<64, 8><<<xcd_grid(s.H_q, L.nblk_cap), 512, 0, st>>>(a);
   prof_end(DMA_STAGE_FWD, st);

@@ -8,36 +8,36 @@
 
 namespace dma {
 
-// One workgroup per (64-token tile, kv-head).  (1) every row is held by D / 8 lanes, which reduce
+// One workgroup per (TT-token tile, kv-head); TT = 64, or 32 at 256 channels (the V tile is kept in LDS).  (1) every row is held by D / 8 lanes, which reduce
 // x = w_h . v for each q-head of the group; (2) one thread per (q-head, row) turns x into dx and
 // the dA summand (the transcendental work, 64 different pairs per wave instruction); (3) the row's
 // lanes add dx w_h into their 8 channels of the dV row; (4) dW and dA partial sums of the tile
 // (from dx and the V tile kept in LDS) are added to the outputs with fp32 atomics (G * D + G per
 // workgroup).
-template <typename TV, int D>
+template <typename TV, int D, int TT>
 __global__ __launch_bounds__(256) void mask_bwd_kernel(const TV* __restrict__ V, const float* __restrict__ W,
                                                        const float* __restrict__ A, const float* __restrict__ dz,
                                                        float* dW, float* dA, TV* dV, int accumulate, int T,
                                                        int H_q, int H_kv, int tiles_per_wg) {
-  extern __shared__ float sm[];  // [64][D] V tile, [G][D] w, [G][D] dW partial, [G][64] x then dx, [G][64] dA summands, [G] dA partial
-  constexpr int LPR = D / 8, RPP = 256 / LPR, NP = 64 / RPP;
+  extern __shared__ float sm[];  // [TT][D] V tile, [G][D] w, [G][D] dW partial, [G][TT] x then dx, [G][TT] dA summands, [G] dA partial
+  constexpr int LPR = D / 8, RPP = 256 / LPR, NP = TT / RPP;
   const int g = blockIdx.y, G = H_q / H_kv;
   float* vs = sm;
-  float* ws = vs + 64 * D;
+  float* ws = vs + TT * D;
   float* dws = ws + G * D;
   float* dxs = dws + G * D;
-  float* das = dxs + G * 64;
-  float* dap = das + G * 64;
+  float* das = dxs + G * TT;
+  float* dap = das + G * TT;
   const int tid = threadIdx.x, sub = tid % LPR, rl = tid / LPR;
   for (int i = tid; i < G * D; i += 256) {
     ws[i] = W[(size_t)g * G * D + i];
     dws[i] = 0.f;
   }
   for (int i = tid; i < G; i += 256) dap[i] = 0.f;
-  // a workgroup walks tiles_per_wg consecutive 64-token tiles, so that the contended atomics on dW / dA
+  // a workgroup walks tiles_per_wg consecutive TT-token tiles, so that the contended atomics on dW / dA
   // are issued once per workgroup instead of once per tile
   for (int tile = 0; tile < tiles_per_wg; tile++) {
-  const int t0 = (blockIdx.x * tiles_per_wg + tile) * 64;
+  const int t0 = (blockIdx.x * tiles_per_wg + tile) * TT;
   if (t0 >= T) break;
   __syncthreads();  // the previous tile's readers of vs / dxs / das are done
   float v[NP][8];
@@ -78,13 +78,13 @@ __global__ __launch_bounds__(256) void mask_bwd_kernel(const TV* __restrict__ V,
       for (int e = 0; e < 8; e++) x = fmaf(v[pass][e], w[e], x);
 #pragma unroll
       for (int off = LPR / 2; off > 0; off >>= 1) x += __shfl_xor(x, off);
-      if (sub == 0) dxs[hh * 64 + r] = x;
+      if (sub == 0) dxs[hh * TT + r] = x;
     }
   }
   __syncthreads();
   // (2) dx and the dA summand, one (q-head, row) pair per thread
-  for (int idx = tid; idx < G * 64; idx += 256) {
-    const int hh = idx / 64, r = idx % 64, t = t0 + r, h = g * G + hh;
+  for (int idx = tid; idx < G * TT; idx += 256) {
+    const int hh = idx / TT, r = idx % TT, t = t0 + r, h = g * G + hh;
     float dx = 0.f, da = 0.f;
     if (t < T) {
       const float x = dxs[idx], a = A[h];
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void mask_bwd_kernel(const TV* __restrict__ V,
 #pragma unroll
     for (int e = 0; e < 8; e++) dv[e] = 0.f;
     for (int hh = 0; hh < G; hh++) {
-      const float dx = dxs[hh * 64 + r];
+      const float dx = dxs[hh * TT + r];
       const float* w = ws + hh * D + 8 * sub;
 #pragma unroll
       for (int e = 0; e < 8; e++) dv[e] = fmaf(dx, w[e], dv[e]);
@@ -145,12 +145,12 @@ __global__ __launch_bounds__(256) void mask_bwd_kernel(const TV* __restrict__ V,
     const int hh = idx / D, c = idx % D;
     float s = 0.f;
 #pragma unroll 8
-    for (int r = 0; r < 64; r++) s = fmaf(dxs[hh * 64 + r], vs[r * D + c], s);
+    for (int r = 0; r < TT; r++) s = fmaf(dxs[hh * TT + r], vs[r * D + c], s);
     dws[idx] += s;  // (the same thread owns idx for every tile)
   }
   for (int hh = tid; hh < G; hh += 256) {
     float s = 0.f;
-    for (int r = 0; r < 64; r++) s += das[hh * 64 + r];
+    for (int r = 0; r < TT; r++) s += das[hh * TT + r];
     dap[hh] += s;
   }
   }  // tiles
@@ -164,25 +164,36 @@ __global__ void fill_zero_kernel(float* a, size_t na, float* b, size_t nb) {
   if (i < nb) b[i] = 0.f;
 }
 
+// dynamic LDS of one workgroup; beyond 64 KiB (very many q-heads per kv-head) the shape is refused
+size_t mask_bwd_lds_bytes(const dma_shape& s) {
+  const size_t G = (size_t)(s.H_q / s.H_kv), TT = s.d == 256 ? 32 : 64;
+  return (TT * s.d + 2 * G * s.d + 2 * G * TT + G) * sizeof(float);
+}
+
 int launch_mask_bwd(const dma_shape& s, const void* V, const float* W, const float* A, const float* dz,
                     float* dW, float* dA, void* dV, int accumulate, hipStream_t st) {
-  const int G = s.H_q / s.H_kv;
+  if (mask_bwd_lds_bytes(s) > 64 * 1024) return DMA_EUNSUPPORTED;  // (before the first launch)
   const size_t nw = (size_t)s.H_q * s.d;
   fill_zero_kernel<<<(unsigned)((nw + 255) / 256), 256, 0, st>>>(dW, nw, dA, (size_t)s.H_q);
-  const int ntiles = (s.T + 63) / 64;
+  const int TT = s.d == 256 ? 32 : 64;  // tokens per tile
+  const int ntiles = (s.T + TT - 1) / TT;
   // enough workgroups to fill the chip (about four per CU), as few contended atomics as possible
   int tpw = (int)(((long)ntiles * s.H_kv + 1023) / 1024);
   if (tpw < 1) tpw = 1;
   const dim3 grid((ntiles + tpw - 1) / tpw, s.H_kv);
-  const size_t sh = ((size_t)64 * s.d + 2 * (size_t)G * s.d + 2 * (size_t)G * 64 + G) * sizeof(float);
-  if (sh > 64 * 1024) return DMA_EUNSUPPORTED;  // too many q-heads per kv-head for one tile's LDS
+  const size_t sh = mask_bwd_lds_bytes(s);
+#define DMA_MB(TV, DD, TTT) \
+  mask_bwd_kernel<TV, DD, TTT><<<grid, 256, sh, st>>>((const TV*)V, W, A, dz, dW, dA, (TV*)dV, accumulate, s.T, s.H_q, s.H_kv, tpw)
   if (s.dtype == DMA_BF16) {
-    if (s.d == 128) mask_bwd_kernel<uint16_t, 128><<<grid, 256, sh, st>>>((const uint16_t*)V, W, A, dz, dW, dA, (uint16_t*)dV, accumulate, s.T, s.H_q, s.H_kv, tpw);
-    else mask_bwd_kernel<uint16_t, 64><<<grid, 256, sh, st>>>((const uint16_t*)V, W, A, dz, dW, dA, (uint16_t*)dV, accumulate, s.T, s.H_q, s.H_kv, tpw);
+    if (s.d == 256) DMA_MB(uint16_t, 256, 32);
+    else if (s.d == 128) DMA_MB(uint16_t, 128, 64);
+    else DMA_MB(uint16_t, 64, 64);
   } else {
-    if (s.d == 128) mask_bwd_kernel<float, 128><<<grid, 256, sh, st>>>((const float*)V, W, A, dz, dW, dA, (float*)dV, accumulate, s.T, s.H_q, s.H_kv, tpw);
-    else mask_bwd_kernel<float, 64><<<grid, 256, sh, st>>>((const float*)V, W, A, dz, dW, dA, (float*)dV, accumulate, s.T, s.H_q, s.H_kv, tpw);
+    if (s.d == 256) DMA_MB(float, 256, 32);
+    else if (s.d == 128) DMA_MB(float, 128, 64);
+    else DMA_MB(float, 64, 64);
   }
+#undef DMA_MB
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;
 }
 

@@ -813,10 +813,12 @@ int launch_mask_gen(const Ptrs& p, const void* V, const float* W, const float* A
 #define DMA_Z(TV, DD, GM) \
   z_kernel<TV, DD, GM><<<grid, 256, sh, st>>>((const TV*)V, W, A, z, zq, inv_scale, s.T, s.H_q, s.H_kv)
     if (s.dtype == DMA_BF16) {
-      if (s.d == 128) { if (G <= 4) DMA_Z(uint16_t, 128, 4); else DMA_Z(uint16_t, 128, 8); }
+      if (s.d == 256) { if (G <= 4) DMA_Z(uint16_t, 256, 4); else DMA_Z(uint16_t, 256, 8); }
+      else if (s.d == 128) { if (G <= 4) DMA_Z(uint16_t, 128, 4); else DMA_Z(uint16_t, 128, 8); }
       else { if (G <= 4) DMA_Z(uint16_t, 64, 4); else DMA_Z(uint16_t, 64, 8); }
     } else {
-      if (s.d == 128) { if (G <= 4) DMA_Z(float, 128, 4); else DMA_Z(float, 128, 8); }
+      if (s.d == 256) { if (G <= 4) DMA_Z(float, 256, 4); else DMA_Z(float, 256, 8); }
+      else if (s.d == 128) { if (G <= 4) DMA_Z(float, 128, 4); else DMA_Z(float, 128, 8); }
       else { if (G <= 4) DMA_Z(float, 64, 4); else DMA_Z(float, 64, 8); }
     }
 #undef DMA_Z

@@ -54,6 +54,9 @@ CONFIGS = {
     # varlen packed batch
     "cfg5": Workload("cfg5", 1005, H_q=16, H_kv=16, d=64, k=512, total_tokens=65536,
                      len_lo=512, len_hi=8192),
+    # not one of the benchmark's shapes: the headline length at head dimension 256 with half the
+    # heads (the same algorithmic FLOPs as cfg3), for the wider-head variant of the kernels
+    "cfg3_d256": Workload("cfg3_d256", 1006, H_q=16, H_kv=4, d=256, k=2048, seqlens=(16384,)),
 }
 
 

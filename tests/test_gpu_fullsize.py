@@ -143,6 +143,37 @@ def test_cfg3_headline_shape(gpu):
     assert np.isfinite(case.host("dQ")).all() and np.isfinite(case.host("dK")).all() and np.isfinite(case.host("dV")).all()
 
 
+def test_head_dim_256_at_the_headline_length(gpu):
+    print("[case] cfg3_d256 (16384 tokens, 16 / 4 heads, d = 256, k = 2048): expiry exhaustive; kv-group 0 dense "
+          "forward and backward; sampled keys of the other kv-heads", flush=True)
+    inp = wlmod.make_inputs(wlmod.CONFIGS["cfg3_d256"])
+    wl = inp.wl
+    case = DeviceCase(inp, gpu)
+    case.mask_gen(); case.fwd(); case.bwd()
+    zg, eg = check_expiry_all(case, "cfg3_d256")
+    rng = np.random.default_rng(31)
+    G = wl.H_q // wl.H_kv
+    heads = list(range(G))
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k, heads=heads)
+    print("  O group0", check_close("O", case.host("O")[:, :G], O[:, :G], **T_BF16), flush=True)
+    print("  LSE group0", check_close("LSE", case.host("LSE")[:G], LSE[:G], **T_BF16), flush=True)
+    dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, heads=heads,
+                                      O_stored=case.host("O"))
+    print("  dQ group0", check_close("dQ", case.host("dQ")[:, :G], dQ[:, :G], **T_BF16), flush=True)
+    print("  dK kv-head 0", check_close("dK", case.host("dK")[:, 0], dK[:, 0], **T_BF16), flush=True)
+    print("  dV kv-head 0", check_close("dV", case.host("dV")[:, 0], dV[:, 0], **T_BF16), flush=True)
+    print("  dz group0", check_close("dz", case.host("dz")[:G], dz[:G], **T_BF16), flush=True)
+    rows = sample_rows(rng, inp, [5, 10, 15], 5)
+    check_rows(case, zg, rows, "cfg3_d256", backward=True)
+    for g in range(1, wl.H_kv):
+        hs = list(range(g * G, (g + 1) * G))
+        keys = short_lived_keys(rng, eg, hs, 4, 300, must=(wl.k - 1, wl.k, wl.k + 255, wl.k + 256, inp.T - 2))
+        check_keys_of_group(case, zg, eg, g, keys, "cfg3_d256", T_BF16)
+    dz_g = case.host("dz")
+    assert (dz_g[eg == np.arange(inp.T)[None, :]] == 0.0).all()
+    assert np.isfinite(case.host("dQ")).all() and np.isfinite(case.host("dK")).all() and np.isfinite(case.host("dV")).all()
+
+
 @pytest.mark.parametrize("k", [1024, 4096, 16384, 65536])
 def test_cfg4_long_forward_sampled(gpu, k):
     print(f"[case] cfg4 forward k={k}", flush=True)

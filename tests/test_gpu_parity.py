@@ -33,6 +33,11 @@ SMALL = {
     "more_docs_than_tokens": lambda: wlmod.small_workload("more_docs_than_tokens", 25, 4, 2, 128, 256, (0, 1, 0)),
     "k2_many_blocks": lambda: wlmod.small_workload("k2_many_blocks", 19, 3, 3, 64, 2, (900,)),
     "gqa8_d64": lambda: wlmod.small_workload("gqa8_d64", 20, 8, 1, 64, 70, (520,)),
+    # head dimension 256: ragged documents over several tiles, a window wider than a document, k = 2, GQA
+    "ragged_d256": lambda: wlmod.small_workload("ragged_d256", 26, 4, 2, 256, 100, (333, 70, 0, 129)),
+    "multi_tile_d256": lambda: wlmod.small_workload("multi_tile_d256", 27, 2, 1, 256, 160, (700, 260)),
+    "k2_d256": lambda: wlmod.small_workload("k2_d256", 28, 2, 2, 256, 2, (530,)),
+    "k_ge_len_d256": lambda: wlmod.small_workload("k_ge_len_d256", 29, 4, 1, 256, 512, (150, 290)),
     # 600 short documents (1..12 tokens, a few empty): block table, per-document sorts and plans at scale
     "many_tiny_docs": lambda: wlmod.small_workload(
         "many_tiny_docs", 24, 2, 1, 64, 5, tuple(int(x) for x in np.random.default_rng(24).integers(0, 13, 600))),
@@ -253,14 +258,16 @@ def test_backward_on_reference_forward_results(gpu, name):
     check_gradients(case, zg, "bf16", label="(reference O) ")
 
 
-def random_small_workloads(seed, count):
+def random_small_workloads(seed, count, head_dim=None):
     """Seeded random shapes around the tile edges (rows 31 ... 1100 per document, windows 1 ... 2000,
-    1 - 6 documents including empty ones, G = 1, 2, 4, both head dimensions, causal or not)."""
+    1 - 6 documents including empty ones, G = 1, 2, 4, head dimension 64 or 128 -- or head_dim for
+    all of them --, causal or not)."""
     import random
     rnd = random.Random(seed)
     out = []
     for it in range(count):
         d = rnd.choice([64, 128])
+        d = d if head_dim is None else head_dim
         H_kv = rnd.choice([1, 2, 3])
         G = rnd.choice([1, 2, 4])
         ndocs = rnd.choice([1, 1, 2, 3, 6])
@@ -278,6 +285,16 @@ def random_small_workloads(seed, count):
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_random_small_shapes(gpu, seed):
     for wl, dtype in random_small_workloads(seed, 14):
+        print(f"[shape] H_q={wl.H_q} H_kv={wl.H_kv} d={wl.d} k={wl.k} seqlens={wl.seqlens} causal={wl.causal}", flush=True)
+        if wl.causal:
+            run_mask_gen_and_forward(gpu, wl, dtype)
+            run_backward(gpu, wl, dtype)
+        else:
+            run_noncausal(gpu, wl, dtype)
+
+
+def test_random_small_shapes_head_dim_256(gpu):
+    for wl, dtype in random_small_workloads(4, 12, head_dim=256):
         print(f"[shape] H_q={wl.H_q} H_kv={wl.H_kv} d={wl.d} k={wl.k} seqlens={wl.seqlens} causal={wl.causal}", flush=True)
         if wl.causal:
             run_mask_gen_and_forward(gpu, wl, dtype)
@@ -307,6 +324,8 @@ MASK_BWD_CASES = {
     "tiny": (5, 2, 1, 64),
     "g16_d64": (300, 16, 1, 64),          # more than 8 q-heads per kv-head: the LDS-based kernel
     "many_tiles_d128": (70000, 4, 1, 128),  # several tiles per workgroup
+    "tail_d256": (333, 4, 2, 256),          # 32-token tiles at 256 channels
+    "many_tiles_d256": (40000, 8, 1, 256),
 }
 
 

@@ -32,6 +32,7 @@ CASES = {
     # name: (seed, H_q, H_kv, d, k, seqlens)
     "gqa_d128": (31, 4, 2, 128, 96, (300, 85)),
     "mha_d64": (32, 2, 2, 64, 40, (517,)),
+    "gqa_d256": (33, 4, 2, 256, 70, (290, 130)),
 }
 
 
