@@ -43,7 +43,7 @@ extern "C" {
 typedef enum {
   DMA_OK = 0,
   DMA_EINVAL = -1,       /* null pointer, misaligned pointer, T<=0, k<=0, n_docs<=0, H_q % H_kv != 0 */
-  DMA_EUNSUPPORTED = -2, /* d not in {64,128,256} (256: mask generation, forward, backward and dma_mask_bwd only),
+  DMA_EUNSUPPORTED = -2, /* d not in {64,128,256} (cross-head scores: {64,128}),
                             unknown dtype, more than 256 q-heads per kv-head,
                             more than 32 heads for the cross-head scores,
                             bf16 dma_fwd / dma_bwd with T >= 2^24 or Q (or K, V) larger than 4 GiB         */
@@ -60,7 +60,7 @@ typedef struct {
   int32_t H_q;          /* query heads                                                */
   int32_t H_kv;         /* key/value heads, divides H_q                               */
   int32_t d;            /* head dimension: 64, 128 or 256 (256: not for the cross-head
-                           scores and the decode entry points)                        */
+                           scores)                                                    */
   int32_t k;            /* keep-window (the paper's w): kept keys per query row;
                            k larger than a document keeps all of its causal keys      */
   int32_t causal;       /* 1: candidates of row i are the keys j <= i of its document;

@@ -19,8 +19,7 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// max_d: 256 for the entry points of the training step (mask generation, forward, backward, the score
-// gradient, their size queries and the bias reductions), 128 for the others (cross-head scores, decode).
+// max_d: 256 everywhere except the cross-head scores (128).
 int check_shape(const dma_shape* s, int max_d = 128) {
   if (!s) return DMA_EINVAL;
   if (s->T <= 0 || s->n_docs <= 0 || s->k <= 0 || s->H_q <= 0 || s->H_kv <= 0) return DMA_EINVAL;
@@ -199,13 +198,13 @@ static size_t decode_list_bytes(const dma_shape& s) {
 }
 
 size_t dma_decode_kept_bytes(const dma_shape* shape) {
-  if (check_shape(shape) != DMA_OK) return 0;
+  if (check_shape(shape, 256) != DMA_OK) return 0;
   return decode_list_bytes(*shape) + decode_scratch_bytes(*shape);
 }
 
 int dma_decode(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
                const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, size_t kept_bytes, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!q || !K || !V || !z || !cu_seqlens || !o || !lse) return DMA_EINVAL;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(z) || !aligned16(o) || !aligned16(kept))
@@ -217,13 +216,13 @@ int dma_decode(const dma_shape* shape, const void* q, const void* K, const void*
 }
 
 size_t dma_decode_static_scratch_bytes(const dma_shape* shape) {
-  if (check_shape(shape) != DMA_OK) return 0;
+  if (check_shape(shape, 256) != DMA_OK) return 0;
   return decode_scratch_bytes(*shape);
 }
 
 int dma_decode_static(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
                       const int32_t* cu_seqlens, void* o, float* lse, int32_t* kept, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!q || !K || !V || !z || !cu_seqlens || !o || !lse || !kept) return DMA_EINVAL;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(z) || !aligned16(o) || !aligned16(kept))
@@ -238,7 +237,7 @@ int dma_decode_static(const dma_shape* shape, const void* q, const void* K, cons
 int dma_decode_step(const dma_shape* shape, const void* q, const void* K, const void* V, const float* z,
                     const int32_t* cu_seqlens, const int32_t* seq_lens, int refresh, void* o, float* lse,
                     int32_t* kept, size_t kept_bytes, void* stream) {
-  int rc = check_shape(shape);
+  int rc = check_shape(shape, 256);
   if (rc != DMA_OK) return rc;
   if (!q || !K || !V || !z || !cu_seqlens || !seq_lens || !o || !lse) return DMA_EINVAL;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(z) || !aligned16(o) || !aligned16(kept))
@@ -255,7 +254,7 @@ const char* dma_strerror(int status) {
   switch (status) {
     case DMA_OK: return "ok";
     case DMA_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, H_q % H_kv != 0)";
-    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64, 128 or 256 -- 256 for mask generation, forward and backward only --, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: Q, K, V at most 4 GiB each, fewer than 2^24 tokens)";
+    case DMA_EUNSUPPORTED: return "unsupported configuration (d must be 64, 128 or 256 -- cross-head scores: 64 or 128 --, dtype bf16 or f32; cross-head scores: at most 32 q-heads; bf16 attention: Q, K, V at most 4 GiB each, fewer than 2^24 tokens)";
     case DMA_EWORKSPACE: return "workspace missing or too small (dma_workspace_bytes, dma_decode_kept_bytes), or the shape needs more than the library-owned scratch of dma_decode_static";
     case DMA_EHIP: return "HIP launch failed";
     default: return "unknown status";

@@ -526,10 +526,12 @@ int launch_decode(const dma_shape& s, float scale, const void* q, const void* K,
     decode_write_kernel<<<sgrid, 256, 0, st>>>(ds);
   }
   if (s.dtype == DMA_BF16) {
-    if (s.d == 128) launch_decode_t<__bf16, 128>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
+    if (s.d == 256) launch_decode_t<__bf16, 256>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
+    else if (s.d == 128) launch_decode_t<__bf16, 128>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
     else launch_decode_t<__bf16, 64>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
   } else {
-    if (s.d == 128) launch_decode_t<float, 128>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
+    if (s.d == 256) launch_decode_t<float, 256>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
+    else if (s.d == 128) launch_decode_t<float, 128>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
     else launch_decode_t<float, 64>(s, c2, q, K, V, z, cu, lens, o, lse, kept, part, nsplit, st);
   }
   return hipGetLastError() == hipSuccess ? DMA_OK : DMA_EHIP;

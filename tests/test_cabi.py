@@ -134,16 +134,13 @@ def test_error_codes_before_any_launch(lib):
     with pytest.raises(B.DmaError) as e:
         B.dma_mask_gen(wide, p, p, p, p, p, p, None, p, stream=0)
     assert e.value.status == B.DMA_EUNSUPPORTED
-    # head dimension 256: the training step takes it, cross-head scores and decode do not
+    # head dimension 256: everything but the cross-head scores takes it
     wide_d = B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=256, k=64)
     assert B.dma_mask_bytes(wide_d) > 0 and B.dma_workspace_bytes(wide_d) > 0
     with pytest.raises(B.DmaError) as e:
         B.dma_scores_xhead(wide_d, p, p, p, p, stream=0)
     assert e.value.status == B.DMA_EUNSUPPORTED
-    with pytest.raises(B.DmaError) as e:
-        B.dma_decode(wide_d, p, p, p, p, p, p, p, p, 1 << 30, stream=0)
-    assert e.value.status == B.DMA_EUNSUPPORTED
-    assert B.dma_decode_kept_bytes(wide_d) == 0
+    assert B.dma_decode_kept_bytes(wide_d) >= 2 * 64 * 4
     assert B.dma_decode_kept_bytes(ok) >= 2 * 64 * 4
     assert "workspace" in B.strerror(B.DMA_EWORKSPACE)
     assert B.strerror(0) == "ok"

@@ -534,6 +534,7 @@ DECODE_CASES = {
     "gqa_d128": ((2500, 129), 8, 2, 128, 128, 0),
     "ties": ((900, 400), 2, 2, 64, 100, 5),
     "k_ge_len": ((50, 200), 2, 1, 128, 512, 0),
+    "gqa_d256": ((1300, 0, 257), 4, 2, 256, 96, 0),
 }
 
 
