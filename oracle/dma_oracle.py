@@ -368,7 +368,8 @@ def dma_forward(Q, K, V, z, cu_seqlens, k, causal=True, scale=None, heads=None,
 
 
 def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=None,
-                 mask_method="sequential", row_chunk=1024, abs_out=None, O_stored=None, bias=None):
+                 mask_method="sequential", row_chunk=1024, abs_out=None, O_stored=None, bias=None,
+                 LSE_stored=None):
     """Eq. 7-10 / Alg. 2 result: dQ [T, H_q, d], dK, dV [T, H_kv, d], dz [H_q, T].
 
     bias [H_q, T]: as in dma_forward.  z and the bias enter the score as a sum, so dz is also the
@@ -383,6 +384,13 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     buffer a backward kernel is handed, e.g. the forward result rounded to bf16); without it D_i uses
     the exact O of Eq. 5 (then D_i equals the sum_j p_ij dp_ij of Eq. 8).  dS = P o (dP - D) is linear
     in D, so the two results differ by dD_i = dO_i . (O_stored_i - O_i) entering as -P_ij dD_i.
+
+    LSE_stored [H_q, T]: Alg. 2 does not renormalise either: it loads the forward's row statistics
+    (l_i and m_i, stored here as one LSE_i = m_i + ln l_i) and forms P_ij = exp(S_ij - LSE_i) from them.
+    With LSE_stored given, P is formed that way from the array (e.g. the forward result rounded to
+    fp32); without it P is the exact softmax of Eq. 5.  A stored LSE_i + e_i scales row i of P by
+    exp(-e_i), and with it that row's contributions to every gradient.  (The exact O of the default D_i
+    is always the exact softmax's.)
 
     A dict passed as abs_out receives the magnitudes of the summands of dK and dV,
     "dK": scale * sum_i |dS_ij| |q_ic| and "dV": sum_i P_ij |do_ic|, both [T, H_kv, d] (no part of the
@@ -402,6 +410,7 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
     dK_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
     dV_abs = np.zeros((T, H_kv, d)) if abs_out is not None else None
     O_st = None if O_stored is None else _as64(O_stored)
+    L_st = None if LSE_stored is None else _as64(LSE_stored)
     for h in heads:
         g = h // G
         for a, b in zip(cu[:-1], cu[1:]):
@@ -415,8 +424,11 @@ def dma_backward(Q, K, V, z, dO, cu_seqlens, k, causal=True, scale=None, heads=N
             for r0 in range(0, n, row_chunk):
                 r1 = min(n, r0 + row_chunk)
                 S = scale * (q[r0:r1] @ kk.T) + sb[None, :]
-                P, _ = _softmax_rows(S, prov(r0, r1))
+                keep = prov(r0, r1)
+                P, _ = _softmax_rows(S, keep)
                 o = P @ v
+                if L_st is not None:                                # Alg. 2 loads l_i, m_i from memory
+                    P = np.where(keep, np.exp(np.where(keep, S, -np.inf) - L_st[h, a + r0:a + r1, None]), 0.0)
                 if O_st is not None:
                     o = O_st[a + r0:a + r1, h]                      # Alg. 2 loads O_i from memory
                 D = (do[r0:r1] * o).sum(axis=1, keepdims=True)      # Alg. 2: D_i

@@ -394,6 +394,55 @@ def test_stored_o_rounded_shifts_the_gradients_by_the_closed_form():
             assert val == pytest.approx(dz1[h, j], abs=1e-12)
 
 
+def test_stored_lse_equal_to_exact_lse_changes_nothing():
+    """Alg. 2 forms P_ij = exp(S_ij - LSE_i) from the stored row statistics; with the exact LSE that is
+    the softmax of Eq. 5, so the LSE_stored mode must reproduce the default (a head / row index slip
+    into LSE_stored, or P exponentiated off the kept set, fails here).  Two documents, ties, non-causal too."""
+    n1, n2, k = 21, 33, 6
+    Q, K, V, dO, z = rand_case(n1 + n2, 4, 2, 8, seed=53, ties=True)
+    cu = [0, n1, n1 + n2]
+    for causal in (True, False):
+        _, LSE = orc.dma_forward(Q, K, V, z, cu, k, causal=causal)
+        a = orc.dma_backward(Q, K, V, z, dO, cu, k, causal=causal)
+        b = orc.dma_backward(Q, K, V, z, dO, cu, k, causal=causal, LSE_stored=LSE, row_chunk=5)
+        for x, y in zip(a, b):
+            assert np.allclose(x, y, atol=1e-13)
+
+
+def test_stored_lse_off_by_e_scales_the_rows_by_exp_minus_e():
+    """With a stored LSE_i + e_i every P_ij of row i is exp(-e_i) times the softmax weight, D_i (from
+    the exact O) is unchanged, and the four gradients follow from Eq. 7-10 term by term.  Written out
+    with explicit loops over (head, row, kept key) from the exact LSE; together with a stored O
+    (both buffers at once, as a backward kernel gets them)."""
+    n, H_q, H_kv, d, k = 24, 4, 2, 8, 5
+    G = H_q // H_kv
+    scale = 1.0 / math.sqrt(d)
+    Q, K, V, dO, z = rand_case(n, H_q, H_kv, d, seed=54)
+    cu = [0, n]
+    O, LSE = orc.dma_forward(Q, K, V, z, cu, k)
+    e = 0.03 * np.random.default_rng(55).standard_normal((H_q, n))
+    Or = _bf16_round(O)
+    for O_used, kw in ((O, {}), (Or, {"O_stored": Or})):
+        dQ1, dK1, dV1, dz1 = orc.dma_backward(Q, K, V, z, dO, cu, k, LSE_stored=LSE + e, **kw)
+        rQ, rK, rV, rz = np.zeros_like(dQ1), np.zeros_like(dK1), np.zeros_like(dV1), np.zeros_like(dz1)
+        for h in range(H_q):
+            g = h // G
+            keep = orc.kept_mask_definition(z[h], k)
+            for i in range(n):
+                D = float(dO[i, h] @ O_used[i, h])
+                for j in np.flatnonzero(keep[i]):
+                    p = math.exp(scale * float(Q[i, h] @ K[j, g]) + z[h, j] - (LSE[h, i] + e[h, i]))
+                    ds = p * (float(dO[i, h] @ V[j, g]) - D)
+                    rV[j, g] += p * dO[i, h]
+                    rz[h, j] += ds
+                    rQ[i, h] += scale * ds * K[j, g]
+                    rK[j, g] += scale * ds * Q[i, h]
+        assert np.allclose(dQ1, rQ, atol=1e-13) and np.allclose(dK1, rK, atol=1e-13)
+        assert np.allclose(dV1, rV, atol=1e-13) and np.allclose(dz1, rz, atol=1e-13)
+    dV0 = orc.dma_backward(Q, K, V, z, dO, cu, k)[2]
+    assert np.abs(dV1 - dV0).max() > 1e-3                   # the offset is visible
+
+
 def test_summand_masses_of_dk_and_dv_match_triple_loops():
     """abs_out["dK"] = scale sum_i |dS_ij| |q_ic| and abs_out["dV"] = sum_i P_ij |dO_ic| (summed over
     the q-heads of the kv-head): the yardsticks a test may add to the tolerance of dK / dV for keep
