@@ -1,8 +1,9 @@
 """Tolerances of the GPU parity tests.
 
 bf16 path: element-wise |gpu - ref| <= 2e-2 + 1e-2 |ref| and ||gpu - ref||_F <= 1e-2 ||ref||_F.
-fp32 debug path: the same form with 1e-5.  check_close enforces exactly that unless a caller passes
-max_beyond > 0 together with a summand mass (degenerate windows k <= 3 only, see BF16_SUM_SREL).
+fp32 debug path: the same form with 1e-5, no exception.  check_close enforces exactly that unless a
+caller passes max_beyond > 0 together with a summand mass (bf16, degenerate windows k <= 3 only, see
+BF16_SUM_SREL).
 """
 from __future__ import annotations
 
@@ -50,13 +51,14 @@ def check_close(name, got, ref, atol, rtol, frob, summand_abs=None, srel=0.0, ma
 # enter the matrix cores rounded to bf16 (relative error up to 2^-9 each, whatever the size of the
 # sum after cancellation).  There, and only there, a few elements of dK / dV (degenerate_sum_allowance)
 # may exceed the plain bound, while staying within + BF16_SUM_SREL * sum_i |term| (the oracle's abs_out).
+# How many: without the causal restriction a window of two keys leaves two to four non-zero rows per
+# document and kv-head, each element a sum over every row of the document; rounding P alone to bf16 in
+# an otherwise exact fp64 computation puts 42 of 1536 such elements (2.7 %) beyond the plain bound for
+# documents of 1100 + 300 rows, and the kernels land on the same elements -- hence 5 %.
 BF16_SUM_SREL = 5e-3
-# fp32 debug path, same windows: LSE is stored in fp32, so every recomputed weight exp(S - LSE) is off by up to
-# 6e-8 |LSE| relative (with one kept key per row: P = 1 +- 5e-7), and a key sums thousands of such terms.
-F32_SUM_SREL = 1e-6
 BF16_SUM_MAX_BEYOND = 16          # elements, or BF16_SUM_FRAC_BEYOND of the non-zero reference elements if more
-BF16_SUM_FRAC_BEYOND = 0.02       # (without the causal restriction a window of three keys leaves 3 non-zero rows
-DEGENERATE_K = 3                  #  per document and head, each a sum over every row of the document)
+BF16_SUM_FRAC_BEYOND = 0.05
+DEGENERATE_K = 3
 
 
 def degenerate_sum_allowance(ref):

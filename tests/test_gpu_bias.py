@@ -50,7 +50,7 @@ def test_bias_forward_backward(gpu, form, dtype):
     print("  O", check_close("O", case.host("O"), O, **t), flush=True)
     print("  LSE", check_close("LSE", case.host("LSE"), LSE, **t), flush=True)
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, bias=bias,
-                                      O_stored=case.host("O") if dtype == "bf16" else None)
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
     for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, **t), flush=True)
     dbias = torch.full((Hb, n_cols), float("nan"), device=gpu)

@@ -66,7 +66,7 @@ def test_cfg2_all_heads_dense(gpu):
     print("  O", check_close("O", case.host("O"), O, **T_BF16), flush=True)
     print("  LSE", check_close("LSE", case.host("LSE"), LSE, **T_BF16), flush=True)
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, inp.wl.k,
-                                      O_stored=case.host("O"))
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
     for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, **T_BF16), flush=True)
 
@@ -124,7 +124,7 @@ def test_cfg3_headline_shape(gpu):
     print("  O group0", check_close("O", case.host("O")[:, :G], O[:, :G], **T_BF16), flush=True)
     print("  LSE group0", check_close("LSE", case.host("LSE")[:G], LSE[:G], **T_BF16), flush=True)
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, heads=heads,
-                                      O_stored=case.host("O"))
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
     print("  dQ group0", check_close("dQ", case.host("dQ")[:, :G], dQ[:, :G], **T_BF16), flush=True)
     print("  dK kv-head 0", check_close("dK", case.host("dK")[:, 0], dK[:, 0], **T_BF16), flush=True)
     print("  dV kv-head 0", check_close("dV", case.host("dV")[:, 0], dV[:, 0], **T_BF16), flush=True)
@@ -158,7 +158,7 @@ def test_head_dim_256_at_the_headline_length(gpu):
     print("  O group0", check_close("O", case.host("O")[:, :G], O[:, :G], **T_BF16), flush=True)
     print("  LSE group0", check_close("LSE", case.host("LSE")[:G], LSE[:G], **T_BF16), flush=True)
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, heads=heads,
-                                      O_stored=case.host("O"))
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
     print("  dQ group0", check_close("dQ", case.host("dQ")[:, :G], dQ[:, :G], **T_BF16), flush=True)
     print("  dK kv-head 0", check_close("dK", case.host("dK")[:, 0], dK[:, 0], **T_BF16), flush=True)
     print("  dV kv-head 0", check_close("dV", case.host("dV")[:, 0], dV[:, 0], **T_BF16), flush=True)
@@ -213,7 +213,7 @@ def test_cfg5_varlen(gpu):
     zg, eg = check_expiry_all(case, "cfg5")
     O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k, heads=[0])
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, heads=[0],
-                                      O_stored=case.host("O"))
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
     print("  O", check_close("O", case.host("O")[:, 0], O[:, 0], **T_BF16), flush=True)
     print("  LSE", check_close("LSE", case.host("LSE")[0], LSE[0], **T_BF16), flush=True)
     print("  dQ", check_close("dQ", case.host("dQ")[:, 0], dQ[:, 0], **T_BF16), flush=True)
@@ -292,7 +292,7 @@ def test_noncausal_cfg2_shape_dense(gpu):
     print("  O", check_close("O", case.host("O"), O, **T_BF16), flush=True)
     print("  LSE", check_close("LSE", case.host("LSE"), LSE, **T_BF16), flush=True)
     dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, causal=False,
-                                      O_stored=case.host("O"))
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
     for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
         print(f"  {nm}", check_close(nm, case.host(nm), ref, **T_BF16), flush=True)
 
