@@ -179,7 +179,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 || D == 256) ? 1 : 2) void dq_ker
   float lse2 = qvalid ? p.LSE[(size_t)h * p.T + qi] * LOG2E : INFINITY;
   settle(lse2);
   if (qvalid && hh == 0) {
-    p.Dws[(size_t)h * p.T + qi] = Dsum;
+    p.Dws[(size_t)h * p.T + qi] = -Dsum;  // (negated: the key-stationary kernel starts its dP accumulators at -D_i)
     p.L2ws[(size_t)h * p.T + qi] = lse2;
   }
   // fragment addresses with the ring bases folded in: inside the stage-unrolled main loop every LDS
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
   constexpr int STC = 32 / NCH;           // columns staged at a time
   __shared__ __align__(16) uint16_t ringQ[NS * STILE];
   __shared__ __align__(16) uint16_t ringdO[NS * STILE];
-  __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) D
+  __shared__ __align__(16) float meta[NS][64];   // per stage: [0,32) LSE * log2 e, [32,64) -D
   __shared__ __align__(16) int idbuf[2][SG];     // column ids of the current / next block
   __shared__ __align__(16) int4 binfo[MAXSWEEP + 1];  // block table of this work item's sweep
   __shared__ __align__(16) float stage_all[8 * STC * LDS_ST];  // per wave: [STC columns][32 channels] fp32, flush staging
@@ -581,18 +581,15 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     // its dK^T MFMAs while role 0 computes P.
     if (role == 1 && pend) {
       const int st = pstep % NS;
-      const float* Dss = meta[st] + 32;
       const f32x4* ph = &pbuf[pstep & 1][kb4][0][l];  // row group gq at ph[64 * gq]
       bf16x8 bb[2];
 #pragma unroll
       for (int gq = 0; gq < 4; gq++) {
-        const int r = 8 * gq + 4 * hh;
-        const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[r]);
         const f32x4 pq = ph[64 * gq];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
           const int vv = 4 * gq + u;
-          const float ds = pq[u] * (sacc[vv] - dd[u]);
+          const float ds = pq[u] * sacc[vv];  // sacc = dP - D (the accumulator started at -D_i)
           dzacc += ds;
           bb[vv >> 3][vv & 7] = (__bf16)ds;
         }
@@ -668,9 +665,14 @@ __global__ __launch_bounds__(512, 1) void dkv_kernel(BwdArgs p) {
     if (role == 0) {  // S starts at z / scale, so that scale * S is the biased score
 #pragma unroll
       for (int vv = 0; vv < 16; vv++) sacc[vv] = zq;
-    } else {
+    } else {  // dP starts at -D_i of the accumulator's rows: the products then leave dP - D, what dS needs
+      const float* Dss = meta[st] + 32;
 #pragma unroll
-      for (int vv = 0; vv < 16; vv++) sacc[vv] = 0.f;  // (a constant accumulator operand, no moves)
+      for (int gq = 0; gq < 4; gq++) {
+        const f32x4 dd = *reinterpret_cast<const f32x4*>(&Dss[8 * gq + 4 * hh]);
+#pragma unroll
+        for (int u = 0; u < 4; u++) sacc[4 * gq + u] = dd[u];
+      }
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
