@@ -48,7 +48,7 @@ struct BwdArgs {
 // NW waves per workgroup: 8 (a whole 256-row block, four ring stages) or 4 (half a block, two ring
 // stages, two workgroups per compute unit), as in the forward kernel.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, (NW == 8 || D == 256) ? 1 : 2) void dq_kernel(BwdArgs p) {
+__global__ __launch_bounds__(NW * 64, (NW == 8 || D == 256) ? 1 : (D == 64 ? 3 : 2)) void dq_kernel(BwdArgs p) {
   using TL = TileLayout<D>;
   constexpr int KS = D / 16, CB = D / 32, CPR = D / 8, RPL = 64 / CPR, WL = KT / RPL / NW;
   constexpr int NS = NW == 8 ? 4 : 2, TILE = KT * D, NT = NW * 64, HALVES = 8 / NW;
@@ -771,7 +771,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   prof_begin(DMA_STAGE_BWD_ZERO, st);  // (an empty stage: dq_kernel clears the accumulators)
   prof_end(DMA_STAGE_BWD_ZERO, st);
   // (at 256 channels the query-stationary kernels run as half blocks: four waves with the whole register file each)
-  const unsigned gq = s.d == 256 ? xcd_grid(s.H_q, 2l * L.nblk_cap) : xcd_grid(s.H_q, L.nblk_cap);
+  const unsigned gq = s.d != 128 ? xcd_grid(s.H_q, 2l * L.nblk_cap) : xcd_grid(s.H_q, L.nblk_cap);
   a.grid_dq = gq;
   const unsigned gclean = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg - 1) / a.seg) * (L.kpad / SG));
   const unsigned gpart = xcd_grid(s.H_q, (long)((L.nblk_cap + a.seg_part - 1) / a.seg_part) * (MAXPART / SG));
@@ -779,7 +779,7 @@ int launch_bwd(const Ptrs& p, const void* Q, const void* K, const void* V, const
   // (the half-block variant, NW = 4, measured the same or slower at every benchmark shape)
   if (s.d == 256) dq_kernel<256, 4><<<gq, 256, 0, st>>>(a);
   else if (s.d == 128) dq_kernel<128, 8><<<gq, 512, 0, st>>>(a);
-  else dq_kernel<64, 8><<<gq, 512, 0, st>>>(a);
+  else dq_kernel<64, 4><<<gq, 256, 0, st>>>(a);  // half blocks, three workgroups per compute unit (three waves per SIMD)
   prof_end(DMA_STAGE_BWD_DQ, st);
   prof_begin(DMA_STAGE_BWD_DKV, st);
   if (s.d == 256) dkv_kernel<256, false><<<gclean, 512, 0, st>>>(a);
