@@ -188,6 +188,9 @@ int dma_bwd(const dma_shape* shape, const void* Q, const void* K, const void* V,
  *       to the existing contents (e.g. the dV of dma_bwd; one rounding of the sum) otherwise.
  * z is recomputed from V, W, A.  dW and dA are accumulated with floating-point atomics.  No
  * workspace; shape->k, n_docs and softmax_scale are not used.  Errors as for the other entry points.
+ * Shapes whose group (H_q / H_kv q-heads per kv-head) does not fit the kernel's 64 KiB of LDS --
+ * (tile * d + 2 G d + 2 G tile + G) floats with tile = 64 tokens (32 at d = 256), i.e. more than 47 / 21 / 14 q-heads per kv-head at d = 64 / 128 / 256 --
+ * are refused with DMA_EUNSUPPORTED before any launch.
  */
 int dma_mask_bwd(const dma_shape* shape, const void* V, const float* W, const float* A, const float* dz,
                  float* dW, float* dA, void* dV, int accumulate, void* stream);

@@ -134,6 +134,12 @@ def test_error_codes_before_any_launch(lib):
     with pytest.raises(B.DmaError) as e:
         B.dma_mask_gen(wide, p, p, p, p, p, p, None, p, stream=0)
     assert e.value.status == B.DMA_EUNSUPPORTED
+    # the score-gradient kernel keeps a token tile and the group's vectors in LDS: a group too large for it
+    # is refused before the first launch
+    big_group = B.make_shape(T=256, n_docs=1, H_q=64, H_kv=1, d=128, k=64)
+    with pytest.raises(B.DmaError) as e:
+        B.dma_mask_bwd(big_group, p, p, p, p, p, p, p, 0, stream=0)
+    assert e.value.status == B.DMA_EUNSUPPORTED
     # head dimension 256: everything but the cross-head scores takes it
     wide_d = B.make_shape(T=256, n_docs=1, H_q=2, H_kv=2, d=256, k=64)
     assert B.dma_mask_bytes(wide_d) > 0 and B.dma_workspace_bytes(wide_d) > 0
