@@ -102,3 +102,32 @@ def test_bias_through_autograd(gpu):
     t32 = dict(atol=1e-4, rtol=1e-4, frob=1e-4)      # (selection on the device's fp32 scores: no near-ties at this size)
     print("  O", check_close("O", O.detach().cpu().numpy(), rO, **t32), flush=True)
     print("  dbias", check_close("dbias", bias.grad.cpu().numpy(), rdb, **t32), flush=True)
+
+
+def test_bias_at_the_cfg2_shape_dense(gpu):
+    """The batch- and head-broadcast form (one bias row indexed by the position in the document) at
+    2 x 4096 tokens, 16 / 4 heads, k = 1024: forward and backward dense against the oracle, and the
+    bias gradient reduced over all heads and both documents."""
+    print("[case] attention bias, head and batch broadcast, cfg2 shape dense", flush=True)
+    inp = wlmod.make_inputs(wlmod.CONFIGS["cfg2"])
+    wl = inp.wl
+    braw = (0.5 * np.random.default_rng(73).standard_normal((1, inp.max_seqlen))).astype(np.float32)
+    case = DeviceCase(inp, gpu)
+    B.dma_mask_gen_bias(case.shape, case.V, case.W, case.A, case.cu, to_dev(braw, gpu), 1, False, case.z, case.expiry,
+                        None, case.mask)
+    case.fwd()
+    case.bwd()
+    zg = case.host("z").astype(np.float64)
+    bias = orc.expand_bias(braw, wl.H_q, inp.cu_seqlens, False)
+    t = tol(True)
+    O, LSE = orc.dma_forward(inp.Q, inp.K, inp.V, zg, inp.cu_seqlens, wl.k, bias=bias)
+    print("  O", check_close("O", case.host("O"), O, **t), flush=True)
+    print("  LSE", check_close("LSE", case.host("LSE"), LSE, **t), flush=True)
+    dQ, dK, dV, dz = orc.dma_backward(inp.Q, inp.K, inp.V, zg, inp.dO, inp.cu_seqlens, wl.k, bias=bias,
+                                      O_stored=case.host("O"), LSE_stored=case.host("LSE"))
+    for nm, ref in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dz", dz)):
+        print(f"  {nm}", check_close(nm, case.host(nm), ref, **t), flush=True)
+    dbias = torch.full((1, inp.max_seqlen), float("nan"), device=gpu)
+    B.dma_bias_bwd(case.shape, case.dz, case.cu, 1, False, dbias)
+    ref_db = orc.bias_backward(dz, 1, inp.cu_seqlens, False, n_max=inp.max_seqlen)
+    print("  dbias", check_close("dbias", dbias.cpu().numpy(), ref_db, **t), flush=True)
